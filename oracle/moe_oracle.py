@@ -1,0 +1,350 @@
+"""CPU oracle for the padding-free MoE layer (X-MoE, arXiv 2508.13337).
+
+TEST INFRASTRUCTURE ONLY.  Only tests/, __graft_entry__.smoke() and the cpu_baseline leg of bench.py may
+import this package.  It shares no code with the HIP library and never calls it.
+
+Everything is written the slow, obvious way in float64 numpy, one step after the other in the order of the
+paper's Listing 1 ("Padding-free MoE-layer": gating -> PFT_construction -> dispatch -> mlp -> combine) with the
+notation of Section 4.1.1 (token_ids, expert_ids, tokens_per_expert, combine_weights = the ERI-arrays of a PFT).
+numpy's matmul and stable argsort serve as library primitives; nothing is blocked, fused or reordered.
+
+Readings of the paper that this oracle fixes (the paper is silent or garbled on each):
+  * top_experts / combine_weights are [T, k] (Appendix B.3), not [S, E] as the listing's docstring says.
+  * combine weights are the raw softmax-over-E probabilities of the selected experts, not renormalised.
+  * top-k is taken on the logits (softmax is monotone), ties go to the lower expert index, slot j holds the
+    j-th largest.
+  * the sort of the flattened expert ids is stable, so rows of one expert stay in ascending token order.
+  * token_ids holds the token index n // k of flat entry n (Section 4.1.1's "ti-th input token").
+  * the hot path is dropless (max_token_count >= T): B = T*k and the ERI-arrays are a permutation.
+  * the scatter of Section 4.1.2 / Appendix B.4 accumulates: out[token_ids[i]] += combine_weights[i]*Y[i].
+  * expert i's segment is rows [sum(tpe[:i]), sum(tpe[:i+1])) (Appendix B.4 prints an off-by-one).
+  * the expert is a SwiGLU FFN, Y = (silu(X Wg) * (X Wu)) Wd, no biases (the benchmark definition binds this;
+    the paper's own expert is a two-matrix MLP).
+  * a shared expert is one more SwiGLU expert applied to every token with weight 1, outside the gate.
+  * the gate projection is evaluated in float32 in a fixed order (oracle/gate_order.c) so that routing is
+    reproducible bit for bit; an all-float64 mode exists for finite-difference checks.
+  * backward is not described in the paper beyond mirroring the forward; it is derived here by calculus with
+    the top-k indices held constant.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_gate_lib = None
+
+
+def _load_gate_lib():
+    global _gate_lib
+    if _gate_lib is None:
+        lib = ctypes.CDLL(_build.build())
+        lib.xmoe_oracle_gate_logits_f32.restype = None
+        lib.xmoe_oracle_gate_logits_f32.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 3
+        _gate_lib = lib
+    return _gate_lib
+
+
+# ----------------------------------------------------------------------------------------------------------
+# gating (Listing 1, gating(); Appendix B.3 "Padding-free Gating")
+# ----------------------------------------------------------------------------------------------------------
+def gate_logits_contract(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray]) -> np.ndarray:
+    """logits[t,e] = sum_i x[t,i] Wr[i,e] (+ bias[e]) in float32, in the fixed order of gate_order.c."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    w32 = np.ascontiguousarray(w_router, dtype=np.float32)
+    T, d = x32.shape
+    E = w32.shape[1]
+    assert w32.shape[0] == d
+    out = np.empty((T, E), dtype=np.float32)
+    b32 = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    _load_gate_lib().xmoe_oracle_gate_logits_f32(
+        x32.ctypes.data, w32.ctypes.data, None if b32 is None else b32.ctypes.data, out.ctypes.data, T, d, E)
+    return out
+
+
+def gate_logits_f64(x, w_router, bias) -> np.ndarray:
+    """The same projection in float64 (for finite differences, where float32 rounding would drown the step)."""
+    l = np.asarray(x, np.float64) @ np.asarray(w_router, np.float64)
+    if bias is not None:
+        l = l + np.asarray(bias, np.float64)[None, :]
+    return l
+
+
+def softmax(logits: np.ndarray) -> np.ndarray:
+    """Row softmax over the E experts (Listing 1: softmax(FFN(tokens), axis=-1))."""
+    l = np.asarray(logits, np.float64)
+    z = l - l.max(axis=1, keepdims=True)
+    ez = np.exp(z)
+    return ez / ez.sum(axis=1, keepdims=True)
+
+
+def route(logits: np.ndarray, k: int):
+    """Top-k gate routing.  Returns (topk_idx [T,k] int32, topk_w [T,k] float64, p [T,E] float64).
+
+    k times: pick the not yet picked expert with the largest logit, lowest index on ties."""
+    l = np.array(logits, copy=True)
+    T, E = l.shape
+    assert 1 <= k <= E
+    p = softmax(logits)
+    idx = np.empty((T, k), dtype=np.int32)
+    taken = np.zeros((T, E), dtype=bool)
+    rows = np.arange(T)
+    for j in range(k):
+        masked = np.where(taken, -np.inf, l)
+        pick = np.argmax(masked, axis=1)          # numpy returns the first (lowest-index) maximum
+        idx[:, j] = pick
+        taken[rows, pick] = True
+    w = p[rows[:, None], idx]
+    return idx, w, p
+
+
+# ----------------------------------------------------------------------------------------------------------
+# PFT construction (Listing 1, PFT_construction(), step 1 and the histogram; dropless)
+# ----------------------------------------------------------------------------------------------------------
+def build_eri(topk_idx: np.ndarray, topk_w: np.ndarray, E: int) -> dict:
+    """ERI-arrays of the PFT (Section 4.1.1) for B = T*k rows.
+
+    flat entry n = t*k + j; rows are the flat entries stably sorted by expert id."""
+    T, k = topk_idx.shape
+    flat_e = topk_idx.reshape(-1).astype(np.int64)
+    order = np.argsort(flat_e, kind="stable")           # row i holds flat entry order[i]
+    token_ids = (order // k).astype(np.int32)
+    expert_ids = flat_e[order].astype(np.int32)
+    combine_weights = np.asarray(topk_w).reshape(-1)[order]
+    row_of_slot = np.empty(T * k, dtype=np.int32)
+    row_of_slot[order] = np.arange(T * k, dtype=np.int32)
+    tokens_per_expert = np.bincount(expert_ids, minlength=E).astype(np.int32)
+    expert_offsets = np.zeros(E + 1, dtype=np.int32)
+    expert_offsets[1:] = np.cumsum(tokens_per_expert)
+    return {
+        "token_ids": token_ids, "expert_ids": expert_ids, "tokens_per_expert": tokens_per_expert,
+        "expert_offsets": expert_offsets, "combine_weights": combine_weights, "row_of_slot": row_of_slot,
+    }
+
+
+# ----------------------------------------------------------------------------------------------------------
+# dispatch / mlp / combine (Listing 1; Section 4.1.2; Appendix B.4)
+# ----------------------------------------------------------------------------------------------------------
+def dispatch(x: np.ndarray, token_ids: np.ndarray) -> np.ndarray:
+    """Gather kernel: dispatch_in[i,:] = gate_out[token_ids[i],:]."""
+    return np.asarray(x)[token_ids]
+
+
+def silu(g):
+    return g / (1.0 + np.exp(-g))
+
+
+def swiglu_ffn(X, wg, wu, wd):
+    """One expert on its rows: Y = (silu(X Wg) * (X Wu)) Wd.  Returns (Y, G, U)."""
+    G = X @ wg
+    U = X @ wu
+    A = silu(G) * U
+    return A @ wd, G, U
+
+
+def expert_ffn_fwd(Xd, expert_offsets, wg, wu, wd):
+    """Sequential GeMM over the ragged segments: expert e multiplies rows [off[e], off[e+1])."""
+    Xd = np.asarray(Xd, np.float64)
+    B = Xd.shape[0]
+    E, d, f = wg.shape
+    Y = np.zeros((B, d))
+    G = np.zeros((B, f))
+    U = np.zeros((B, f))
+    for e in range(E):
+        lo, hi = int(expert_offsets[e]), int(expert_offsets[e + 1])
+        if hi == lo:
+            continue
+        Y[lo:hi], G[lo:hi], U[lo:hi] = swiglu_ffn(Xd[lo:hi], np.asarray(wg[e], np.float64),
+                                                  np.asarray(wu[e], np.float64), np.asarray(wd[e], np.float64))
+    return Y, G, U
+
+
+def combine(Y, token_ids, combine_weights, T):
+    """Scatter kernel, accumulating: out[token_ids[i],:] += combine_weights[i] * Y[i,:]."""
+    out = np.zeros((T, Y.shape[1]))
+    for i in range(Y.shape[0]):
+        out[token_ids[i]] += combine_weights[i] * Y[i]
+    return out
+
+
+def shared_ffn_fwd(x, swg, swu, swd):
+    """Sum over shared experts of FFN_s(x[t]) for every token (weight 1)."""
+    x = np.asarray(x, np.float64)
+    out = np.zeros_like(x)
+    G, U = [], []
+    for s in range(swg.shape[0]):
+        y, g, u = swiglu_ffn(x, np.asarray(swg[s], np.float64), np.asarray(swu[s], np.float64),
+                             np.asarray(swd[s], np.float64))
+        out += y
+        G.append(g)
+        U.append(u)
+    return out, G, U
+
+
+# ----------------------------------------------------------------------------------------------------------
+# whole layer
+# ----------------------------------------------------------------------------------------------------------
+def moe_layer_fwd(inp: dict, k: int, logits_mode: str = "contract") -> dict:
+    """Listing 1's call(): gating -> PFT_construction -> dispatch -> mlp -> combine (+ shared experts).
+
+    inp: x [T,d], w_router [d,E], bias [E]|None, wg/wu [E,d,f], wd [E,f,d], shared_wg/wu/wd [E_s,...]."""
+    x = np.asarray(inp["x"], np.float64)
+    T = x.shape[0]
+    E = inp["wg"].shape[0]
+    if logits_mode == "contract":
+        logits = gate_logits_contract(inp["x"], inp["w_router"], inp.get("bias"))
+    else:
+        logits = gate_logits_f64(inp["x"], inp["w_router"], inp.get("bias"))
+    topk_idx, topk_w, p = route(logits, k)
+    eri = build_eri(topk_idx, topk_w, E)
+    Xd = dispatch(x, eri["token_ids"])
+    Y, G, U = expert_ffn_fwd(Xd, eri["expert_offsets"], inp["wg"], inp["wu"], inp["wd"])
+    out = combine(Y, eri["token_ids"], eri["combine_weights"], T)
+    res = {"logits": logits, "p": p, "topk_idx": topk_idx, "topk_w": topk_w, "eri": eri,
+           "Xd": Xd, "Y": Y, "G": G, "U": U, "out_routed": out}
+    sh = inp.get("shared_wg")
+    if sh is not None and sh.shape[0] > 0:
+        so, sG, sU = shared_ffn_fwd(x, inp["shared_wg"], inp["shared_wu"], inp["shared_wd"])
+        res["shared_out"], res["shared_G"], res["shared_U"] = so, sG, sU
+        out = out + so
+    res["out"] = out
+    return res
+
+
+def moe_dense_definition(inp: dict, k: int, logits: np.ndarray) -> np.ndarray:
+    """The layer's plain definition with no ERI-arrays at all:
+    out[t] = sum_e [e in TopK(t)] p[t,e] FFN_e(x[t]) + sum_s FFN_s(x[t]), looping over every (t, e)."""
+    x = np.asarray(inp["x"], np.float64)
+    T, d = x.shape
+    E = inp["wg"].shape[0]
+    p = softmax(logits)
+    out = np.zeros((T, d))
+    for t in range(T):
+        # the k largest logits, lower index first among equals
+        chosen = sorted(range(E), key=lambda e: (-float(logits[t, e]), e))[:k]
+        for e in range(E):
+            if e in chosen:
+                y, _, _ = swiglu_ffn(x[t:t + 1], np.asarray(inp["wg"][e], np.float64),
+                                     np.asarray(inp["wu"][e], np.float64), np.asarray(inp["wd"][e], np.float64))
+                out[t] += p[t, e] * y[0]
+        sh = inp.get("shared_wg")
+        if sh is not None:
+            for s in range(sh.shape[0]):
+                y, _, _ = swiglu_ffn(x[t:t + 1], np.asarray(inp["shared_wg"][s], np.float64),
+                                     np.asarray(inp["shared_wu"][s], np.float64),
+                                     np.asarray(inp["shared_wd"][s], np.float64))
+                out[t] += y[0]
+    return out
+
+
+# ----------------------------------------------------------------------------------------------------------
+# backward (derived: the paper only says it mirrors the forward, Section 4.3)
+# ----------------------------------------------------------------------------------------------------------
+def combine_bwd(dout, Y, token_ids, combine_weights, row_of_slot, k):
+    """dY[i] = combine_weights[i] * dOut[token_ids[i]];  dw[t,j] = <dOut[t], Y[row_of_slot[t*k+j]]>."""
+    dout = np.asarray(dout, np.float64)
+    T = dout.shape[0]
+    dY = combine_weights[:, None] * dout[token_ids]
+    dw = np.zeros((T, k))
+    for t in range(T):
+        for j in range(k):
+            dw[t, j] = np.dot(dout[t], Y[row_of_slot[t * k + j]])
+    return dY, dw
+
+
+def swiglu_ffn_bwd(X, G, U, dY, wg, wu, wd):
+    """Backward of one expert.  Returns dX, dWg, dWu, dWd."""
+    sig = 1.0 / (1.0 + np.exp(-G))
+    S = G * sig
+    A = S * U
+    dA = dY @ wd.T
+    dWd = A.T @ dY
+    dG = dA * U * (sig * (1.0 + G * (1.0 - sig)))
+    dU = dA * S
+    dX = dG @ wg.T + dU @ wu.T
+    dWg = X.T @ dG
+    dWu = X.T @ dU
+    return dX, dWg, dWu, dWd
+
+
+def expert_ffn_bwd(Xd, G, U, dY, expert_offsets, wg, wu, wd):
+    """Backward of the sequential GeMM; an empty expert gets zero weight gradients."""
+    E, d, f = wg.shape
+    dXd = np.zeros_like(np.asarray(Xd, np.float64))
+    dWg = np.zeros((E, d, f))
+    dWu = np.zeros((E, d, f))
+    dWd = np.zeros((E, f, d))
+    for e in range(E):
+        lo, hi = int(expert_offsets[e]), int(expert_offsets[e + 1])
+        if hi == lo:
+            continue
+        dXd[lo:hi], dWg[e], dWu[e], dWd[e] = swiglu_ffn_bwd(
+            np.asarray(Xd[lo:hi], np.float64), G[lo:hi], U[lo:hi], dY[lo:hi],
+            np.asarray(wg[e], np.float64), np.asarray(wu[e], np.float64), np.asarray(wd[e], np.float64))
+    return dXd, dWg, dWu, dWd
+
+
+def dispatch_bwd(dXd, row_of_slot, T, k):
+    """dx[t] = sum_j dXd[row_of_slot[t*k+j]] (transpose of the gather)."""
+    dx = np.zeros((T, dXd.shape[1]))
+    for t in range(T):
+        for j in range(k):
+            dx[t] += dXd[row_of_slot[t * k + j]]
+    return dx
+
+
+def route_bwd(p, topk_idx, dw):
+    """Softmax Jacobian on the selected entries: dp[t,e_j] = dw[t,j], 0 elsewhere;
+    dlogits = p * (dp - sum_e p*dp)."""
+    T, E = p.shape
+    dp = np.zeros((T, E))
+    rows = np.arange(T)
+    for j in range(topk_idx.shape[1]):
+        dp[rows, topk_idx[:, j]] += dw[:, j]
+    inner = (p * dp).sum(axis=1, keepdims=True)
+    return p * (dp - inner)
+
+
+def moe_layer_bwd(inp: dict, fwd: dict, k: int) -> dict:
+    """Gradients of L = <dout, out> with respect to x, w_router, wg, wu, wd and the shared experts."""
+    x = np.asarray(inp["x"], np.float64)
+    dout = np.asarray(inp["dout"], np.float64)
+    T = x.shape[0]
+    eri = fwd["eri"]
+    dY, dw = combine_bwd(dout, fwd["Y"], eri["token_ids"], eri["combine_weights"], eri["row_of_slot"], k)
+    dXd, dWg, dWu, dWd = expert_ffn_bwd(fwd["Xd"], fwd["G"], fwd["U"], dY, eri["expert_offsets"],
+                                        inp["wg"], inp["wu"], inp["wd"])
+    dx = dispatch_bwd(dXd, eri["row_of_slot"], T, k)
+    dlogits = route_bwd(fwd["p"], fwd["topk_idx"], dw)
+    dWr = x.T @ dlogits
+    dx_gate = dlogits @ np.asarray(inp["w_router"], np.float64).T
+    res = {"dY": dY, "dw": dw, "dXd": dXd, "dwg": dWg, "dwu": dWu, "dwd": dWd, "dx_routed": dx,
+           "dlogits": dlogits, "dw_router": dWr, "dx_gate": dx_gate}
+    dx = dx + dx_gate
+    sh = inp.get("shared_wg")
+    if sh is not None and sh.shape[0] > 0:
+        Es = sh.shape[0]
+        dsx = np.zeros_like(x)
+        dswg = np.zeros(np.shape(inp["shared_wg"]))
+        dswu = np.zeros(np.shape(inp["shared_wu"]))
+        dswd = np.zeros(np.shape(inp["shared_wd"]))
+        for s in range(Es):
+            dxs, dswg[s], dswu[s], dswd[s] = swiglu_ffn_bwd(
+                x, fwd["shared_G"][s], fwd["shared_U"][s], dout, np.asarray(inp["shared_wg"][s], np.float64),
+                np.asarray(inp["shared_wu"][s], np.float64), np.asarray(inp["shared_wd"][s], np.float64))
+            dsx += dxs
+        res.update({"dx_shared": dsx, "dshared_wg": dswg, "dshared_wu": dswu, "dshared_wd": dswd})
+        dx = dx + dsx
+    res["dx"] = dx
+    return res
+
+
+# ----------------------------------------------------------------------------------------------------------
+# activation footprint (Section 3.1, Table 2; the paper's printed instance is Table 4's "Theoretical" row)
+# ----------------------------------------------------------------------------------------------------------
+def activation_bytes(T: int, k: int, d: int, f: int, bytes_per_el: int, c: float = 1.0) -> float:
+    """A_dispatch + A_combine (k*T*d each) plus the two FFN intermediates (k*T*f each), times capacity c."""
+    return c * bytes_per_el * T * k * (2 * d + 2 * f)
