@@ -1,0 +1,183 @@
+/*
+ * xmoe.h - C ABI of libxmoe: the single-GPU hot path of the padding-free MoE layer of X-MoE
+ * (arXiv 2508.13337) as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * The entry points follow the functions of the paper's Listing 1 ("Padding-free MoE-layer"):
+ *     gating()            -> xmoe_gate_logits + xmoe_route
+ *     PFT_construction()  -> xmoe_build_eri            (dropless: B = T*k rows)
+ *     dispatch()          -> xmoe_dispatch             (the gather kernel; the all-to-alls are identity on one GPU)
+ *     mlp()               -> xmoe_expert_ffn_fwd       (the "sequential GeMM" as one ragged grouped GEMM)
+ *     combine()           -> xmoe_combine              (the scatter kernel, as an atomics-free gather-reduce)
+ * and their backward companions (the paper only says backward mirrors forward, Section 4.3).
+ *
+ * Conventions that hold for every call
+ *   - Every pointer except `stream` is a DEVICE pointer owned by the caller; the library never allocates,
+ *     frees or synchronises.  All work is enqueued on the hipStream_t passed as `void* stream` (NULL = the
+ *     null stream).  Sizes are host integers.  Matrices are row-major and dense.
+ *   - `dt` is the storage type of activations and weights: XMOE_F32 (4 bytes) or XMOE_BF16 (2 bytes).
+ *     All arithmetic accumulates in float32; results are rounded once (nearest-even) when stored as bf16.
+ *     Logits, probabilities, combine weights and their gradients are always float32; indices are int32.
+ *   - Notation: T tokens, d model width (paper: S, H), E experts, k experts per token, f expert FFN width
+ *     (paper: H_FFN), B = T*k routed rows.
+ *   - Scratch memory comes from a caller-provided workspace of at least xmoe_workspace_bytes(...) bytes,
+ *     256-byte aligned.  Its contents are undefined after the call.
+ *   - Return value: an xmoe_status.  Argument errors are detected on the host before anything is enqueued
+ *     (XMOE_ERR_INVALID_ARG, XMOE_ERR_UNSUPPORTED, XMOE_ERR_WORKSPACE); a failed launch gives XMOE_ERR_HIP.
+ *   - Inputs must be finite; behaviour on NaN/Inf logits is unspecified.  Index arrays handed to a call must
+ *     be the ones an earlier call of this library produced for the same sizes (they are not re-validated on
+ *     the device).
+ */
+#ifndef XMOE_H
+#define XMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XMOE_OK = 0,
+    XMOE_ERR_INVALID_ARG = 1,   /* null required pointer, size out of range, k > E, T*k >= 2^31, ... */
+    XMOE_ERR_UNSUPPORTED = 2,   /* unknown dtype, E beyond the routing kernels' limit */
+    XMOE_ERR_WORKSPACE = 3,     /* workspace missing, misaligned or too small */
+    XMOE_ERR_HIP = 4            /* the HIP runtime reported an error at launch */
+} xmoe_status;
+
+typedef enum { XMOE_F32 = 0, XMOE_BF16 = 1 } xmoe_dtype;
+
+/* `op` of xmoe_workspace_bytes */
+typedef enum {
+    XMOE_WS_BUILD_ERI = 0,      /* rows = T           */
+    XMOE_WS_FFN_FWD = 1,        /* rows = B (FFN rows) */
+    XMOE_WS_FFN_BWD = 2,        /* rows = B            */
+    XMOE_WS_GATE_BWD = 3        /* rows = T            */
+} xmoe_ws_op;
+
+/* Largest expert count the routing / ERI kernels accept. */
+#define XMOE_MAX_EXPERTS 512
+
+/* Human-readable name of a status code (static storage). */
+const char* xmoe_status_string(int status);
+
+/* Library version string (static storage). */
+const char* xmoe_version(void);
+
+/* Bytes of workspace the given call needs.  Host-only, pure.  Returns 0 for an unknown op. */
+size_t xmoe_workspace_bytes(int op, int rows, int d, int E, int k, int f, int dt);
+
+/* ---------------------------------------------------------------------------------------------------------
+ * Gating, part 1 (Listing 1 gating(): "FFN(tokens)"; Appendix B.3: [S,H] tokens projected to [S,E] logits).
+ *   logits[t,e] = sum_i x[t,i] * w_router[i,e] (+ bias[e])
+ * evaluated in float32 in a fixed order, so that the top-k decision is reproducible bit for bit:
+ *   64 partial sums, partial l taking i = l, l+64, ... in ascending i with one fused multiply-add per term from
+ *   +0.0f; the partials folded by halving (offsets 32,16,8,4,2,1: p[l] += p[l+off]); then + bias[e].
+ * x [T,d] dt; w_router [d,E] dt; bias [E] float32 or NULL; logits [T,E] float32 (out).
+ */
+int xmoe_gate_logits(const void* x, const void* w_router, const float* bias, float* logits,
+                     int T, int d, int E, int dt, void* stream);
+
+/* Gating, part 2 (Listing 1 gating(): softmax over E, then top-k).
+ *   p = softmax(logits[t,:]);  slot j of token t holds the expert with the j-th largest logit, the lower index
+ *   winning ties;  topk_w[t,j] = p[t, topk_idx[t,j]]  (raw probabilities, not renormalised).
+ * logits [T,E] float32; topk_idx [T,k] int32 (out); topk_w [T,k] float32 (out).  1 <= k <= E <= XMOE_MAX_EXPERTS.
+ */
+int xmoe_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, void* stream);
+
+/* PFT construction (Listing 1 PFT_construction(), step 1 and the histogram; Section 4.1.1 defines the
+ * ERI-arrays).  Stable counting sort of the T*k flat entries n = t*k + j by expert id; row i of the PFT is the
+ * i-th entry of that order.  Dropless (max_token_count >= T), so B = T*k.
+ *   token_ids[i]        token of row i (n / k)                    [B] int32
+ *   expert_ids[i]       expert of row i (non-decreasing)          [B] int32
+ *   combine_weights[i]  topk_w of row i's entry                   [B] float32
+ *   tokens_per_expert   segment lengths                           [E] int32
+ *   expert_offsets      exclusive prefix sum of the above, [E+1]  (expert e owns rows [off[e], off[e+1]))
+ *   row_of_slot[n]      row that flat entry n landed in (inverse permutation)  [T*k] int32
+ * ws: XMOE_WS_BUILD_ERI bytes.
+ */
+int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                   int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                   int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Dispatch (Section 4.1.2 / Appendix B.4 gather kernel): xd[i,:] = x[token_ids[i],:], a bit copy.
+ * x [T,d] dt; token_ids [B] int32 with values in [0,T); xd [B,d] dt (out).
+ */
+int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, int dt, void* xd, void* stream);
+
+/* Expert MLP (Listing 1 mlp(); Appendix B.4 "Sequential GeMM"): for each expert e and its rows
+ * r in [expert_offsets[e], expert_offsets[e+1]):
+ *   G = Xd_e Wg_e,  U = Xd_e Wu_e,  A = silu(G) * U,  Y_e = A Wd_e          (SwiGLU, no biases)
+ * xd [B,d]; wg, wu [E,d,f]; wd [E,f,d] ("in x out"); expert_offsets [E+1] int32 on the device with
+ * offsets[0] = 0 and offsets[E] = B.  Outputs: y [B,d]; g_save, u_save [B,f] (kept for backward).
+ * An expert with no rows reads no weights.  Shared experts are served by the same call on x itself with
+ * E = 1, offsets {0,T} and the E_s experts concatenated along f (wg, wu [1,d,E_s*f]; wd [1,E_s*f,d]).
+ * ws: XMOE_WS_FFN_FWD bytes.
+ */
+int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, int E, int d, int f,
+                        const void* wg, const void* wu, const void* wd,
+                        void* g_save, void* u_save, void* y, int dt,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the expert MLP (derived; A is recomputed from the saved G and U):
+ *   dA = dY Wd^T;  dWd_e = A_e^T dY_e;  dG = dA * U * silu'(G);  dU = dA * silu(G);
+ *   dXd = dG Wg^T + dU Wu^T;  dWg_e = Xd_e^T dG_e;  dWu_e = Xd_e^T dU_e.
+ * Outputs: dxd [B,d]; dwg, dwu [E,d,f]; dwd [E,f,d] - overwritten, all zero for an expert with no rows.
+ * ws: XMOE_WS_FFN_BWD bytes.
+ */
+int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, const void* dy,
+                        const int32_t* expert_offsets, int B, int E, int d, int f,
+                        const void* wg, const void* wu, const void* wd,
+                        void* dxd, void* dwg, void* dwu, void* dwd, int dt,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* Combine (Section 4.1.2 / Appendix B.4 scatter kernel, which must accumulate since k rows share a token),
+ * written as a gather-reduce so that no atomics are needed and the sum order is fixed:
+ *   out[t,:] = sum_{j<k} topk_w[t,j] * y[row_of_slot[t*k+j],:]  (+ addend[t,:]) (+ addend2[t,:])
+ * accumulated in float32 in slot order, rounded once.  topk_w == NULL means all weights are 1 (this is then
+ * the backward of dispatch).  addend / addend2 [T,d] dt or NULL (e.g. the shared experts' output).
+ */
+int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
+                 const void* addend, const void* addend2, int T, int k, int d, int dt, void* out, void* stream);
+
+/* Backward of combine:
+ *   dy[row_of_slot[t*k+j],:] = topk_w[t,j] * dout[t,:];     dw[t,j] = <dout[t,:], y[row_of_slot[t*k+j],:]>
+ * dout [T,d]; y [B,d]; dy [B,d] (out); dw [T,k] float32 (out).
+ */
+int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w,
+                     int T, int k, int d, int dt, void* dy, float* dw, void* stream);
+
+/* Backward of dispatch: dx[t,:] = sum_j dxd[row_of_slot[t*k+j],:] (+ addend) (+ addend2).
+ * Same kernel as xmoe_combine with unit weights. */
+int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* addend, const void* addend2,
+                      int T, int k, int d, int dt, void* dx, void* stream);
+
+/* Backward of softmax + top-k with the indices held constant:
+ *   dp[t,e] = dw[t,j] if e == topk_idx[t,j] else 0;   dlogits = p * (dp - sum_e p*dp),  p = softmax(logits).
+ * dlogits [T,E] float32 (out).
+ */
+int xmoe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dw, int T, int E, int k,
+                   float* dlogits, void* stream);
+
+/* Backward of the gate projection:  dw_router = x^T dlogits  [d,E] dt;  dx_gate = dlogits w_router^T  [T,d] dt.
+ * ws: XMOE_WS_GATE_BWD bytes.
+ */
+int xmoe_gate_logits_bwd(const void* x, const void* w_router, const float* dlogits, int T, int d, int E, int dt,
+                         void* dw_router, void* dx_gate, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------------------
+ * Optional per-kernel timing with HIP events on the caller's stream (for benchmarks).  Off by default.
+ * While enabled, every kernel launch of the library is bracketed by a pair of events.  Not thread-safe.
+ */
+void xmoe_prof_enable(int on);
+void xmoe_prof_reset(void);                       /* drop all recorded samples */
+int xmoe_prof_num_kernels(void);                  /* number of kernel ids */
+const char* xmoe_prof_kernel_name(int kernel_id); /* name of the __global__ function behind a kernel id */
+/* Waits for all recorded events, then returns launches and total milliseconds of one kernel id. */
+int xmoe_prof_get(int kernel_id, int* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XMOE_H */

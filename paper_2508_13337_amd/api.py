@@ -1,0 +1,210 @@
+"""Python binding of the C ABI (include/xmoe.h): same names, argument marshalling only.
+
+Every function takes torch tensors that live on the GPU (torch supplies device memory and the current stream),
+checks dtype / contiguity / shape on the host, passes raw device pointers to libxmoe and raises XMoEError on a
+non-zero status.  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional
+
+import torch
+
+from ._lib import lib
+
+XMOE_F32, XMOE_BF16 = 0, 1
+WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD = 0, 1, 2, 3
+
+__all__ = [
+    "XMoEError", "xmoe_version", "xmoe_workspace_bytes", "xmoe_gate_logits", "xmoe_route", "xmoe_build_eri",
+    "xmoe_dispatch", "xmoe_expert_ffn_fwd", "xmoe_expert_ffn_bwd", "xmoe_combine", "xmoe_combine_bwd",
+    "xmoe_dispatch_bwd", "xmoe_route_bwd", "xmoe_gate_logits_bwd", "xmoe_prof_enable", "xmoe_prof_reset",
+    "xmoe_prof_read", "dtype_code", "alloc_workspace",
+    "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD",
+]
+
+
+class XMoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().xmoe_status_string(status).decode()} (status {status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise XMoEError(status, where)
+
+
+def dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float32:
+        return XMOE_F32
+    if dt == torch.bfloat16:
+        return XMOE_BF16
+    raise TypeError(f"xmoe supports float32 and bfloat16 storage, not {dt}")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def xmoe_version() -> str:
+    return lib().xmoe_version().decode()
+
+
+def xmoe_workspace_bytes(op: int, rows: int, d: int, E: int, k: int, f: int, dt: int) -> int:
+    return int(lib().xmoe_workspace_bytes(op, rows, d, E, k, f, dt))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """A byte tensor of at least nbytes whose base is 256-byte aligned (torch's allocator aligns to 512)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def xmoe_gate_logits(x, w_router, bias, logits) -> None:
+    T, d = x.shape
+    E = w_router.shape[1]
+    assert w_router.shape[0] == d and tuple(logits.shape) == (T, E)
+    _check(lib().xmoe_gate_logits(_ptr(x, None, "x"), _ptr(w_router, x.dtype, "w_router"),
+                                  _ptr(bias, torch.float32, "bias"), _ptr(logits, torch.float32, "logits"),
+                                  T, d, E, dtype_code(x.dtype), _stream()), "xmoe_gate_logits")
+
+
+def xmoe_route(logits, k: int, topk_idx, topk_w) -> None:
+    T, E = logits.shape
+    assert tuple(topk_idx.shape) == (T, k) and tuple(topk_w.shape) == (T, k)
+    _check(lib().xmoe_route(_ptr(logits, torch.float32, "logits"), T, E, k, _ptr(topk_idx, torch.int32, "topk_idx"),
+                            _ptr(topk_w, torch.float32, "topk_w"), _stream()), "xmoe_route")
+
+
+def xmoe_build_eri(topk_idx, topk_w, E: int, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                   combine_weights, row_of_slot, ws) -> None:
+    T, k = topk_idx.shape
+    B = T * k
+    assert tokens_per_expert.numel() == E and expert_offsets.numel() == E + 1
+    assert token_ids.numel() == B and expert_ids.numel() == B and combine_weights.numel() == B
+    assert row_of_slot.numel() == B
+    _check(lib().xmoe_build_eri(
+        _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"), T, E, k,
+        _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
+        _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_build_eri")
+
+
+def xmoe_dispatch(x, token_ids, xd) -> None:
+    T, d = x.shape
+    B = token_ids.numel()
+    assert tuple(xd.shape) == (B, d) and xd.dtype == x.dtype
+    _check(lib().xmoe_dispatch(_ptr(x, None, "x"), _ptr(token_ids, torch.int32, "token_ids"), T, B, d,
+                               dtype_code(x.dtype), _ptr(xd, None, "xd"), _stream()), "xmoe_dispatch")
+
+
+def xmoe_expert_ffn_fwd(xd, expert_offsets, wg, wu, wd, g_save, u_save, y, ws) -> None:
+    B, d = xd.shape
+    E, d2, f = wg.shape
+    dt = xd.dtype
+    assert d2 == d and tuple(wu.shape) == (E, d, f) and tuple(wd.shape) == (E, f, d)
+    assert expert_offsets.numel() == E + 1
+    assert tuple(g_save.shape) == (B, f) and tuple(u_save.shape) == (B, f) and tuple(y.shape) == (B, d)
+    _check(lib().xmoe_expert_ffn_fwd(
+        _ptr(xd, None, "xd"), _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f,
+        _ptr(wg, dt, "wg"), _ptr(wu, dt, "wu"), _ptr(wd, dt, "wd"), _ptr(g_save, dt, "g_save"),
+        _ptr(u_save, dt, "u_save"), _ptr(y, dt, "y"), dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(),
+        _stream()), "xmoe_expert_ffn_fwd")
+
+
+def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd, dwg, dwu, dwd, ws) -> None:
+    B, d = xd.shape
+    E, d2, f = wg.shape
+    dt = xd.dtype
+    assert d2 == d and tuple(wu.shape) == (E, d, f) and tuple(wd.shape) == (E, f, d)
+    assert tuple(dwg.shape) == (E, d, f) and tuple(dwu.shape) == (E, d, f) and tuple(dwd.shape) == (E, f, d)
+    assert tuple(g_save.shape) == (B, f) and tuple(u_save.shape) == (B, f)
+    assert tuple(dy.shape) == (B, d) and tuple(dxd.shape) == (B, d)
+    _check(lib().xmoe_expert_ffn_bwd(
+        _ptr(xd, None, "xd"), _ptr(g_save, dt, "g_save"), _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(wg, dt), _ptr(wu, dt), _ptr(wd, dt),
+        _ptr(dxd, dt, "dxd"), _ptr(dwg, dt, "dwg"), _ptr(dwu, dt, "dwu"), _ptr(dwd, dt, "dwd"), dtype_code(dt),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")
+
+
+def xmoe_combine(y, row_of_slot, topk_w, addend, addend2, k: int, out) -> None:
+    T, d = out.shape
+    dt = out.dtype
+    assert y.shape[1] == d and row_of_slot.numel() == T * k
+    _check(lib().xmoe_combine(_ptr(y, dt, "y"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
+                              _ptr(topk_w, torch.float32, "topk_w"), _ptr(addend, dt, "addend"),
+                              _ptr(addend2, dt, "addend2"), T, k, d, dtype_code(dt), _ptr(out, None, "out"),
+                              _stream()), "xmoe_combine")
+
+
+def xmoe_combine_bwd(dout, y, row_of_slot, topk_w, dy, dw) -> None:
+    T, d = dout.shape
+    k = topk_w.shape[1]
+    dt = dout.dtype
+    assert tuple(dy.shape) == tuple(y.shape) == (T * k, d) and tuple(dw.shape) == (T, k)
+    _check(lib().xmoe_combine_bwd(_ptr(dout, None, "dout"), _ptr(y, dt, "y"),
+                                  _ptr(row_of_slot, torch.int32, "row_of_slot"),
+                                  _ptr(topk_w, torch.float32, "topk_w"), T, k, d, dtype_code(dt), _ptr(dy, dt, "dy"),
+                                  _ptr(dw, torch.float32, "dw"), _stream()), "xmoe_combine_bwd")
+
+
+def xmoe_dispatch_bwd(dxd, row_of_slot, addend, addend2, k: int, dx) -> None:
+    T, d = dx.shape
+    dt = dx.dtype
+    assert tuple(dxd.shape) == (T * k, d)
+    _check(lib().xmoe_dispatch_bwd(_ptr(dxd, dt, "dxd"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
+                                   _ptr(addend, dt, "addend"), _ptr(addend2, dt, "addend2"), T, k, d,
+                                   dtype_code(dt), _ptr(dx, None, "dx"), _stream()), "xmoe_dispatch_bwd")
+
+
+def xmoe_route_bwd(logits, topk_idx, dw, dlogits) -> None:
+    T, E = logits.shape
+    k = topk_idx.shape[1]
+    assert tuple(dw.shape) == (T, k) and tuple(dlogits.shape) == (T, E)
+    _check(lib().xmoe_route_bwd(_ptr(logits, torch.float32, "logits"), _ptr(topk_idx, torch.int32, "topk_idx"),
+                                _ptr(dw, torch.float32, "dw"), T, E, k, _ptr(dlogits, torch.float32, "dlogits"),
+                                _stream()), "xmoe_route_bwd")
+
+
+def xmoe_gate_logits_bwd(x, w_router, dlogits, dw_router, dx_gate, ws) -> None:
+    T, d = x.shape
+    E = w_router.shape[1]
+    dt = x.dtype
+    assert tuple(dlogits.shape) == (T, E) and tuple(dw_router.shape) == (d, E) and tuple(dx_gate.shape) == (T, d)
+    _check(lib().xmoe_gate_logits_bwd(_ptr(x, None, "x"), _ptr(w_router, dt, "w_router"),
+                                      _ptr(dlogits, torch.float32, "dlogits"), T, d, E, dtype_code(dt),
+                                      _ptr(dw_router, dt, "dw_router"), _ptr(dx_gate, dt, "dx_gate"),
+                                      _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_gate_logits_bwd")
+
+
+def xmoe_prof_enable(on: bool) -> None:
+    lib().xmoe_prof_enable(1 if on else 0)
+
+
+def xmoe_prof_reset() -> None:
+    lib().xmoe_prof_reset()
+
+
+def xmoe_prof_read() -> dict:
+    """{kernel name: (launches, total milliseconds)} for every kernel that was launched while profiling."""
+    out = {}
+    n = ctypes.c_int()
+    ms = ctypes.c_double()
+    for kid in range(lib().xmoe_prof_num_kernels()):
+        _check(lib().xmoe_prof_get(kid, ctypes.byref(n), ctypes.byref(ms)), "xmoe_prof_get")
+        if n.value:
+            out[lib().xmoe_prof_kernel_name(kid).decode()] = (n.value, ms.value)
+    return out

@@ -1,0 +1,142 @@
+// Status strings, workspace sizing and the optional event profiler of libxmoe.
+#include <vector>
+
+#include "xmoe_internal.h"
+#include "xmoe_sizes.h"
+
+namespace xmoe {
+
+namespace {
+struct Sample {
+    int kid;
+    hipEvent_t start, stop;
+};
+struct Prof {
+    bool on = false;
+    std::vector<Sample> samples;
+    std::vector<hipEvent_t> free_events;
+    hipEvent_t pending_start = nullptr;
+};
+Prof g_prof;
+
+const char* const kKernelNames[K_COUNT] = {
+    "gate_logits_kernel",
+    "route_kernel",
+    "eri_hist_kernel",
+    "eri_scan_kernel",
+    "eri_scatter_kernel",
+    "dispatch_kernel",
+    "combine_kernel",
+    "combine_bwd_kernel",
+    "route_bwd_kernel",
+    "gate_bwd_dw_kernel",
+    "gate_bwd_dw_reduce_kernel",
+    "gate_bwd_dx_kernel",
+    "tile_map_kernel",
+    "ffn_gateup_simt_kernel",
+    "ffn_down_simt_kernel",
+    "ffn_dact_simt_kernel",
+    "ffn_dx_simt_kernel",
+    "ffn_wgrad_simt_kernel",
+    "ffn_gateup_mfma_kernel",
+    "ffn_down_mfma_kernel",
+    "ffn_dact_mfma_kernel",
+    "ffn_dx_mfma_kernel",
+    "ffn_wgrad_mfma_kernel",
+};
+
+hipEvent_t get_event() {
+    if (!g_prof.free_events.empty()) {
+        hipEvent_t e = g_prof.free_events.back();
+        g_prof.free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+void prof_begin(int kid, hipStream_t s) {
+    (void)kid;
+    if (!g_prof.on) return;
+    hipEvent_t e = get_event();
+    g_prof.pending_start = e;
+    if (e) (void)hipEventRecord(e, s);
+}
+
+void prof_end(int kid, hipStream_t s) {
+    if (!g_prof.on) return;
+    hipEvent_t st = g_prof.pending_start;
+    g_prof.pending_start = nullptr;
+    hipEvent_t e = get_event();
+    if (!st || !e) return;
+    (void)hipEventRecord(e, s);
+    g_prof.samples.push_back(Sample{kid, st, e});
+}
+
+}  // namespace xmoe
+
+using namespace xmoe;
+
+extern "C" {
+
+const char* xmoe_status_string(int status) {
+    switch (status) {
+        case XMOE_OK: return "XMOE_OK";
+        case XMOE_ERR_INVALID_ARG: return "XMOE_ERR_INVALID_ARG: null pointer or size out of range";
+        case XMOE_ERR_UNSUPPORTED: return "XMOE_ERR_UNSUPPORTED: dtype or size not supported";
+        case XMOE_ERR_WORKSPACE: return "XMOE_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case XMOE_ERR_HIP: return "XMOE_ERR_HIP: HIP runtime error at kernel launch";
+        default: return "unknown xmoe status";
+    }
+}
+
+const char* xmoe_version(void) { return "xmoe 0.1 (gfx950)"; }
+
+size_t xmoe_workspace_bytes(int op, int rows, int d, int E, int k, int f, int dt) {
+    if (rows < 0 || d < 0 || E < 0 || k < 0 || f < 0 || !dtype_ok(dt)) return 0;
+    switch (op) {
+        case XMOE_WS_BUILD_ERI: return eri_ws_bytes(rows, E, k);
+        case XMOE_WS_FFN_FWD: return ffn_fwd_ws_bytes(rows, E, d, f, dt);
+        case XMOE_WS_FFN_BWD: return ffn_bwd_ws_bytes(rows, E, d, f, dt);
+        case XMOE_WS_GATE_BWD: return gate_bwd_ws_bytes(rows, d, E);
+        default: return 0;
+    }
+}
+
+void xmoe_prof_enable(int on) { g_prof.on = (on != 0); }
+
+void xmoe_prof_reset(void) {
+    for (auto& s : g_prof.samples) {
+        g_prof.free_events.push_back(s.start);
+        g_prof.free_events.push_back(s.stop);
+    }
+    g_prof.samples.clear();
+}
+
+int xmoe_prof_num_kernels(void) { return K_COUNT; }
+
+const char* xmoe_prof_kernel_name(int kernel_id) {
+    if (kernel_id < 0 || kernel_id >= K_COUNT) return "";
+    return kKernelNames[kernel_id];
+}
+
+int xmoe_prof_get(int kernel_id, int* launches, double* total_ms) {
+    if (kernel_id < 0 || kernel_id >= K_COUNT || !launches || !total_ms) return XMOE_ERR_INVALID_ARG;
+    int n = 0;
+    double ms = 0.0;
+    for (auto& s : g_prof.samples) {
+        if (s.kid != kernel_id) continue;
+        if (hipEventSynchronize(s.stop) != hipSuccess) return XMOE_ERR_HIP;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, s.start, s.stop) != hipSuccess) return XMOE_ERR_HIP;
+        ms += t;
+        ++n;
+    }
+    *launches = n;
+    *total_ms = ms;
+    return XMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Internal interface between the expert-MLP entry points and their two kernel families.
+#pragma once
+
+#include "xmoe_internal.h"
+#include "xmoe_sizes.h"
+
+namespace xmoe {
+
+struct FfnArgs {
+    int B, E, d, f, dt;
+    const int32_t* off;          // expert_offsets [E+1], device
+    const void *xd, *wg, *wu, *wd;
+    // forward: outputs g, u, y; backward: inputs g, u, dy and outputs dxd, dwg, dwu, dwd
+    void *g, *u, *y;
+    const void* dy;
+    void *dxd, *dwg, *dwu, *dwd;
+    // workspace carve-up
+    int32_t* map;                // tile map
+    void *act, *dg, *du;         // A = silu(G)*U, dG, dU   [B,f]
+};
+
+int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, hipStream_t s);
+
+int ffn_fwd_simt(const FfnArgs& a, hipStream_t s);
+int ffn_bwd_simt(const FfnArgs& a, hipStream_t s);
+
+// bf16 MFMA family: needs d % 64 == 0, f % 64 == 0 and 16-byte aligned operands
+bool ffn_mfma_supported(const FfnArgs& a);
+int ffn_fwd_mfma(const FfnArgs& a, hipStream_t s);
+int ffn_bwd_mfma(const FfnArgs& a, hipStream_t s);
+
+}  // namespace xmoe

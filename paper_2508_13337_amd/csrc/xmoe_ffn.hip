@@ -1,0 +1,86 @@
+// Entry points of the expert MLP (paper: Listing 1 mlp(); Appendix B.4): argument checks, workspace carve-up,
+// and the choice between the bf16 MFMA kernels and the float32-ALU kernels.
+#include <stdlib.h>
+
+#include "xmoe_ffn.h"
+
+namespace xmoe {
+
+static int g_force_simt = -1;
+static bool force_simt() {
+    if (g_force_simt < 0) {
+        const char* v = getenv("XMOE_FFN_FORCE_SIMT");
+        g_force_simt = (v && v[0] == '1') ? 1 : 0;
+    }
+    return g_force_simt == 1;
+}
+
+static int check_common(int B, int E, int d, int f, int dt) {
+    if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
+    if (B < 0 || E < 1 || d < 1 || f < 1) return XMOE_ERR_INVALID_ARG;
+    if (E > XMOE_MAX_EXPERTS) return XMOE_ERR_UNSUPPORTED;
+    if ((long long)B * d >= (1ll << 40) || (long long)B * f >= (1ll << 40)) return XMOE_ERR_INVALID_ARG;
+    return XMOE_OK;
+}
+
+}  // namespace xmoe
+
+using namespace xmoe;
+
+extern "C" {
+
+int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg,
+                        const void* wu, const void* wd, void* g_save, void* u_save, void* y, int dt, void* ws,
+                        size_t ws_bytes, void* stream) {
+    int st = check_common(B, E, d, f, dt);
+    if (st != XMOE_OK) return st;
+    if (!expert_offsets || !wg || !wu || !wd) return XMOE_ERR_INVALID_ARG;
+    if (B == 0) return XMOE_OK;
+    if (!xd || !g_save || !u_save || !y) return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < ffn_fwd_ws_bytes(B, E, d, f, dt))
+        return XMOE_ERR_WORKSPACE;
+    FfnArgs a{};
+    a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt;
+    a.off = expert_offsets;
+    a.xd = xd; a.wg = wg; a.wu = wu; a.wd = wd;
+    a.g = g_save; a.u = u_save; a.y = y;
+    char* p = (char*)ws;
+    a.map = (int32_t*)p;
+    p += ffn_tilemap_bytes(B, E);
+    a.act = p;
+    hipStream_t s = (hipStream_t)stream;
+    if (!force_simt() && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
+    return ffn_fwd_simt(a, s);
+}
+
+int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, const void* dy,
+                        const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
+                        const void* wd, void* dxd, void* dwg, void* dwu, void* dwd, int dt, void* ws,
+                        size_t ws_bytes, void* stream) {
+    int st = check_common(B, E, d, f, dt);
+    if (st != XMOE_OK) return st;
+    if (!expert_offsets || !wg || !wu || !wd || !dwg || !dwu || !dwd) return XMOE_ERR_INVALID_ARG;
+    if (B > 0 && (!xd || !g_save || !u_save || !dy || !dxd)) return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < ffn_bwd_ws_bytes(B, E, d, f, dt))
+        return XMOE_ERR_WORKSPACE;
+    FfnArgs a{};
+    a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt;
+    a.off = expert_offsets;
+    a.xd = xd; a.wg = wg; a.wu = wu; a.wd = wd;
+    a.g = const_cast<void*>(g_save); a.u = const_cast<void*>(u_save);
+    a.dy = dy;
+    a.dxd = dxd; a.dwg = dwg; a.dwu = dwu; a.dwd = dwd;
+    char* p = (char*)ws;
+    a.map = (int32_t*)p;
+    p += ffn_tilemap_bytes(B, E);
+    a.dg = p;
+    p += ffn_act_bytes(B, f, dt);
+    a.du = p;
+    p += ffn_act_bytes(B, f, dt);
+    a.act = p;
+    hipStream_t s = (hipStream_t)stream;
+    if (!force_simt() && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
+    return ffn_bwd_simt(a, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,274 @@
+// Expert MLP over ragged segments (paper: Listing 1 mlp(); Appendix B.4 "Sequential GeMM"), float32-ALU version:
+// serves float32 workloads and any shape the MFMA kernels do not take.  One launch covers every expert: a tile
+// map built on the device says which expert and which rows each row tile belongs to, so there is no host
+// round trip on tokens_per_expert and no per-expert launch.
+#include "xmoe_ffn.h"
+#include "xmoe_simt_gemm.h"
+
+namespace xmoe {
+
+// ---------------------------------------------------------------------------------------------------------
+// tile map: header {total tiles, 0, 0, 0} then (expert, first row) per row tile; unused entries have expert -1
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void tile_map_kernel(const int32_t* __restrict__ off, int E, int tile_rows,
+                                                       int max_tiles, int32_t* __restrict__ map) {
+    __shared__ int start[XMOE_MAX_EXPERTS + 1];
+    const int e = threadIdx.x;
+    int nt = 0, lo = 0;
+    if (e < E) {
+        lo = off[e];
+        int m = off[e + 1] - lo;
+        nt = m > 0 ? (m + tile_rows - 1) / tile_rows : 0;
+        start[e] = nt;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int i = 0; i < E; ++i) {
+            int v = start[i];
+            start[i] = run;
+            run += v;
+        }
+        start[E] = run < max_tiles ? run : max_tiles;
+        map[0] = start[E];
+        map[1] = map[2] = map[3] = 0;
+    }
+    __syncthreads();
+    if (e < E) {
+        for (int i = 0; i < nt; ++i) {
+            int ti = start[e] + i;
+            if (ti < max_tiles) {
+                map[4 + 2 * ti] = e;
+                map[4 + 2 * ti + 1] = lo + i * tile_rows;
+            }
+        }
+    }
+    for (int ti = start[E] + threadIdx.x; ti < max_tiles; ti += 512) {
+        map[4 + 2 * ti] = -1;
+        map[4 + 2 * ti + 1] = 0;
+    }
+}
+
+int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, hipStream_t s) {
+    XMOE_LAUNCH(K_TILE_MAP, s,
+                hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(512), 0, s, off, E, tile_rows, max_tiles, map));
+    return XMOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// forward 1: G = Xd Wg, U = Xd Wu, A = silu(G) * U          rows: ragged, K = d, N = f
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ffn_gateup_simt_kernel(const T* __restrict__ xd, const int32_t* __restrict__ off,
+                                                              const int32_t* __restrict__ map, int d, int f,
+                                                              const T* __restrict__ wg, const T* __restrict__ wu,
+                                                              T* __restrict__ G, T* __restrict__ U,
+                                                              T* __restrict__ A) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* wge = wg + (size_t)e * d * f;
+    const T* wue = wu + (size_t)e * d * f;
+    auto loadA = [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(xd[(size_t)r * d + kk]) : 0.f; };
+    float accg[4][4] = {}, accu[4][4] = {};
+    simt_mainloop<true, true>(accg, d, sm, loadA,
+                              [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wge[(size_t)kk * f + n]) : 0.f; });
+    simt_mainloop<true, true>(accu, d, sm, loadA,
+                              [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wue[(size_t)kk * f + n]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < f) {
+                float g = accg[i][j], u = accu[i][j];
+                G[(size_t)r * f + n] = from_float<T>(g);
+                U[(size_t)r * f + n] = from_float<T>(u);
+                A[(size_t)r * f + n] = from_float<T>(siluf_(g) * u);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// forward 2: Y = A Wd                                       rows: ragged, K = f, N = d
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ffn_down_simt_kernel(const T* __restrict__ A, const int32_t* __restrict__ off,
+                                                            const int32_t* __restrict__ map, int d, int f,
+                                                            const T* __restrict__ wd, T* __restrict__ Y) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* wde = wd + (size_t)e * f * d;
+    float acc[4][4] = {};
+    simt_mainloop<true, true>(
+        acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(A[(size_t)r * f + kk]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wde[(size_t)kk * d + n]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < d) Y[(size_t)r * d + n] = from_float<T>(acc[i][j]);
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// backward 1: dA = dY Wd^T, then dG = dA * U * silu'(G), dU = dA * silu(G), A = silu(G) * U
+//                                                            rows: ragged, K = d, N = f
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict__ dY, const int32_t* __restrict__ off,
+                                                            const int32_t* __restrict__ map, int d, int f,
+                                                            const T* __restrict__ wd, const T* __restrict__ G,
+                                                            const T* __restrict__ U, T* __restrict__ dG,
+                                                            T* __restrict__ dU, T* __restrict__ A) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* wde = wd + (size_t)e * f * d;
+    float acc[4][4] = {};
+    simt_mainloop<true, false>(
+        acc, d, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dY[(size_t)r * d + kk]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wde[(size_t)n * d + kk]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < f) {
+                size_t ix = (size_t)r * f + n;
+                float g = to_float(G[ix]), u = to_float(U[ix]), da = acc[i][j];
+                float sg = sigmoidf_(g);
+                float sl = g * sg;
+                dG[ix] = from_float<T>(da * u * (sg * (1.0f + g * (1.0f - sg))));
+                dU[ix] = from_float<T>(da * sl);
+                A[ix] = from_float<T>(sl * u);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// backward 2: dXd = dG Wg^T + dU Wu^T                        rows: ragged, K = f (twice), N = d
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ffn_dx_simt_kernel(const T* __restrict__ dG, const T* __restrict__ dU,
+                                                          const int32_t* __restrict__ off,
+                                                          const int32_t* __restrict__ map, int d, int f,
+                                                          const T* __restrict__ wg, const T* __restrict__ wu,
+                                                          T* __restrict__ dXd) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* wge = wg + (size_t)e * d * f;
+    const T* wue = wu + (size_t)e * d * f;
+    float acc[4][4] = {};
+    simt_mainloop<true, false>(
+        acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dG[(size_t)r * f + kk]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wge[(size_t)n * f + kk]) : 0.f; });
+    simt_mainloop<true, false>(
+        acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dU[(size_t)r * f + kk]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wue[(size_t)n * f + kk]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < d) dXd[(size_t)r * d + n] = from_float<T>(acc[i][j]);
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// weight gradients: dW_e[m,n] = sum over the expert's rows r of P[r,m] * Q[r,n]   (K = ragged)
+//   dWd = A^T dY (M=f, N=d);  dWg = Xd^T dG, dWu = Xd^T dU (M=d, N=f).  Empty experts get zeros.
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict__ P, const T* __restrict__ Q,
+                                                             const int32_t* __restrict__ off, int M, int N,
+                                                             T* __restrict__ dW) {
+    __shared__ SimtSmem sm;
+    const int e = blockIdx.z;
+    const int lo = off[e], hi = off[e + 1];
+    const int m0 = blockIdx.x * kSimtTile, n0 = blockIdx.y * kSimtTile;
+    float acc[4][4] = {};
+    simt_mainloop<false, true>(
+        acc, hi - lo, sm, [&](int mm, int kk) { int m = m0 + mm; return m < M ? to_float(P[(size_t)(lo + kk) * M + m]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < N ? to_float(Q[(size_t)(lo + kk) * N + n]) : 0.f; });
+    T* out = dW + (size_t)e * M * N;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (m < M && n < N) out[(size_t)m * N + n] = from_float<T>(acc[i][j]);
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// host-side drivers
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+static int fwd_simt(const FfnArgs& a, hipStream_t s) {
+    const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, s);
+    if (st != XMOE_OK) return st;
+    dim3 g1(max_tiles, (a.f + kSimtTile - 1) / kSimtTile), g2(max_tiles, (a.d + kSimtTile - 1) / kSimtTile);
+    XMOE_LAUNCH(K_FFN_GATEUP_SIMT, s,
+                hipLaunchKernelGGL(ffn_gateup_simt_kernel<T>, g1, dim3(256), 0, s, (const T*)a.xd, a.off, a.map, a.d,
+                                   a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.g, (T*)a.u, (T*)a.act));
+    XMOE_LAUNCH(K_FFN_DOWN_SIMT, s,
+                hipLaunchKernelGGL(ffn_down_simt_kernel<T>, g2, dim3(256), 0, s, (const T*)a.act, a.off, a.map, a.d,
+                                   a.f, (const T*)a.wd, (T*)a.y));
+    return XMOE_OK;
+}
+
+template <typename T>
+static int bwd_simt(const FfnArgs& a, hipStream_t s) {
+    const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, s);
+    if (st != XMOE_OK) return st;
+    const int tf = (a.f + kSimtTile - 1) / kSimtTile, td = (a.d + kSimtTile - 1) / kSimtTile;
+    XMOE_LAUNCH(K_FFN_DACT_SIMT, s,
+                hipLaunchKernelGGL(ffn_dact_simt_kernel<T>, dim3(max_tiles, tf), dim3(256), 0, s, (const T*)a.dy, a.off,
+                                   a.map, a.d, a.f, (const T*)a.wd, (const T*)a.g, (const T*)a.u, (T*)a.dg, (T*)a.du,
+                                   (T*)a.act));
+    XMOE_LAUNCH(K_FFN_DX_SIMT, s,
+                hipLaunchKernelGGL(ffn_dx_simt_kernel<T>, dim3(max_tiles, td), dim3(256), 0, s, (const T*)a.dg,
+                                   (const T*)a.du, a.off, a.map, a.d, a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.dxd));
+    XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
+                hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(tf, td, a.E), dim3(256), 0, s, (const T*)a.act,
+                                   (const T*)a.dy, a.off, a.f, a.d, (T*)a.dwd));
+    XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
+                hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
+                                   (const T*)a.dg, a.off, a.d, a.f, (T*)a.dwg));
+    XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
+                hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
+                                   (const T*)a.du, a.off, a.d, a.f, (T*)a.dwu));
+    return XMOE_OK;
+}
+
+int ffn_fwd_simt(const FfnArgs& a, hipStream_t s) {
+    return a.dt == XMOE_F32 ? fwd_simt<float>(a, s) : fwd_simt<bf16_t>(a, s);
+}
+int ffn_bwd_simt(const FfnArgs& a, hipStream_t s) {
+    return a.dt == XMOE_F32 ? bwd_simt<float>(a, s) : bwd_simt<bf16_t>(a, s);
+}
+
+}  // namespace xmoe

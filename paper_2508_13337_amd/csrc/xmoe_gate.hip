@@ -1,0 +1,406 @@
+// Gating of the padding-free MoE layer (paper: Listing 1 gating(); Appendix B.3 "Padding-free Gating"):
+// gate projection in a fixed float32 order, softmax + top-k routing, and their backward.
+#include "xmoe_internal.h"
+#include "xmoe_simt_gemm.h"
+#include "xmoe_sizes.h"
+
+namespace xmoe {
+
+// =========================================================================================================
+// gate projection, fixed summation order
+// =========================================================================================================
+// One wave owns GT tokens x GE experts.  Lane l is partial sum l of the contract: it walks i = l, l+64, ...
+// and keeps GT*GE accumulators.  The 64 partials of every (token, expert) pair are then folded by halving
+// (lane l with lane l^32, then l^16, ...), which is the order the contract prescribes; the fold is done as a
+// transposing reduction so that lane v ends up with the finished sum of pair v.
+constexpr int kGT = 8;
+constexpr int kGE = 8;
+
+template <typename T>
+__device__ __forceinline__ void load_w8(const T* __restrict__ wrow, int e0, int E, bool vec, float (&wv)[kGE]);
+
+template <>
+__device__ __forceinline__ void load_w8<float>(const float* __restrict__ wrow, int e0, int E, bool vec,
+                                               float (&wv)[kGE]) {
+    if (vec) {
+        const float4* p = reinterpret_cast<const float4*>(wrow + e0);
+        float4 a = p[0], b = p[1];
+        wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w;
+        wv[4] = b.x; wv[5] = b.y; wv[6] = b.z; wv[7] = b.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < kGE; ++j) wv[j] = (e0 + j < E) ? wrow[e0 + j] : 0.f;
+    }
+}
+
+template <>
+__device__ __forceinline__ void load_w8<bf16_t>(const bf16_t* __restrict__ wrow, int e0, int E, bool vec,
+                                                float (&wv)[kGE]) {
+    if (vec) {
+        uint4 q = *reinterpret_cast<const uint4*>(wrow + e0);
+        uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            wv[2 * j] = __uint_as_float(u[j] << 16);
+            wv[2 * j + 1] = __uint_as_float(u[j] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kGE; ++j) wv[j] = (e0 + j < E) ? to_float(wrow[e0 + j]) : 0.f;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gate_logits_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                          const float* __restrict__ bias,
+                                                          float* __restrict__ logits, int Tn, int d, int E,
+                                                          int vec_w) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int t0 = blockIdx.x * kGT;
+    const int e0 = (blockIdx.y * 4 + wave) * kGE;
+    if (e0 >= E) return;
+
+    float acc[kGT * kGE];
+#pragma unroll
+    for (int v = 0; v < kGT * kGE; ++v) acc[v] = 0.0f;
+
+    const T* xrow[kGT];
+#pragma unroll
+    for (int tt = 0; tt < kGT; ++tt) {
+        int t = t0 + tt;
+        t = t < Tn ? t : Tn - 1;
+        xrow[tt] = x + (size_t)t * d;
+    }
+
+    for (int i = lane; i < d; i += 64) {
+        float wv[kGE];
+        load_w8<T>(w + (size_t)i * E, e0, E, vec_w != 0, wv);
+        float xv[kGT];
+#pragma unroll
+        for (int tt = 0; tt < kGT; ++tt) xv[tt] = to_float(xrow[tt][i]);
+#pragma unroll
+        for (int tt = 0; tt < kGT; ++tt)
+#pragma unroll
+            for (int ee = 0; ee < kGE; ++ee) acc[tt * kGE + ee] = fmaf(xv[tt], wv[ee], acc[tt * kGE + ee]);
+    }
+
+    // fold the 64 lane partials of each of the 64 (token, expert) pairs: offsets 32, 16, 8, 4, 2, 1
+#pragma unroll
+    for (int width = 32; width >= 1; width >>= 1) {
+        const bool upper = (lane & width) != 0;
+#pragma unroll
+        for (int v = 0; v < width; ++v) {
+            float send = upper ? acc[v] : acc[v + width];
+            float keep = upper ? acc[v + width] : acc[v];
+            float recv = __shfl_xor(send, width, 64);
+            acc[v] = keep + recv;
+        }
+    }
+    // lane v now holds pair v = tt*kGE + ee
+    const int t = t0 + (lane / kGE);
+    const int e = e0 + (lane % kGE);
+    if (t < Tn && e < E) {
+        float v = acc[0];
+        if (bias) v = v + bias[e];
+        logits[(size_t)t * E + e] = v;
+    }
+}
+
+// =========================================================================================================
+// softmax + top-k: one wave per token
+// =========================================================================================================
+constexpr int kMaxPerLane = XMOE_MAX_EXPERTS / 64;   // 8
+
+__device__ __forceinline__ uint32_t order_key(float v) {
+    uint32_t u = __float_as_uint(v);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        unsigned long long o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+template <int PER_LANE>
+__global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ logits, int Tn, int E, int k,
+                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    const float* row = logits + (size_t)t * E;
+    float l[PER_LANE];
+    // key = (order-preserving bits of the logit, inverted expert index): the maximum is the largest logit,
+    // and among equal logits the smallest index
+    unsigned long long key[PER_LANE];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        int e = lane + 64 * j;
+        bool ok = e < E;
+        l[j] = ok ? row[e] : -INFINITY;
+        key[j] = ok ? (((unsigned long long)order_key(l[j]) << 32) | (uint32_t)(0xffffffffu - (uint32_t)e)) : 0ull;
+        m = fmaxf(m, l[j]);
+    }
+    m = wave_max(m);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) s += (lane + 64 * j < E) ? expf(l[j] - m) : 0.f;
+    s = wave_sum(s);
+    const float inv = 1.0f / s;
+
+    int my_idx = 0;
+    float my_w = 0.f;
+    for (int slot = 0; slot < k; ++slot) {
+        unsigned long long best = 0ull;
+#pragma unroll
+        for (int j = 0; j < PER_LANE; ++j) best = key[j] > best ? key[j] : best;
+        best = wave_max_u64(best);
+        const int e = (int)(0xffffffffu - (uint32_t)(best & 0xffffffffull));
+        // the owner retires the winner
+#pragma unroll
+        for (int j = 0; j < PER_LANE; ++j)
+            if (lane + 64 * j == e) key[j] = 0ull;
+        // every lane can rebuild the winning logit from the key
+        uint32_t ob = (uint32_t)(best >> 32);
+        uint32_t fb = (ob & 0x80000000u) ? (ob & 0x7fffffffu) : ~ob;
+        float lw = __uint_as_float(fb);
+        if (lane == slot) {
+            my_idx = e;
+            my_w = expf(lw - m) * inv;
+        }
+    }
+    if (lane < k) {
+        topk_idx[(size_t)t * k + lane] = my_idx;
+        topk_w[(size_t)t * k + lane] = my_w;
+    }
+}
+
+// backward of softmax + top-k (indices constant): one wave per token
+template <int PER_LANE>
+__global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict__ logits,
+                                                        const int32_t* __restrict__ topk_idx,
+                                                        const float* __restrict__ dw, int Tn, int E, int k,
+                                                        float* __restrict__ dlogits) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    const float* row = logits + (size_t)t * E;
+    float p[PER_LANE], dp[PER_LANE];
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        int e = lane + 64 * j;
+        p[j] = e < E ? row[e] : -INFINITY;
+        dp[j] = 0.f;
+        m = fmaxf(m, p[j]);
+    }
+    m = wave_max(m);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        p[j] = (lane + 64 * j < E) ? expf(p[j] - m) : 0.f;
+        s += p[j];
+    }
+    s = wave_sum(s);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) p[j] *= inv;
+    for (int slot = 0; slot < k; ++slot) {
+        int e = topk_idx[(size_t)t * k + slot];
+        float g = dw[(size_t)t * k + slot];
+#pragma unroll
+        for (int j = 0; j < PER_LANE; ++j)
+            if (lane + 64 * j == e) dp[j] += g;
+    }
+    float inner = 0.f;
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) inner += p[j] * dp[j];
+    inner = wave_sum(inner);
+#pragma unroll
+    for (int j = 0; j < PER_LANE; ++j) {
+        int e = lane + 64 * j;
+        if (e < E) dlogits[(size_t)t * E + e] = p[j] * (dp[j] - inner);
+    }
+}
+
+// =========================================================================================================
+// backward of the gate projection
+// =========================================================================================================
+// partial[s][i][e] = sum over the s-th slice of tokens of x[t,i] * dlogits[t,e]
+template <typename T>
+__global__ __launch_bounds__(256) void gate_bwd_dw_kernel(const T* __restrict__ x, const float* __restrict__ dl,
+                                                          float* __restrict__ partial, int Tn, int d, int E,
+                                                          int t_per_split) {
+    __shared__ SimtSmem sm;
+    const int i0 = blockIdx.x * kSimtTile, e0 = blockIdx.y * kSimtTile;
+    const int tb = blockIdx.z * t_per_split;
+    int te = tb + t_per_split;
+    te = te < Tn ? te : Tn;
+    const int K = te > tb ? te - tb : 0;
+    float acc[4][4] = {};
+    simt_mainloop<false, true>(
+        acc, K, sm,
+        [&](int mm, int kk) { int i = i0 + mm; return i < d ? to_float(x[(size_t)(tb + kk) * d + i]) : 0.f; },
+        [&](int kk, int nn) { int e = e0 + nn; return e < E ? dl[(size_t)(tb + kk) * E + e] : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float* out = partial + (size_t)blockIdx.z * d * E;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            int i = i0 + ty * 4 + a, e = e0 + tx * 4 + b;
+            if (i < d && e < E) out[(size_t)i * E + e] = acc[a][b];
+        }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gate_bwd_dw_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                                 size_t n, T* __restrict__ dwr) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int sp = 0; sp < splits; ++sp) s += partial[(size_t)sp * n + i];
+    dwr[i] = from_float<T>(s);
+}
+
+// dx_gate[t,i] = sum_e dlogits[t,e] * w[i,e]
+template <typename T>
+__global__ __launch_bounds__(256) void gate_bwd_dx_kernel(const float* __restrict__ dl, const T* __restrict__ w,
+                                                          T* __restrict__ dxg, int Tn, int d, int E) {
+    __shared__ SimtSmem sm;
+    const int t0 = blockIdx.x * kSimtTile, i0 = blockIdx.y * kSimtTile;
+    float acc[4][4] = {};
+    simt_mainloop<true, false>(
+        acc, E, sm,
+        [&](int mm, int kk) { int t = t0 + mm; return t < Tn ? dl[(size_t)t * E + kk] : 0.f; },
+        [&](int kk, int nn) { int i = i0 + nn; return i < d ? to_float(w[(size_t)i * E + kk]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            int t = t0 + ty * 4 + a, i = i0 + tx * 4 + b;
+            if (t < Tn && i < d) dxg[(size_t)t * d + i] = from_float<T>(acc[a][b]);
+        }
+}
+
+template <typename T>
+static int launch_gate_logits(const void* x, const void* w, const float* bias, float* logits, int Tn, int d,
+                              int E, hipStream_t s) {
+    int vec = (E % kGE == 0) && aligned16(w) && ((E * sizeof(T)) % 16 == 0);
+    dim3 grid((Tn + kGT - 1) / kGT, (E + 4 * kGE - 1) / (4 * kGE));
+    XMOE_LAUNCH(K_GATE_LOGITS, s,
+                hipLaunchKernelGGL(gate_logits_kernel<T>, grid, dim3(256), 0, s, (const T*)x, (const T*)w, bias,
+                                   logits, Tn, d, E, vec));
+    return XMOE_OK;
+}
+
+template <typename T>
+static int launch_gate_bwd(const void* x, const void* w, const float* dl, int Tn, int d, int E, void* dwr,
+                           void* dxg, float* partial, hipStream_t s) {
+    const int splits = gate_bwd_splits(Tn);
+    const int tps = (Tn + splits - 1) / splits;
+    dim3 g1((d + kSimtTile - 1) / kSimtTile, (E + kSimtTile - 1) / kSimtTile, splits);
+    XMOE_LAUNCH(K_GATE_BWD_DW, s,
+                hipLaunchKernelGGL(gate_bwd_dw_kernel<T>, g1, dim3(256), 0, s, (const T*)x, dl, partial, Tn, d, E,
+                                   tps));
+    size_t n = (size_t)d * E;
+    XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, s,
+                hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                                   s, partial, splits, n, (T*)dwr));
+    dim3 g2((Tn + kSimtTile - 1) / kSimtTile, (d + kSimtTile - 1) / kSimtTile);
+    XMOE_LAUNCH(K_GATE_BWD_DX, s,
+                hipLaunchKernelGGL(gate_bwd_dx_kernel<T>, g2, dim3(256), 0, s, dl, (const T*)w, (T*)dxg, Tn, d, E));
+    return XMOE_OK;
+}
+
+template <int PL>
+static int launch_route(const float* logits, int Tn, int E, int k, int32_t* idx, float* w, hipStream_t s) {
+    XMOE_LAUNCH(K_ROUTE, s,
+                hipLaunchKernelGGL(route_kernel<PL>, dim3((Tn + 3) / 4), dim3(256), 0, s, logits, Tn, E, k, idx, w));
+    return XMOE_OK;
+}
+template <int PL>
+static int launch_route_bwd(const float* logits, const int32_t* idx, const float* dw, int Tn, int E, int k,
+                            float* dl, hipStream_t s) {
+    XMOE_LAUNCH(K_ROUTE_BWD, s,
+                hipLaunchKernelGGL(route_bwd_kernel<PL>, dim3((Tn + 3) / 4), dim3(256), 0, s, logits, idx, dw, Tn,
+                                   E, k, dl));
+    return XMOE_OK;
+}
+
+}  // namespace xmoe
+
+using namespace xmoe;
+
+extern "C" {
+
+int xmoe_gate_logits(const void* x, const void* w_router, const float* bias, float* logits, int T, int d, int E,
+                     int dt, void* stream) {
+    if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
+    if (T < 0 || d < 1 || E < 1) return XMOE_ERR_INVALID_ARG;
+    if ((long long)T * E >= (1ll << 31) || (long long)T * d >= (1ll << 40)) return XMOE_ERR_INVALID_ARG;
+    if (T == 0) return XMOE_OK;
+    if (!x || !w_router || !logits) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    return dt == XMOE_F32 ? launch_gate_logits<float>(x, w_router, bias, logits, T, d, E, s)
+                          : launch_gate_logits<bf16_t>(x, w_router, bias, logits, T, d, E, s);
+}
+
+int xmoe_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, void* stream) {
+    if (T < 0 || E < 1 || k < 1 || k > E) return XMOE_ERR_INVALID_ARG;
+    if (E > XMOE_MAX_EXPERTS || k > 64) return XMOE_ERR_UNSUPPORTED;
+    if ((long long)T * k >= (1ll << 31) || (long long)T * E >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (T == 0) return XMOE_OK;
+    if (!logits || !topk_idx || !topk_w) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (E <= 64) return launch_route<1>(logits, T, E, k, topk_idx, topk_w, s);
+    if (E <= 128) return launch_route<2>(logits, T, E, k, topk_idx, topk_w, s);
+    if (E <= 256) return launch_route<4>(logits, T, E, k, topk_idx, topk_w, s);
+    return launch_route<8>(logits, T, E, k, topk_idx, topk_w, s);
+}
+
+int xmoe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dw, int T, int E, int k,
+                   float* dlogits, void* stream) {
+    if (T < 0 || E < 1 || k < 1 || k > E) return XMOE_ERR_INVALID_ARG;
+    if (E > XMOE_MAX_EXPERTS || k > 64) return XMOE_ERR_UNSUPPORTED;
+    if ((long long)T * k >= (1ll << 31) || (long long)T * E >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (T == 0) return XMOE_OK;
+    if (!logits || !topk_idx || !dw || !dlogits) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (E <= 64) return launch_route_bwd<1>(logits, topk_idx, dw, T, E, k, dlogits, s);
+    if (E <= 128) return launch_route_bwd<2>(logits, topk_idx, dw, T, E, k, dlogits, s);
+    if (E <= 256) return launch_route_bwd<4>(logits, topk_idx, dw, T, E, k, dlogits, s);
+    return launch_route_bwd<8>(logits, topk_idx, dw, T, E, k, dlogits, s);
+}
+
+int xmoe_gate_logits_bwd(const void* x, const void* w_router, const float* dlogits, int T, int d, int E, int dt,
+                         void* dw_router, void* dx_gate, void* ws, size_t ws_bytes, void* stream) {
+    if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
+    if (T < 1 || d < 1 || E < 1) return XMOE_ERR_INVALID_ARG;
+    if ((long long)T * E >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (!x || !w_router || !dlogits || !dw_router || !dx_gate) return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < gate_bwd_ws_bytes(T, d, E))
+        return XMOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    return dt == XMOE_F32
+               ? launch_gate_bwd<float>(x, w_router, dlogits, T, d, E, dw_router, dx_gate, (float*)ws, s)
+               : launch_gate_bwd<bf16_t>(x, w_router, dlogits, T, d, E, dw_router, dx_gate, (float*)ws, s);
+}
+
+}  // extern "C"

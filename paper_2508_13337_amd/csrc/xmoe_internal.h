@@ -1,0 +1,91 @@
+// Internal helpers shared by the HIP sources of libxmoe (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xmoe.h"
+
+namespace xmoe {
+
+// ---------------------------------------------------------------------------------------------------------
+// kernel ids for the optional event profiler (names returned by xmoe_prof_kernel_name)
+// ---------------------------------------------------------------------------------------------------------
+enum KernelId : int {
+    K_GATE_LOGITS = 0,
+    K_ROUTE,
+    K_ERI_HIST,
+    K_ERI_SCAN,
+    K_ERI_SCATTER,
+    K_DISPATCH,
+    K_COMBINE,
+    K_COMBINE_BWD,
+    K_ROUTE_BWD,
+    K_GATE_BWD_DW,
+    K_GATE_BWD_DW_REDUCE,
+    K_GATE_BWD_DX,
+    K_TILE_MAP,
+    K_FFN_GATEUP_SIMT,
+    K_FFN_DOWN_SIMT,
+    K_FFN_DACT_SIMT,
+    K_FFN_DX_SIMT,
+    K_FFN_WGRAD_SIMT,
+    K_FFN_GATEUP_MFMA,
+    K_FFN_DOWN_MFMA,
+    K_FFN_DACT_MFMA,
+    K_FFN_DX_MFMA,
+    K_FFN_WGRAD_MFMA,
+    K_COUNT
+};
+
+void prof_begin(int kid, hipStream_t s);
+void prof_end(int kid, hipStream_t s);
+
+// Brackets one kernel launch with the profiler hooks and turns a launch error into XMOE_ERR_HIP.
+#define XMOE_LAUNCH(kid, stream, ...)                              \
+    do {                                                           \
+        ::xmoe::prof_begin((kid), (stream));                       \
+        __VA_ARGS__;                                               \
+        ::xmoe::prof_end((kid), (stream));                         \
+        if (hipGetLastError() != hipSuccess) return XMOE_ERR_HIP;  \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------------------
+// element types: float32 and bfloat16 (stored as raw 16-bit patterns)
+// ---------------------------------------------------------------------------------------------------------
+struct bf16_t {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even float32 -> bfloat16 (finite inputs; NaN is kept a NaN)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float v) {
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return bf16_bits_to_float(v.bits); }
+
+template <typename T>
+__device__ __forceinline__ T from_float(float v);
+template <>
+__device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float v) { return bf16_t{float_to_bf16_bits(v)}; }
+
+static inline size_t dtype_size(int dt) { return dt == XMOE_F32 ? 4 : 2; }
+static inline bool dtype_ok(int dt) { return dt == XMOE_F32 || dt == XMOE_BF16; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr int kWave = 64;
+
+// silu(g) = g * sigmoid(g) and its derivative, in float32
+__device__ __forceinline__ float sigmoidf_(float g) { return 1.0f / (1.0f + expf(-g)); }
+__device__ __forceinline__ float siluf_(float g) { return g * sigmoidf_(g); }
+
+}  // namespace xmoe

@@ -1,0 +1,265 @@
+// Row movers of the padding-free MoE layer (paper: Section 4.1.2 and Appendix B.4, gather and scatter kernels):
+// dispatch (gather), combine (weighted gather-reduce instead of a scatter with atomics), and their backward.
+// All of them are HBM-bound: one wave moves one row (or one token's k rows) with 16-byte accesses per lane
+// along the hidden dimension, so every request is fully coalesced whatever the row permutation.
+#include "xmoe_internal.h"
+
+namespace xmoe {
+
+// ---- 8 (bf16) or 4 (float) elements per 16-byte vector --------------------------------------------------
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<float> {
+    static constexpr int N = 4;
+    __device__ static void unpack(const uint4& q, float (&v)[4]) {
+        v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y);
+        v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
+    }
+    __device__ static uint4 pack(const float (&v)[4]) {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
+};
+template <>
+struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static void unpack(const uint4& q, float (&v)[8]) {
+        const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[2 * j] = __uint_as_float(u[j] << 16);
+            v[2 * j + 1] = __uint_as_float(u[j] & 0xffff0000u);
+        }
+    }
+    __device__ static uint4 pack(const float (&v)[8]) {
+        uint32_t u[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            u[j] = (uint32_t)float_to_bf16_bits(v[2 * j]) | ((uint32_t)float_to_bf16_bits(v[2 * j + 1]) << 16);
+        return make_uint4(u[0], u[1], u[2], u[3]);
+    }
+};
+
+// =========================================================================================================
+// dispatch: xd[i,:] = x[token_ids[i],:]     one wave per row
+// =========================================================================================================
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void dispatch_kernel(const T* __restrict__ x, const int32_t* __restrict__ token_ids,
+                                                       int Tn, int B, int d, T* __restrict__ xd) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= B) return;
+    int t = token_ids[row];
+    if ((unsigned)t >= (unsigned)Tn) return;   // never true for index arrays built by this library
+    const T* src = x + (size_t)t * d;
+    T* dst = xd + (size_t)row * d;
+    if (VEC) {
+        const int nv = d / Vec16<T>::N;
+        const uint4* s4 = reinterpret_cast<const uint4*>(src);
+        uint4* d4 = reinterpret_cast<uint4*>(dst);
+        for (int c = lane; c < nv; c += 64) d4[c] = s4[c];
+    } else {
+        for (int c = lane; c < d; c += 64) dst[c] = src[c];
+    }
+}
+
+// =========================================================================================================
+// combine: out[t,:] = sum_j w[t,j] * y[row_of_slot[t*k+j],:] (+ addend) (+ addend2)   one wave per token
+// =========================================================================================================
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, const int32_t* __restrict__ row_of_slot,
+                                                      const float* __restrict__ topk_w, const T* __restrict__ add1,
+                                                      const T* __restrict__ add2, int Tn, int k, int d, int B,
+                                                      T* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    constexpr int N = Vec16<T>::N;
+    if (VEC) {
+        const int nv = d / N;
+        for (int c = lane; c < nv; c += 64) {
+            float acc[N];
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[i] = 0.f;
+            for (int j = 0; j < k; ++j) {
+                const int r = row_of_slot[(size_t)t * k + j];
+                if ((unsigned)r >= (unsigned)B) continue;
+                const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.0f;
+                float v[N];
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(y + (size_t)r * d)[c], v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+            }
+            if (add1) {
+                float v[N];
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(add1 + (size_t)t * d)[c], v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] += v[i];
+            }
+            if (add2) {
+                float v[N];
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(add2 + (size_t)t * d)[c], v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] += v[i];
+            }
+            reinterpret_cast<uint4*>(out + (size_t)t * d)[c] = Vec16<T>::pack(acc);
+        }
+    } else {
+        for (int c = lane; c < d; c += 64) {
+            float acc = 0.f;
+            for (int j = 0; j < k; ++j) {
+                const int r = row_of_slot[(size_t)t * k + j];
+                if ((unsigned)r >= (unsigned)B) continue;
+                const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.0f;
+                acc = fmaf(w, to_float(y[(size_t)r * d + c]), acc);
+            }
+            if (add1) acc += to_float(add1[(size_t)t * d + c]);
+            if (add2) acc += to_float(add2[(size_t)t * d + c]);
+            out[(size_t)t * d + c] = from_float<T>(acc);
+        }
+    }
+}
+
+// =========================================================================================================
+// combine backward: dy[r,:] = w[t,j] * dout[t,:],  dw[t,j] = <dout[t,:], y[r,:]>,  r = row_of_slot[t*k+j]
+// one wave per token; dout[t,:] is read once per slot from cache
+// =========================================================================================================
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ y,
+                                                          const int32_t* __restrict__ row_of_slot,
+                                                          const float* __restrict__ topk_w, int Tn, int k, int d,
+                                                          int B, T* __restrict__ dy, float* __restrict__ dw) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    constexpr int N = Vec16<T>::N;
+    for (int j = 0; j < k; ++j) {
+        const int r = row_of_slot[(size_t)t * k + j];
+        if ((unsigned)r >= (unsigned)B) continue;
+        const float w = topk_w[(size_t)t * k + j];
+        float dot = 0.f;
+        if (VEC) {
+            const int nv = d / N;
+            for (int c = lane; c < nv; c += 64) {
+                float g[N], v[N], o[N];
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(dout + (size_t)t * d)[c], g);
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(y + (size_t)r * d)[c], v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    dot = fmaf(g[i], v[i], dot);
+                    o[i] = w * g[i];
+                }
+                reinterpret_cast<uint4*>(dy + (size_t)r * d)[c] = Vec16<T>::pack(o);
+            }
+        } else {
+            for (int c = lane; c < d; c += 64) {
+                const float g = to_float(dout[(size_t)t * d + c]);
+                dot = fmaf(g, to_float(y[(size_t)r * d + c]), dot);
+                dy[(size_t)r * d + c] = from_float<T>(w * g);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+        if (lane == 0) dw[(size_t)t * k + j] = dot;
+    }
+}
+
+template <typename T>
+static bool can_vec(int d, std::initializer_list<const void*> ptrs) {
+    if (d % Vec16<T>::N != 0) return false;
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+
+template <typename T>
+static int launch_dispatch(const void* x, const int32_t* token_ids, int Tn, int B, int d, void* xd, hipStream_t s) {
+    dim3 grid((B + 3) / 4), block(256);
+    if (can_vec<T>(d, {x, xd}))
+        XMOE_LAUNCH(K_DISPATCH, s, hipLaunchKernelGGL((dispatch_kernel<T, true>), grid, block, 0, s, (const T*)x,
+                                                      token_ids, Tn, B, d, (T*)xd));
+    else
+        XMOE_LAUNCH(K_DISPATCH, s, hipLaunchKernelGGL((dispatch_kernel<T, false>), grid, block, 0, s, (const T*)x,
+                                                      token_ids, Tn, B, d, (T*)xd));
+    return XMOE_OK;
+}
+
+template <typename T>
+static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* a1, const void* a2, int Tn,
+                          int k, int d, void* out, hipStream_t s) {
+    dim3 grid((Tn + 3) / 4), block(256);
+    const int B = Tn * k;
+    if (can_vec<T>(d, {y, a1, a2, out}))
+        XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, true>), grid, block, 0, s, (const T*)y, ros, w,
+                                                     (const T*)a1, (const T*)a2, Tn, k, d, B, (T*)out));
+    else
+        XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, false>), grid, block, 0, s, (const T*)y, ros,
+                                                     w, (const T*)a1, (const T*)a2, Tn, k, d, B, (T*)out));
+    return XMOE_OK;
+}
+
+template <typename T>
+static int launch_combine_bwd(const void* dout, const void* y, const int32_t* ros, const float* w, int Tn, int k,
+                              int d, void* dy, float* dw, hipStream_t s) {
+    dim3 grid((Tn + 3) / 4), block(256);
+    const int B = Tn * k;
+    if (can_vec<T>(d, {dout, y, dy}))
+        XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, true>), grid, block, 0, s,
+                                                         (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw));
+    else
+        XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, false>), grid, block, 0, s,
+                                                         (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw));
+    return XMOE_OK;
+}
+
+static int check_rows_args(int T, int k, int d, int dt) {
+    if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
+    if (T < 0 || k < 1 || d < 1) return XMOE_ERR_INVALID_ARG;
+    if ((long long)T * k >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    return XMOE_OK;
+}
+
+}  // namespace xmoe
+
+using namespace xmoe;
+
+extern "C" {
+
+int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, int dt, void* xd, void* stream) {
+    if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
+    if (T < 0 || B < 0 || d < 1) return XMOE_ERR_INVALID_ARG;
+    if (B == 0) return XMOE_OK;
+    if (T == 0 || !x || !token_ids || !xd) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    return dt == XMOE_F32 ? launch_dispatch<float>(x, token_ids, T, B, d, xd, s)
+                          : launch_dispatch<bf16_t>(x, token_ids, T, B, d, xd, s);
+}
+
+int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* addend,
+                 const void* addend2, int T, int k, int d, int dt, void* out, void* stream) {
+    int st = check_rows_args(T, k, d, dt);
+    if (st != XMOE_OK) return st;
+    if (T == 0) return XMOE_OK;
+    if (!y || !row_of_slot || !out) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    return dt == XMOE_F32 ? launch_combine<float>(y, row_of_slot, topk_w, addend, addend2, T, k, d, out, s)
+                          : launch_combine<bf16_t>(y, row_of_slot, topk_w, addend, addend2, T, k, d, out, s);
+}
+
+int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* addend, const void* addend2, int T,
+                      int k, int d, int dt, void* dx, void* stream) {
+    return xmoe_combine(dxd, row_of_slot, nullptr, addend, addend2, T, k, d, dt, dx, stream);
+}
+
+int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w, int T, int k,
+                     int d, int dt, void* dy, float* dw, void* stream) {
+    int st = check_rows_args(T, k, d, dt);
+    if (st != XMOE_OK) return st;
+    if (T == 0) return XMOE_OK;
+    if (!dout || !y || !row_of_slot || !topk_w || !dy || !dw) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    return dt == XMOE_F32 ? launch_combine_bwd<float>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s)
+                          : launch_combine_bwd<bf16_t>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s);
+}
+
+}  // extern "C"

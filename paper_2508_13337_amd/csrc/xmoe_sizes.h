@@ -1,0 +1,47 @@
+// Host-side workspace layouts of libxmoe (shared by xmoe_workspace_bytes and the entry points).
+#pragma once
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "xmoe_internal.h"
+
+namespace xmoe {
+
+// ----- ERI construction: one histogram row of E counters per chunk of kEriChunk flat entries -----
+constexpr int kEriChunk = 1024;
+static inline int eri_num_chunks(long long B) { return (int)((B + kEriChunk - 1) / kEriChunk); }
+static inline size_t eri_ws_bytes(int T, int E, int k) {
+    long long B = (long long)T * k;
+    return align_up((size_t)(eri_num_chunks(B) > 0 ? eri_num_chunks(B) : 1) * (size_t)E * sizeof(int32_t), 256);
+}
+
+// ----- ragged grouped GEMM: the tile map lists, for every row tile, its expert and first row -----
+// Sized for the smallest row tile any kernel uses (kMinRowTile rows): at most ceil(B/tile) + E tiles.
+constexpr int kMinRowTile = 64;
+static inline int ffn_max_tiles(int B, int E, int tile_rows) { return (B + tile_rows - 1) / tile_rows + E; }
+static inline size_t ffn_tilemap_bytes(int B, int E) {
+    // header of 4 ints (total tiles, ...) followed by (expert, row0) pairs
+    return align_up((size_t)(4 + 2 * (size_t)ffn_max_tiles(B, E, kMinRowTile)) * sizeof(int32_t), 256);
+}
+static inline size_t ffn_act_bytes(int B, int f, int dt) { return align_up((size_t)B * (size_t)f * dtype_size(dt), 256); }
+
+static inline size_t ffn_fwd_ws_bytes(int B, int E, int d, int f, int dt) {
+    (void)d;
+    return ffn_tilemap_bytes(B, E) + ffn_act_bytes(B, f, dt);                 // tile map | A = silu(G)*U
+}
+static inline size_t ffn_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
+    (void)d;
+    return ffn_tilemap_bytes(B, E) + 3 * ffn_act_bytes(B, f, dt);             // tile map | dG | dU | A
+}
+
+// ----- gate projection backward: split-K partial sums of dWr -----
+static inline int gate_bwd_splits(int T) {
+    int s = (T + 255) / 256;
+    return s < 1 ? 1 : (s > 32 ? 32 : s);
+}
+static inline size_t gate_bwd_ws_bytes(int T, int d, int E) {
+    return align_up((size_t)gate_bwd_splits(T) * (size_t)d * (size_t)E * sizeof(float), 256);
+}
+
+}  // namespace xmoe

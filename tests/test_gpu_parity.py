@@ -1,0 +1,295 @@
+"""GPU parity: every C-ABI entry point of libxmoe against the CPU oracle on the same seeded inputs.
+
+Integer outputs (top-k indices, ERI-arrays) and the fixed-order gate logits must match bit for bit; floating
+point outputs must stay within the benchmark definition's tolerance (max relative error 1e-5 for float32
+workloads, 2e-2 for bf16 with float32 accumulation; relative error floored at the tensor's RMS).
+All calls go through the ctypes binding, i.e. through the C ABI."""
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import xmoe_inputs as xi
+from gpu_util import TOL, assert_close, rel_err, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+SMALL = ["tiny_f32", "mini_f32", "odd_f32", "odd_bf16", "mini_bf16", "mini_bf16_skew", "mid_bf16"]
+
+
+def xm():
+    import paper_2508_13337_amd as m
+    return m
+
+
+@functools.lru_cache(maxsize=16)
+def oracle_run(name: str):
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe_layer_fwd(inp, cfg.k)
+    bwd = oracle.moe_layer_bwd(inp, fwd, cfg.k)
+    return cfg, inp, fwd, bwd
+
+
+def i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def bits_equal(t: torch.Tensor, ref32: np.ndarray) -> bool:
+    return np.array_equal(t.cpu().numpy().view(np.uint32), np.ascontiguousarray(ref32, np.float32).view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------------ gating
+@pytest.mark.parametrize("name", SMALL)
+def test_gate_logits_bit_exact(name):
+    cfg = xi.CONFIGS[name]
+    x, w, b = xi.make_x(cfg), xi.make_w_router(cfg), xi.make_gate_bias(cfg)
+    want = oracle.gate_logits_contract(x, w, b)
+    logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
+    xm().xmoe_gate_logits(to_dev(x, cfg.dtype), to_dev(w, cfg.dtype), None if b is None else f32(b), logits)
+    torch.cuda.synchronize()
+    assert bits_equal(logits, want)
+
+
+ROUTE_CASES = [(256, 8, 2, 0, 1.0), (1000, 64, 6, 1, 1.0), (513, 256, 8, 2, 1.0), (77, 7, 3, 3, 1.0),
+               (300, 512, 8, 4, 1.0), (64, 5, 5, 5, 1.0), (10, 1, 1, 6, 1.0), (129, 130, 64, 7, 3.0)]
+
+
+@pytest.mark.parametrize("T,E,k,seed,std", ROUTE_CASES)
+def test_route_bit_exact(T, E, k, seed, std):
+    logits = xi.make_logits(T, E, seed=seed, std=std)
+    if seed % 2 == 1:                       # plant exact ties, including across the k-th / (k+1)-th boundary
+        logits[::3, : max(1, E // 2)] = np.float32(0.25)
+        logits[1::7] = np.float32(-1.5)
+    idx_ref, w_ref, _ = oracle.route(logits, k)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    xm().xmoe_route(f32(logits), k, idx, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert rel_err(to_host(w), w_ref) <= 1e-5
+
+
+# ------------------------------------------------------------------------------------------------ ERI arrays
+def run_build_eri(topk_idx, topk_w, E):
+    T, k = topk_idx.shape
+    B = T * k
+    m = xm()
+    out = {
+        "tokens_per_expert": torch.full((E,), -7, dtype=torch.int32, device="cuda"),
+        "expert_offsets": torch.full((E + 1,), -7, dtype=torch.int32, device="cuda"),
+        "token_ids": torch.full((B,), -7, dtype=torch.int32, device="cuda"),
+        "expert_ids": torch.full((B,), -7, dtype=torch.int32, device="cuda"),
+        "combine_weights": torch.full((B,), -7.0, dtype=torch.float32, device="cuda"),
+        "row_of_slot": torch.full((B,), -7, dtype=torch.int32, device="cuda"),
+    }
+    ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_BUILD_ERI, T, 0, E, k, 0, 0))
+    m.xmoe_build_eri(i32(topk_idx), f32(topk_w), E, out["tokens_per_expert"], out["expert_offsets"],
+                     out["token_ids"], out["expert_ids"], out["combine_weights"], out["row_of_slot"], ws)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_eri(out, ref, topk_w32):
+    for key in ("tokens_per_expert", "expert_offsets", "token_ids", "expert_ids", "row_of_slot"):
+        assert np.array_equal(out[key].cpu().numpy(), ref[key]), key
+    # combine weights are copies of the float32 top-k weights that went in
+    want = np.asarray(topk_w32, np.float32).reshape(-1)[np.argsort(ref["row_of_slot"], kind="stable")]
+    assert bits_equal(out["combine_weights"], want)
+
+
+ERI_CASES = [(256, 8, 2, 0, 0.0), (1000, 64, 6, 1, 0.0), (4099, 64, 6, 2, 2.0), (77, 7, 3, 3, 0.0),
+             (700, 512, 8, 4, 0.0), (10, 1, 1, 5, 0.0), (2048, 256, 8, 6, 3.0), (1, 4, 4, 7, 0.0),
+             (8192, 64, 6, 8, 0.0)]
+
+
+@pytest.mark.parametrize("T,E,k,seed,skew", ERI_CASES)
+def test_build_eri_bit_exact(T, E, k, seed, skew):
+    logits = xi.make_logits(T, E, seed=seed)
+    if skew:
+        logits = logits - np.float32(skew) * np.log(np.arange(1, E + 1, dtype=np.float32))[None, :]
+        logits[:, E // 2] = -1e30          # a forced empty expert
+    idx, w, _ = oracle.route(logits, k)
+    w32 = w.astype(np.float32)
+    ref = oracle.build_eri(idx, w32, E)
+    out = run_build_eri(idx, w32, E)
+    check_eri(out, ref, w32)
+
+
+# ------------------------------------------------------------------------------------------------ row movers
+@pytest.mark.parametrize("name", SMALL)
+def test_dispatch_combine_and_backward(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    m = xm()
+    dt = cfg.dtype
+    eri = fwd["eri"]
+    x = to_dev(inp["x"], dt)
+    xd = torch.empty((cfg.B, cfg.d), dtype=x.dtype, device="cuda")
+    m.xmoe_dispatch(x, i32(eri["token_ids"]), xd)
+    torch.cuda.synchronize()
+    assert torch.equal(xd, x[torch.from_numpy(eri["token_ids"]).long().cuda()])          # bit copy
+    assert np.array_equal(to_host(xd), fwd["Xd"])
+
+    # combine on the oracle's Y (rounded to storage), with and without an addend
+    Y = xi.round_to_storage(fwd["Y"].astype(np.float32), dt)
+    ros, tw = i32(eri["row_of_slot"]), f32(fwd["topk_w"])
+    out = torch.empty((cfg.T, cfg.d), dtype=x.dtype, device="cuda")
+    m.xmoe_combine(to_dev(Y, dt), ros, tw, None, None, cfg.k, out)
+    want = oracle.combine(Y.astype(np.float64), eri["token_ids"], eri["combine_weights"].astype(np.float32), cfg.T)
+    assert_close(to_host(out), want, dt, "combine", scale=0.5)
+    add = xi.round_to_storage(inp["dout"], dt)
+    m.xmoe_combine(to_dev(Y, dt), ros, tw, to_dev(add, dt), to_dev(inp["x"], dt), cfg.k, out)
+    assert_close(to_host(out), want + add + inp["x"], dt, "combine+addends", scale=0.5)
+
+    # combine backward
+    dy = torch.empty((cfg.B, cfg.d), dtype=x.dtype, device="cuda")
+    dw = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    m.xmoe_combine_bwd(to_dev(inp["dout"], dt), to_dev(Y, dt), ros, tw, dy, dw)
+    dY_ref, dw_ref = oracle.combine_bwd(inp["dout"], Y.astype(np.float64), eri["token_ids"],
+                                        fwd["topk_w"].astype(np.float32).reshape(-1)[
+                                            np.argsort(eri["row_of_slot"], kind="stable")].astype(np.float64),
+                                        eri["row_of_slot"], cfg.k)
+    assert_close(to_host(dy), dY_ref, dt, "combine_bwd dy", scale=0.5)
+    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw", scale=2.0)
+
+    # dispatch backward on the oracle's dXd
+    dXd = xi.round_to_storage(bwd["dXd"].astype(np.float32), dt)
+    dx = torch.empty((cfg.T, cfg.d), dtype=x.dtype, device="cuda")
+    m.xmoe_dispatch_bwd(to_dev(dXd, dt), ros, None, None, cfg.k, dx)
+    assert_close(to_host(dx), oracle.dispatch_bwd(dXd.astype(np.float64), eri["row_of_slot"], cfg.T, cfg.k), dt,
+                 "dispatch_bwd", scale=0.5)
+
+
+# ------------------------------------------------------------------------------------------------ gating backward
+@pytest.mark.parametrize("name", SMALL)
+def test_route_bwd_and_gate_bwd(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    m = xm()
+    dt = cfg.dtype
+    dl = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
+    dw32 = bwd["dw"].astype(np.float32)
+    m.xmoe_route_bwd(f32(fwd["logits"]), i32(fwd["topk_idx"]), f32(dw32), dl)
+    want = oracle.route_bwd(fwd["p"], fwd["topk_idx"], dw32.astype(np.float64))
+    assert_close(to_host(dl), want, "f32", "route_bwd dlogits", scale=2.0)
+
+    dl32 = bwd["dlogits"].astype(np.float32)
+    dwr = torch.empty((cfg.d, cfg.E), dtype=torch_dtype(dt), device="cuda")
+    dxg = torch.empty((cfg.T, cfg.d), dtype=torch_dtype(dt), device="cuda")
+    ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_GATE_BWD, cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, 0))
+    m.xmoe_gate_logits_bwd(to_dev(inp["x"], dt), to_dev(inp["w_router"], dt), f32(dl32), dwr, dxg, ws)
+    x64, w64 = np.asarray(inp["x"], np.float64), np.asarray(inp["w_router"], np.float64)
+    assert_close(to_host(dwr), x64.T @ dl32.astype(np.float64), dt, "gate_bwd dw_router")
+    assert_close(to_host(dxg), dl32.astype(np.float64) @ w64.T, dt, "gate_bwd dx_gate")
+
+
+# ------------------------------------------------------------------------------------------------ expert MLP
+@pytest.mark.parametrize("name", SMALL)
+def test_expert_ffn_fwd_bwd(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    m = xm()
+    dt = cfg.dtype
+    tdt = torch_dtype(dt)
+    code = m.dtype_code(tdt)
+    eri = fwd["eri"]
+    B, d, f, E = cfg.B, cfg.d, cfg.f, cfg.E
+    xd = to_dev(fwd["Xd"], dt)
+    off = i32(eri["expert_offsets"])
+    wg, wu, wd = (to_dev(inp[k_], dt) for k_ in ("wg", "wu", "wd"))
+    g = torch.empty((B, f), dtype=tdt, device="cuda")
+    u = torch.empty((B, f), dtype=tdt, device="cuda")
+    y = torch.empty((B, d), dtype=tdt, device="cuda")
+    ws = m.alloc_workspace(max(m.xmoe_workspace_bytes(m.WS_FFN_FWD, B, d, E, cfg.k, f, code),
+                               m.xmoe_workspace_bytes(m.WS_FFN_BWD, B, d, E, cfg.k, f, code)))
+    m.xmoe_expert_ffn_fwd(xd, off, wg, wu, wd, g, u, y, ws)
+    assert_close(to_host(g), fwd["G"], dt, "G")
+    assert_close(to_host(u), fwd["U"], dt, "U")
+    assert_close(to_host(y), fwd["Y"], dt, "Y")
+
+    # backward from the oracle's saved activations and dY (rounded to storage)
+    G = xi.round_to_storage(fwd["G"].astype(np.float32), dt)
+    U = xi.round_to_storage(fwd["U"].astype(np.float32), dt)
+    dY = xi.round_to_storage(bwd["dY"].astype(np.float32), dt)
+    ref = oracle.expert_ffn_bwd(fwd["Xd"], G.astype(np.float64), U.astype(np.float64), dY.astype(np.float64),
+                                eri["expert_offsets"], inp["wg"], inp["wu"], inp["wd"])
+    dxd = torch.empty((B, d), dtype=tdt, device="cuda")
+    dwg = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
+    dwu = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
+    dwd = torch.full((E, f, d), 3.0, dtype=tdt, device="cuda")
+    m.xmoe_expert_ffn_bwd(xd, to_dev(G, dt), to_dev(U, dt), to_dev(dY, dt), off, wg, wu, wd, dxd, dwg, dwu, dwd, ws)
+    for got, want, what in zip((dxd, dwg, dwu, dwd), ref, ("dXd", "dWg", "dWu", "dWd")):
+        assert_close(to_host(got), want, dt, what)
+    tpe = eri["tokens_per_expert"]
+    for e in range(E):
+        if tpe[e] == 0:
+            assert not dwg[e].any() and not dwu[e].any() and not dwd[e].any()
+
+
+# ------------------------------------------------------------------------------------------------ whole layer
+def run_layer(cfg, inp):
+    m = xm()
+    dt = cfg.dtype
+    tdt = torch_dtype(dt)
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
+    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"]),
+         "wg": to_dev(inp["wg"], dt), "wu": to_dev(inp["wu"], dt), "wd": to_dev(inp["wd"], dt)}
+    grads = {"dw_router": torch.empty_like(w["w_router"]), "dwg": torch.empty_like(w["wg"]),
+             "dwu": torch.empty_like(w["wu"]), "dwd": torch.empty_like(w["wd"])}
+    if cfg.E_s > 0:
+        for k_ in ("wg", "wu", "wd"):
+            w["shared_" + k_] = m.fuse_shared(to_dev(inp["shared_" + k_], dt), k_)
+            grads["dshared_" + k_] = torch.empty_like(w["shared_" + k_])
+    x, dout = to_dev(inp["x"], dt), to_dev(inp["dout"], dt)
+    out = layer.forward(x, w)
+    dx = layer.backward(x, w, dout, grads)
+    torch.cuda.synchronize()
+    return layer, out, dx, grads
+
+
+def check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads):
+    m = xm()
+    dt = cfg.dtype
+    eri = fwd["eri"]
+    assert bits_equal(layer.logits, fwd["logits"])
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), fwd["topk_idx"])
+    for key in ("tokens_per_expert", "expert_offsets", "token_ids", "expert_ids", "row_of_slot"):
+        assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
+    assert rel_err(to_host(layer.topk_w), fwd["topk_w"]) <= 1e-5
+    assert rel_err(to_host(layer.combine_weights), eri["combine_weights"]) <= 1e-5
+    errs = {}
+    errs["out"] = assert_close(to_host(out), fwd["out"], dt, "out")
+    errs["Y"] = assert_close(to_host(layer.y), fwd["Y"], dt, "Y")
+    errs["dx"] = assert_close(to_host(dx), bwd["dx"], dt, "dx")
+    errs["dw_router"] = assert_close(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router")
+    for k_ in ("dwg", "dwu", "dwd"):
+        errs[k_] = assert_close(to_host(grads[k_]), bwd[k_], dt, k_)
+    if cfg.E_s > 0:
+        for k_ in ("wg", "wu", "wd"):
+            got = m.unfuse_shared_grad(grads["dshared_" + k_], k_, cfg.E_s)
+            errs["dshared_" + k_] = assert_close(to_host(got), bwd["dshared_" + k_], dt, "dshared_" + k_)
+    return errs
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_layer_fwd_bwd(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    layer, out, dx, grads = run_layer(cfg, inp)
+    errs = check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads)
+    print(name, {k_: f"{v:.2e}" for k_, v in errs.items()})
+
+
+def test_layer_is_reproducible_run_to_run():
+    """No atomics anywhere on the path: two runs must agree bit for bit."""
+    cfg, inp, _, _ = oracle_run("mini_bf16_skew")
+    _, out1, dx1, g1 = run_layer(cfg, inp)
+    out1, dx1 = out1.clone(), dx1.clone()
+    g1 = {k_: v.clone() for k_, v in g1.items()}
+    _, out2, dx2, g2 = run_layer(cfg, inp)
+    assert torch.equal(out1, out2) and torch.equal(dx1, dx2)
+    for k_ in g1:
+        assert torch.equal(g1[k_], g2[k_]), k_
