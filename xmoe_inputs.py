@@ -147,9 +147,24 @@ def make_expert_weight(cfg: MoEConfig, which: str, e: int) -> np.ndarray:
     return _normal(cfg.seed, which, e, shape, cfg.w_std, cfg.dtype)
 
 
+def iter_expert_weights(cfg: MoEConfig, which: str, batch: int = 16):
+    """Yields (e, matrix) for every routed expert in order, drawing `batch` experts at a time on host threads
+    (numpy's generators release the GIL), so that large workloads never hold a whole tensor on the host."""
+    import concurrent.futures
+    with concurrent.futures.ThreadPoolExecutor(max_workers=batch) as pool:
+        for e0 in range(0, cfg.E, batch):
+            es = list(range(e0, min(cfg.E, e0 + batch)))
+            for e, a in zip(es, pool.map(lambda e: make_expert_weight(cfg, which, e), es)):
+                yield e, a
+
+
 def make_expert_weights(cfg: MoEConfig, which: str) -> np.ndarray:
     """All routed experts' matrices stacked: [E, d, f] or [E, f, d]."""
-    return np.stack([make_expert_weight(cfg, which, e) for e in range(cfg.E)])
+    shape = (cfg.d, cfg.f) if which in ("wg", "wu") else (cfg.f, cfg.d)
+    out = np.empty((cfg.E,) + shape, dtype=np.float32)
+    for e, a in iter_expert_weights(cfg, which):
+        out[e] = a
+    return out
 
 
 def make_shared_weight(cfg: MoEConfig, which: str, s: int) -> np.ndarray:
