@@ -1,0 +1,164 @@
+"""GPU parity at the benchmark definition's full sizes, in the launch configuration bench.py times.
+
+Configs 2 and 3 (DeepSeek-MoE-16B-shaped layer, uniform and Zipf-skewed routing) are compared with the whole
+oracle.  Config 4 (large fine-grained layer, 22.6 GB of expert weights) and config 5 (long-sequence sweep) are too
+big for the float64 oracle to redo in full, so there every integer array is compared in full and the floating
+point tensors on a seeded sample the oracle computes one piece at a time: whole expert segments (forward
+activations, dXd and that expert's three weight gradients) and whole output rows (out and dx of sampled tokens,
+which pull in every expert those tokens were routed to, the shared experts and the gate path).  The gate weights'
+gradient needs every token's dlogits and is only checked in the whole-oracle tests."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import xmoe_inputs as xi
+from gpu_util import assert_close_chain, rel_err, to_dev, to_host, torch_dtype
+from test_gpu_parity import bits_equal, check_layer, f32, xm
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def build_gpu_layer(cfg):
+    """Inputs generated expert by expert (never a second host copy of the big tensors) and one fwd+bwd pass."""
+    m = xm()
+    dt = cfg.dtype
+    tdt = torch_dtype(dt)
+    w = {"w_router": to_dev(xi.make_w_router(cfg), dt)}
+    bias = xi.make_gate_bias(cfg)
+    w["bias"] = None if bias is None else f32(bias)
+    for key in ("wg", "wu", "wd"):
+        shape = (cfg.E, cfg.d, cfg.f) if key != "wd" else (cfg.E, cfg.f, cfg.d)
+        w[key] = torch.empty(shape, dtype=tdt, device="cuda")
+        for e, a in xi.iter_expert_weights(cfg, key):
+            w[key][e].copy_(to_dev(a, dt))
+        if cfg.E_s:
+            w["shared_" + key] = m.fuse_shared(to_dev(xi.make_shared_weights(cfg, key), dt), key)
+    grads = {"dw_router": torch.empty_like(w["w_router"])}
+    for key in ("wg", "wu", "wd"):
+        grads["d" + key] = torch.empty_like(w[key])
+        if cfg.E_s:
+            grads["dshared_" + key] = torch.empty_like(w["shared_" + key])
+    x_np, dout_np = xi.make_x(cfg), xi.make_dout(cfg)
+    x, dout = to_dev(x_np, dt), to_dev(dout_np, dt)
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
+    out = layer.forward(x, w)
+    dx = layer.backward(x, w, dout, grads)
+    torch.cuda.synchronize()
+    return layer, out, dx, grads, x_np, dout_np, bias
+
+
+@pytest.mark.parametrize("name", ["dsmoe16b", "dsmoe16b_skew"])
+def test_full_size_whole_oracle(name):
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe_layer_fwd(inp, cfg.k)
+    bwd = oracle.moe_layer_bwd(inp, fwd, cfg.k)
+    layer, out, dx, grads, _, _, _ = build_gpu_layer(cfg)
+    errs = check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads)
+    print(name, {k_: f"{v[0]:.2e}/{v[1]:.2e}" for k_, v in errs.items()})
+    tpe = fwd["eri"]["tokens_per_expert"]
+    if cfg.skew_alpha:
+        assert tpe.max() >= 9 * tpe.mean() and (tpe == 0).any()
+
+
+class ExpertWeights:
+    """Regenerates single experts' matrices on demand (float64), keeping a few in memory."""
+
+    def __init__(self, cfg, keep=12):
+        self.cfg, self.keep, self.cache = cfg, keep, {}
+
+    def get(self, e):
+        if e not in self.cache:
+            if len(self.cache) >= self.keep:
+                self.cache.pop(next(iter(self.cache)))
+            self.cache[e] = tuple(xi.make_expert_weight(self.cfg, k_, e).astype(np.float64)
+                                  for k_ in ("wg", "wu", "wd"))
+        return self.cache[e]
+
+
+def verify_sampled(cfg, n_experts, n_tokens, seed=0):
+    dt = cfg.dtype
+    layer, out, dx, grads, x_np, dout_np, bias = build_gpu_layer(cfg)
+    k, E, T = cfg.k, cfg.E, cfg.T
+    wr = xi.make_w_router(cfg)
+
+    # ---- integers, in full
+    logits = oracle.gate_logits_contract(x_np, wr, bias)
+    assert bits_equal(layer.logits, logits)
+    topk_idx, topk_w, p = oracle.route(logits, k)
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), topk_idx)
+    eri = oracle.build_eri(topk_idx, topk_w, E)
+    for key in ("tokens_per_expert", "expert_offsets", "token_ids", "expert_ids", "row_of_slot"):
+        assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
+    assert rel_err(to_host(layer.topk_w), topk_w) <= 1e-5
+    off, tok, ros, cw = eri["expert_offsets"], eri["token_ids"], eri["row_of_slot"], eri["combine_weights"]
+
+    x64, dout64 = x_np.astype(np.float64), dout_np.astype(np.float64)
+    ew = ExpertWeights(cfg)
+    rng = np.random.default_rng(seed)
+    tpe = eri["tokens_per_expert"]
+    nonempty = np.flatnonzero(tpe > 0)
+    chosen = {int(nonempty[np.argmax(tpe[nonempty])]), int(nonempty[np.argmin(tpe[nonempty])])}
+    chosen |= set(int(e) for e in rng.choice(nonempty, size=min(n_experts, len(nonempty)), replace=False))
+    chosen = sorted(chosen)[:max(n_experts, 2)]
+
+    # ---- whole expert segments
+    for e in chosen:
+        lo, hi = int(off[e]), int(off[e + 1])
+        wg, wu, wd = ew.get(e)
+        Xd = x64[tok[lo:hi]]
+        assert np.array_equal(to_host(layer.xd[lo:hi]), Xd)
+        Y, G, U = oracle.swiglu_ffn(Xd, wg, wu, wd)
+        assert_close_chain(to_host(layer.g[lo:hi]), G, dt, f"G e{e}")
+        assert_close_chain(to_host(layer.u[lo:hi]), U, dt, f"U e{e}")
+        assert_close_chain(to_host(layer.y[lo:hi]), Y, dt, f"Y e{e}")
+        dY = cw[lo:hi, None] * dout64[tok[lo:hi]]
+        dXd, dWg, dWu, dWd = oracle.swiglu_ffn_bwd(Xd, G, U, dY, wg, wu, wd)
+        assert_close_chain(to_host(layer.dxd[lo:hi]), dXd, dt, f"dXd e{e}")
+        assert_close_chain(to_host(grads["dwg"][e]), dWg, dt, f"dWg e{e}", floor="row")
+        assert_close_chain(to_host(grads["dwu"][e]), dWu, dt, f"dWu e{e}", floor="row")
+        assert_close_chain(to_host(grads["dwd"][e]), dWd, dt, f"dWd e{e}", floor="row")
+    for e in np.flatnonzero(tpe == 0):
+        assert not grads["dwg"][e].any() and not grads["dwu"][e].any() and not grads["dwd"][e].any()
+
+    # ---- whole output rows of sampled tokens: out[t] and dx[t]
+    toks = np.sort(rng.choice(T, size=min(n_tokens, T), replace=False))
+    sh = [tuple(xi.make_shared_weight(cfg, k_, s).astype(np.float64) for k_ in ("wg", "wu", "wd"))
+          for s in range(cfg.E_s)]
+    want_out = np.zeros((len(toks), cfg.d))
+    want_dx = np.zeros((len(toks), cfg.d))
+    # group the (token, slot) pairs by expert so that each expert's weights are generated once
+    pairs = sorted((int(topk_idx[t, j]), ti, j) for ti, t in enumerate(toks) for j in range(k))
+    ys = np.zeros((len(toks), k, cfg.d))
+    for e, ti, j in pairs:
+        wg, wu, wd = ew.get(e)
+        t = toks[ti]
+        y, g, u = oracle.swiglu_ffn(x64[t:t + 1], wg, wu, wd)
+        ys[ti, j] = y[0]
+        want_out[ti] += topk_w[t, j] * y[0]
+        dxr, _, _, _ = oracle.swiglu_ffn_bwd(x64[t:t + 1], g, u, topk_w[t, j] * dout64[t:t + 1], wg, wu, wd)
+        want_dx[ti] += dxr[0]
+    for wg, wu, wd in sh:
+        y, g, u = oracle.swiglu_ffn(x64[toks], wg, wu, wd)
+        want_out += y
+        want_dx += oracle.swiglu_ffn_bwd(x64[toks], g, u, dout64[toks], wg, wu, wd)[0]
+    dw = np.einsum("td,tkd->tk", dout64[toks], ys)
+    dlogits = oracle.route_bwd(p[toks], topk_idx[toks], dw)
+    want_dx += dlogits @ wr.astype(np.float64).T
+    tsel = torch.from_numpy(toks).long().cuda()
+    e_out = assert_close_chain(to_host(out[tsel]), want_out, dt, "out rows")
+    e_dx = assert_close_chain(to_host(dx[tsel]), want_dx, dt, "dx rows")
+    print(cfg.name, "experts", chosen, "tokens", len(toks), "out", e_out, "dx", e_dx)
+    # activation footprint held for backward (Xd, Y, G, U) equals the closed form s*T*k*(2d+2f)
+    held = sum(t_.numel() * t_.element_size() for t_ in (layer.xd, layer.y, layer.g, layer.u))
+    assert held == oracle.activation_bytes(T, k, cfg.d, cfg.f, 2 if dt == "bf16" else 4)
+
+
+def test_full_size_large_sampled():
+    verify_sampled(xi.CONFIGS["large"], n_experts=8, n_tokens=12)
+
+
+@pytest.mark.parametrize("T", [16384, 32768, 65536])
+def test_full_size_longseq_sampled(T):
+    verify_sampled(xi.CONFIGS["longseq"].with_T(T), n_experts=8, n_tokens=1024)

@@ -268,11 +268,11 @@ def check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads):
     errs["dw_router"] = assert_close_chain(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router", floor="tensor",
                                            norm="tensor")
     for k_ in ("dwg", "dwu", "dwd"):
-        errs[k_] = assert_close_chain(to_host(grads[k_]), bwd[k_], dt, k_, floor="expert")
+        errs[k_] = assert_close_chain(to_host(grads[k_]), bwd[k_], dt, k_, floor="row")
     if cfg.E_s > 0:
         for k_ in ("wg", "wu", "wd"):
             got = m.unfuse_shared_grad(grads["dshared_" + k_], k_, cfg.E_s)
-            errs["dshared_" + k_] = assert_close_chain(to_host(got), bwd["dshared_" + k_], dt, "dshared_" + k_, floor="expert")
+            errs["dshared_" + k_] = assert_close_chain(to_host(got), bwd["dshared_" + k_], dt, "dshared_" + k_, floor="row")
     return errs
 
 
