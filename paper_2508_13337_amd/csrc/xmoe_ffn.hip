@@ -1,18 +1,24 @@
 // Entry points of the expert MLP (paper: Listing 1 mlp(); Appendix B.4): argument checks, workspace carve-up,
 // and the choice between the bf16 MFMA kernels and the float32-ALU kernels.
 #include <stdlib.h>
+#include <string.h>
 
 #include "xmoe_ffn.h"
 
 namespace xmoe {
 
-static int g_force_simt = -1;
-static bool force_simt() {
-    if (g_force_simt < 0) {
-        const char* v = getenv("XMOE_FFN_FORCE_SIMT");
-        g_force_simt = (v && v[0] == '1') ? 1 : 0;
+// Kernel family for the expert MLP: the environment variable XMOE_FFN_FAMILY = dma | reg | simt caps the choice
+// (for tests and comparisons); by default the best family that supports the shapes is taken.
+enum Family { FAM_DMA = 0, FAM_REG = 1, FAM_SIMT = 2 };
+static int g_family_cap = -1;
+static int family_cap() {
+    if (g_family_cap < 0) {
+        const char* v = getenv("XMOE_FFN_FAMILY");
+        g_family_cap = FAM_DMA;
+        if (v && strcmp(v, "reg") == 0) g_family_cap = FAM_REG;
+        if (v && strcmp(v, "simt") == 0) g_family_cap = FAM_SIMT;
     }
-    return g_force_simt == 1;
+    return g_family_cap;
 }
 
 static int check_common(int B, int E, int d, int f, int dt) {
@@ -49,7 +55,8 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, in
     p += ffn_tilemap_bytes(B, E);
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
-    if (!force_simt() && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
+    if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_fwd_dma(a, s);
+    if (family_cap() <= FAM_REG && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
     return ffn_fwd_simt(a, s);
 }
 
@@ -79,7 +86,8 @@ int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, 
     p += ffn_act_bytes(B, f, dt);
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
-    if (!force_simt() && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
+    if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
+    if (family_cap() <= FAM_REG && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
     return ffn_bwd_simt(a, s);
 }
 

@@ -1,0 +1,693 @@
+// Expert MLP over ragged segments (paper: Listing 1 mlp(); Appendix B.4 "Sequential GeMM") on the gfx950 matrix
+// cores, with operand tiles streamed straight from global memory into LDS (global_load_lds_dwordx4) through a
+// 4-stage ring, so that no tile ever passes through registers and three K-steps of loads are always in flight.
+//
+//   block = 512 threads = 8 waves (2 x 4); block tile 256 x 256, K stepped by 32; wave tile 128 x 64 =
+//   4 x 2 tiles of v_mfma_f32_32x32x16_bf16 with float32 accumulators; one block per CU (128 KiB of LDS).
+//
+// Two LDS tile layouts, chosen by which index of the operand is contiguous in memory:
+//   K-contiguous operand ("row" tile): [256 rows][32 k], 64-byte rows; fragments are read with ds_read_b128.
+//   K-strided operand    ("col" tile): [32 k][256 n], 512-byte rows, kept as it lies in memory; fragments are read
+//                                       with the transposing LDS read ds_read_b64_tr_b16, so neither the weights
+//                                       stored "in x out" nor the operands of the weight-gradient GEMMs are ever
+//                                       transposed by ALU code.
+// A direct-to-LDS load writes lane l's 16 bytes at (wave-uniform base) + 16*l, so the bank-conflict-avoiding XOR
+// swizzle is applied on the global-address side (which 16-byte chunk a lane fetches) and undone by the fragment
+// reads.  Rows / columns / k-indices outside the operand fetch a 16-byte block of zeros instead, so a ragged tail
+// costs no branch and no padded row ever exists in HBM.
+//
+// The MFMA is issued with the operands swapped (B fragment first), so a lane ends up with 4 consecutive output
+// columns of one row; results are rounded to bf16, staged through LDS and written with row-contiguous stores.
+#include "xmoe_ffn.h"
+
+namespace xmoe {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int TM = 256, TN = 256, TK = 32;
+constexpr int kStages = 4;
+constexpr int kOpBytes = 256 * TK * 2;          // one operand tile of one stage: 16 KiB
+constexpr int kStageBytes = 2 * kOpBytes;       // A + B
+constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
+constexpr int kLoadsPerTile = 4;                // per thread: 2 for A, 2 for B
+constexpr int kNumXcd = 8;
+
+__device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt in bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// operand descriptions
+// ---------------------------------------------------------------------------------------------------------
+// row tile: element (row, k) at p + row*ld + k; rows >= rows_valid read as zero.
+// col tile: element (k, col) at p_lo + k*ld + col for col < 128 and p_hi + k*ld + (col-128) for col >= 128;
+//           columns >= n_lo (resp. n_hi) of a half and k >= k_valid read as zero.
+struct Operand {
+    const bf16_t* p_lo;
+    const bf16_t* p_hi;
+    long ld;
+    int n_lo, n_hi;    // row tile: n_lo = valid rows (0..256); col tile: valid columns per 128-wide half
+    int k_valid;       // col tile only
+};
+
+// per-thread state of the two direct-to-LDS loads an operand needs per stage.  TWO: the K range is the
+// concatenation of two GEMMs (k-tiles [0, nk1) come from operand set 1, [nk1, nk) from set 2).
+template <bool COL, bool TWO>
+struct Loader {
+    const bf16_t* g[TWO ? 2 : 1][2];   // global address of this lane's 16 bytes for k-tile 0 (or kZero16)
+    long step[2];         // elements to advance per k-tile (0 for lanes that fetch zeros)
+    int krow[2];          // col tile: k index inside the tile, for the k_valid test
+    int lds_off[2];       // wave-uniform byte offset of the instruction's 1 KiB destination inside the tile
+    int k_valid;
+    int nk1, nk;          // k-tiles of set 1, total k-tiles; tiles past the end fetch zeros
+
+    __device__ __forceinline__ void init(const Operand& o, const Operand& o2, int num_k1, int num_k) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        k_valid = o.k_valid;
+        nk1 = num_k1;
+        nk = num_k;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (!COL) {
+                const int row = wave * 32 + i * 16 + (lane >> 2);
+                const int c = (lane & 3) ^ ((row >> 2) & 3);
+                const bool ok = row < o.n_lo;
+                const bf16_t* z = reinterpret_cast<const bf16_t*>(kZero16);
+                g[0][i] = ok ? o.p_lo + (long)row * o.ld + c * 8 : z;
+                if (TWO) g[TWO ? 1 : 0][i] = ok ? o2.p_lo + (long)row * o2.ld + c * 8 : z;
+                step[i] = ok ? TK : 0;
+                krow[i] = 0;
+                lds_off[i] = (wave * 32 + i * 16) * 64;
+            } else {
+                const int kr = wave * 4 + i * 2 + (lane >> 5);
+                const int c = (lane & 31) ^ ((kr & 3) << 2);
+                const int col = (c & 15) * 8;
+                const bool hi = c >= 16;
+                const bool ok = col < (hi ? o.n_hi : o.n_lo);
+                g[0][i] = ok ? (hi ? o.p_hi : o.p_lo) + (long)kr * o.ld + col : reinterpret_cast<const bf16_t*>(kZero16);
+                step[i] = ok ? (long)TK * o.ld : 0;
+                krow[i] = ok ? kr : (1 << 30);
+                lds_off[i] = (wave * 4 + i * 2) * 512;
+            }
+        }
+    }
+
+    // issues the two loads of k-tile kt into `tile` (LDS address of this operand's tile in the target stage)
+    __device__ __forceinline__ void issue(char* tile, int kt) const {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const bf16_t* p;
+            if (TWO) {
+                p = kt < nk1 ? g[0][i] + (long)kt * step[i] : g[TWO ? 1 : 0][i] + (long)(kt - nk1) * step[i];
+            } else {
+                p = g[0][i] + (long)kt * step[i];
+            }
+            if (COL) {
+                if (kt * TK + krow[i] >= k_valid) p = reinterpret_cast<const bf16_t*>(kZero16);
+            } else {
+                if (kt >= nk) p = reinterpret_cast<const bf16_t*>(kZero16);
+            }
+            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, 0);
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------------------------------------
+// fragment reads: 8 bf16 (k = 16*ks + 8*(lane/32) + 0..7) of row / column (base + lane%32)
+// ---------------------------------------------------------------------------------------------------------
+template <bool COL>
+__device__ __forceinline__ bf16x8_t read_frag(const char* tile, int base, int ks) {
+    const int lane = threadIdx.x & 63;
+    if (!COL) {
+        const int r = base + (lane & 31);
+        const int chunk = 2 * ks + (lane >> 5);
+        return *reinterpret_cast<const bf16x8_t*>(tile + r * 64 + ((chunk ^ ((r >> 2) & 3)) << 4));
+    } else {
+        // 16-lane groups: group G covers columns base + 16*(G%2) .. +15 and k = 16*ks + 8*(G/2) .. +7; inside a
+        // group, lane s addresses 4 consecutive columns (s%4) of k-row (s/4); the transposing read hands every
+        // lane one column with 4 consecutive k.
+        const int G = lane >> 4, s = lane & 15;
+        const int col = base + 16 * (G & 1) + 4 * (s & 3);
+        const int k0 = 16 * ks + 8 * (G >> 1) + (s >> 2);
+        s16x4_t h[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int kr = k0 + 4 * q;
+            const char* a = tile + kr * 512 + ((((col >> 3) ^ ((kr & 3) << 2))) << 4) + (col & 7) * 2;
+            h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)LDS_PTR(a));
+        }
+        s16x8_t v = {h[0][0], h[0][1], h[0][2], h[0][3], h[1][0], h[1][1], h[1][2], h[1][3]};
+        return __builtin_bit_cast(bf16x8_t, v);
+    }
+}
+
+// column base (inside the 256-wide B tile) of the wave's ni-th 32-column block.  Plain tiles: 64 contiguous
+// columns per wave.  Dual tiles (two matrices side by side, 128 columns each): the same 32 columns of both.
+template <bool DUAL>
+__device__ __forceinline__ int b_col(int wn, int ni) { return DUAL ? ni * 128 + wn * 32 : wn * 64 + ni * 32; }
+
+// acc[mi][ni][v] holds C(row = wm*128 + mi*32 + lane%32, col = b_col(wn, ni) + 8*(v/4) + 4*(lane/32) + v%4)
+template <bool A_COL, bool B_COL, bool DUAL>
+__device__ __forceinline__ void stage_mma(f32x16_t (&acc)[4][2], const char* ta, const char* tb) {
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    // all fragment reads of the k-tile first, then 16 MFMAs back to back
+    bf16x8_t a[TK / 16][4], b[TK / 16][2];
+#pragma unroll
+    for (int ks = 0; ks < TK / 16; ++ks) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) b[ks][ni] = read_frag<B_COL>(tb, b_col<DUAL>(wn, ni), ks);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) a[ks][mi] = read_frag<A_COL>(ta, wm * 128 + mi * 32, ks);
+    }
+#pragma unroll
+    for (int ks = 0; ks < TK / 16; ++ks)
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks][ni], a[ks][mi], acc[mi][ni], 0, 0, 0);
+}
+
+// waits until at most N of this wave's vector-memory operations are outstanding, then joins the workgroup barrier.
+// Written as one asm block: __syncthreads() would make the compiler wait for ALL outstanding direct-to-LDS loads
+// (they are memory writes the fence has to cover) and so serialise the load ring.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
+// valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
+// 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
+// accumulator registers around every iteration.)
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
+__device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
+                                          const Operand& oa2, const Operand& ob2, int K2, int mi_count,
+                                          char* smem) {
+    const int nk1 = (K + TK - 1) / TK;
+    const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
+    if (nk <= 0) return;
+    mi_count = __builtin_amdgcn_readfirstlane(mi_count);
+    Loader<A_COL, TWO> la;
+    Loader<B_COL, TWO> lb;
+    la.init(oa, oa2, nk1, nk);
+    lb.init(ob, ob2, nk1, nk);
+    // prologue: k-tiles 0 .. kStages-2 (tiles past the end fetch zeros into stages nobody reads, which keeps the
+    // number of outstanding loads uniform)
+#pragma unroll
+    for (int s = 0; s < kStages - 1; ++s) {
+        la.issue(smem + s * kStageBytes, s);
+        lb.issue(smem + s * kStageBytes + kOpBytes, s);
+    }
+    if (mi_count > 0) {
+        for (int kt = 0; kt < nk; ++kt) {
+            // everything but the newest (kStages-2) k-tiles of this thread has landed, and after the barrier that
+            // holds for every thread; all waves are also done reading stage (kt-1), which is refilled next
+            wait_loads_and_barrier<(kStages - 2) * kLoadsPerTile>();
+            const int nt = kt + kStages - 1;
+            char* st_next = smem + (nt % kStages) * kStageBytes;
+            // past the end these fetch zeros into a stage that is not read any more: the count of outstanding
+            // loads stays uniform
+            la.issue(st_next, nt);
+            lb.issue(st_next + kOpBytes, nt);
+            const char* st = smem + (kt % kStages) * kStageBytes;
+            stage_mma<A_COL, B_COL, DUAL>(acc, st, st + kOpBytes);
+        }
+    } else {
+        // a wave whose rows (or columns) all lie past the ragged tail: it only feeds the ring and keeps the barriers
+        for (int kt = 0; kt < nk; ++kt) {
+            wait_loads_and_barrier<(kStages - 2) * kLoadsPerTile>();
+            const int nt = kt + kStages - 1;
+            char* st_next = smem + (nt % kStages) * kStageBytes;
+            la.issue(st_next, nt);
+            lb.issue(st_next + kOpBytes, nt);
+        }
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+}
+
+template <bool A_COL, bool B_COL, bool DUAL>
+__device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
+                                         int mi_count, char* smem) {
+    mainloop2<A_COL, B_COL, DUAL, false>(acc, oa, ob, K, oa, ob, 0, mi_count, smem);
+}
+
+__device__ __forceinline__ void zero_acc(f32x16_t (&acc)[4][2]) {
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// epilogue helpers: a wave stages 32 rows x NC columns of bf16 in its private LDS strip, then writes rows out
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kStripStride = 200;                 // bytes per staged row (96 columns + 8 bytes: conflict-free)
+constexpr int kStripBytes = 32 * kStripStride;    // per wave
+
+__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
+    return make_uint2((uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16),
+                      (uint32_t)float_to_bf16_bits(c) | ((uint32_t)float_to_bf16_bits(d) << 16));
+}
+
+// writes this lane's 16 values of one 32 x 32 accumulator tile at columns col0 .. col0+31 of the strip
+__device__ __forceinline__ void strip_put(char* strip, int col0, const float (&x)[16]) {
+    const int lane = threadIdx.x & 63;
+    char* row = strip + (lane & 31) * kStripStride;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int n = col0 + 8 * q + 4 * (lane >> 5);
+        *reinterpret_cast<uint2*>(row + n * 2) = pack4(x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]);
+    }
+}
+
+// writes strip columns [col0, col0 + NC) of rows [0, rows_valid) to C (row stride ldc); columns >= cols_valid
+// (a multiple of 4) are skipped.  NC = 32 or 64.
+template <int NC>
+__device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t* C, long ldc, int rows_valid,
+                                            int cols_valid) {
+    const int lane = threadIdx.x & 63;
+    constexpr int LPR = NC / 4;          // lanes per row, 4 columns (8 bytes) each
+    constexpr int RPI = 64 / LPR;        // rows per instruction
+    const int c4 = (lane % LPR) * 4;
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + lane / LPR;
+        if (r < rows_valid && c4 < cols_valid)
+            *reinterpret_cast<uint2*>(C + (long)r * ldc + c4) =
+                *reinterpret_cast<const uint2*>(strip + r * kStripStride + (col0 + c4) * 2);
+    }
+}
+
+// Each XCD gets a contiguous run of the `total` logical tiles.  Returns -1 for a workgroup with nothing to do.
+__device__ __forceinline__ int xcd_tile(int total) {
+    const int b = blockIdx.x;
+    const int chunk = (total + kNumXcd - 1) / kNumXcd;
+    const int within = b / kNumXcd;
+    const int t = (b % kNumXcd) * chunk + within;
+    return (within < chunk && t < total) ? t : -1;
+}
+
+struct RowTile {
+    int e, row0, rows;   // expert, first row, valid rows (1..256)
+};
+__device__ __forceinline__ RowTile get_row_tile(const int32_t* __restrict__ map, const int32_t* __restrict__ off,
+                                                int mt) {
+    RowTile t;
+    t.e = map[4 + 2 * mt];
+    t.row0 = map[4 + 2 * mt + 1];
+    const int r = off[t.e + 1] - t.row0;
+    t.rows = r < TM ? r : TM;
+    return t;
+}
+
+__device__ __forceinline__ Operand row_op(const bf16_t* p, long ld, int rows) {
+    Operand o;
+    o.p_lo = o.p_hi = p;
+    o.ld = ld;
+    o.n_lo = o.n_hi = rows;
+    o.k_valid = 0;
+    return o;
+}
+__device__ __forceinline__ Operand col_op(const bf16_t* p, long ld, int cols, int k_valid) {
+    Operand o;
+    o.p_lo = p;
+    o.p_hi = p + 128;
+    o.ld = ld;
+    o.n_lo = cols < 128 ? cols : 128;
+    o.n_hi = cols > 128 ? cols - 128 : 0;
+    o.k_valid = k_valid;
+    return o;
+}
+
+// number of 32-row blocks of wave-row wm that contain valid rows
+__device__ __forceinline__ int wave_mi_count(int rows) {
+    const int wm = threadIdx.x >> 8;
+    int r = rows - wm * 128;
+    r = r < 0 ? 0 : (r > 128 ? 128 : r);
+    return (r + 31) >> 5;
+}
+
+}  // namespace
+
+// =========================================================================================================
+// forward 1: G = Xd Wg, U = Xd Wu, A = silu(G) * U.   Block tile: 256 rows x (128 gate + 128 up columns).
+// =========================================================================================================
+__global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __restrict__ xd,
+                                                             const int32_t* __restrict__ off,
+                                                             const int32_t* __restrict__ map, int d, int f,
+                                                             const bf16_t* __restrict__ wg,
+                                                             const bf16_t* __restrict__ wu, bf16_t* __restrict__ G,
+                                                             bf16_t* __restrict__ U, bf16_t* __restrict__ A) {
+    extern __shared__ __align__(16) char smem[];
+    const int nt = (f + 127) / 128;
+    const int t = xcd_tile(map[0] * nt);
+    if (t < 0) return;
+    const RowTile rt = get_row_tile(map, off, t / nt);
+    const int n0 = (t % nt) * 128;
+    const int ncols = f - n0 < 128 ? f - n0 : 128;
+    Operand a = row_op(xd + (long)rt.row0 * d, d, rt.rows);
+    Operand b;
+    b.p_lo = wg + (long)rt.e * d * f + n0;
+    b.p_hi = wu + (long)rt.e * d * f + n0;
+    b.ld = f;
+    b.n_lo = b.n_hi = ncols;
+    b.k_valid = d;
+    f32x16_t acc[4][2];
+    zero_acc(acc);
+    const int mi_count = wave_mi_count(rt.rows);
+    mainloop<false, true, true>(acc, a, b, d, mi_count, smem);
+
+    const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+    char* strip = smem + wave * kStripBytes;
+    const int cols_valid = ncols - wn * 32;   // of this wave's 32 columns
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        float g[16], u[16], s[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            g[v] = acc[mi][0][v];
+            u[v] = acc[mi][1][v];
+            s[v] = siluf_(g[v]) * u[v];
+        }
+        const int r0 = wm * 128 + mi * 32;
+        const int rows_valid = rt.rows - r0;
+        const long base = (long)(rt.row0 + r0) * f + n0 + wn * 32;
+        strip_put(strip, 0, g);
+        strip_put(strip, 32, u);
+        __syncthreads();
+        strip_flush<32>(strip, 0, G + base, f, rows_valid, cols_valid);
+        strip_flush<32>(strip, 32, U + base, f, rows_valid, cols_valid);
+        __syncthreads();
+        strip_put(strip, 0, s);
+        __syncthreads();
+        strip_flush<32>(strip, 0, A + base, f, rows_valid, cols_valid);
+        __syncthreads();
+    }
+}
+
+// =========================================================================================================
+// forward 2: Y = A Wd          (K = f, N = d, weights "in x out" -> col tile)
+// backward 1: dA = dY Wd^T     (K = d, N = f, weights K-contiguous -> row tile) + dG, dU, A in the epilogue
+// =========================================================================================================
+template <bool DACT>
+__global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __restrict__ X,
+                                                              const int32_t* __restrict__ off,
+                                                              const int32_t* __restrict__ map, int K, int N,
+                                                              const bf16_t* __restrict__ W, bf16_t* __restrict__ Y,
+                                                              const bf16_t* __restrict__ G,
+                                                              const bf16_t* __restrict__ U, bf16_t* __restrict__ dG,
+                                                              bf16_t* __restrict__ dU, bf16_t* __restrict__ A) {
+    extern __shared__ __align__(16) char smem[];
+    const int nt = (N + TN - 1) / TN;
+    const int t = xcd_tile(map[0] * nt);
+    if (t < 0) return;
+    const RowTile rt = get_row_tile(map, off, t / nt);
+    const int n0 = (t % nt) * TN;
+    const int ncols = N - n0 < TN ? N - n0 : TN;
+    Operand a = row_op(X + (long)rt.row0 * K, K, rt.rows);
+    const bf16_t* We = W + (long)rt.e * K * N;
+    f32x16_t acc[4][2];
+    zero_acc(acc);
+    const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+    // waves whose 64 columns lie past N have nothing to compute either
+    const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
+    if (DACT) {
+        Operand b = row_op(We + (long)n0 * K, K, ncols);   // Wd is [f, d]: its rows are the output columns
+        mainloop<false, false, false>(acc, a, b, K, mi_count, smem);
+    } else {
+        Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
+        mainloop<false, true, false>(acc, a, b, K, mi_count, smem);
+    }
+    char* strip = smem + wave * kStripBytes;
+    const int lane = threadIdx.x & 63;
+    const int cols_valid = ncols - wn * 64;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int r0 = wm * 128 + mi * 32;
+        const int rows_valid = rt.rows - r0;
+        const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
+        if (!DACT) {
+            float x0[16], x1[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                x0[v] = acc[mi][0][v];
+                x1[v] = acc[mi][1][v];
+            }
+            strip_put(strip, 0, x0);
+            strip_put(strip, 32, x1);
+            __syncthreads();
+            strip_flush<64>(strip, 0, Y + base, N, rows_valid, cols_valid);
+            __syncthreads();
+        } else {
+            const int m = lane & 31;
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                float dg[16], du[16], av[16];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = ni * 32 + 8 * q + 4 * (lane >> 5);
+                    uint2 gq = make_uint2(0, 0), uq = make_uint2(0, 0);
+                    if (m < rows_valid && c < cols_valid) {
+                        gq = *reinterpret_cast<const uint2*>(G + base + (long)m * N + c);
+                        uq = *reinterpret_cast<const uint2*>(U + base + (long)m * N + c);
+                    }
+                    const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
+                        const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
+                        const float g = __uint_as_float(gb), u = __uint_as_float(ub);
+                        const float da = acc[mi][ni][4 * q + j];
+                        const float sg = sigmoidf_(g);
+                        const float sl = g * sg;
+                        dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
+                        du[4 * q + j] = da * sl;
+                        av[4 * q + j] = sl * u;
+                    }
+                }
+                strip_put(strip, 0, dg);
+                strip_put(strip, 32, du);
+                strip_put(strip, 64, av);
+                __syncthreads();
+                const long o = base + ni * 32;
+                strip_flush<32>(strip, 0, dG + o, N, rows_valid, cols_valid - ni * 32);
+                strip_flush<32>(strip, 32, dU + o, N, rows_valid, cols_valid - ni * 32);
+                strip_flush<32>(strip, 64, A + o, N, rows_valid, cols_valid - ni * 32);
+                __syncthreads();
+            }
+        }
+    }
+}
+
+// =========================================================================================================
+// backward 2: dXd = dG Wg^T + dU Wu^T     (K = f twice, N = d; Wg, Wu [d, f]: rows are output columns)
+// =========================================================================================================
+__global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restrict__ dG, const bf16_t* __restrict__ dU,
+                                                         const int32_t* __restrict__ off,
+                                                         const int32_t* __restrict__ map, int d, int f,
+                                                         const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
+                                                         bf16_t* __restrict__ dXd) {
+    extern __shared__ __align__(16) char smem[];
+    const int nt = (d + TN - 1) / TN;
+    const int t = xcd_tile(map[0] * nt);
+    if (t < 0) return;
+    const RowTile rt = get_row_tile(map, off, t / nt);
+    const int n0 = (t % nt) * TN;
+    const int ncols = d - n0 < TN ? d - n0 : TN;
+    const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+    const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
+    f32x16_t acc[4][2];
+    zero_acc(acc);
+    {
+        Operand a1 = row_op(dG + (long)rt.row0 * f, f, rt.rows);
+        Operand b1 = row_op(wg + (long)rt.e * d * f + (long)n0 * f, f, ncols);
+        Operand a2 = row_op(dU + (long)rt.row0 * f, f, rt.rows);
+        Operand b2 = row_op(wu + (long)rt.e * d * f + (long)n0 * f, f, ncols);
+        mainloop2<false, false, false, true>(acc, a1, b1, f, a2, b2, f, mi_count, smem);
+    }
+    char* strip = smem + wave * kStripBytes;
+    const int cols_valid = ncols - wn * 64;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int r0 = wm * 128 + mi * 32;
+        float x0[16], x1[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            x0[v] = acc[mi][0][v];
+            x1[v] = acc[mi][1][v];
+        }
+        strip_put(strip, 0, x0);
+        strip_put(strip, 32, x1);
+        __syncthreads();
+        strip_flush<64>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
+        __syncthreads();
+    }
+}
+
+// =========================================================================================================
+// weight gradients: dW_e[m, n] = sum over the expert's rows r of P[r, m] * Q[r, n]   (K = ragged row count; both
+// operands are K-strided -> col tiles).  DUAL: two right-hand sides Q1, Q2 sharing P (dWg and dWu share Xd);
+// the block then covers 128 columns of each.  An expert with no rows gets zeros.
+// =========================================================================================================
+template <bool DUAL>
+__global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P, const bf16_t* __restrict__ Q1,
+                                                            const bf16_t* __restrict__ Q2,
+                                                            const int32_t* __restrict__ off, int E, int M, int N,
+                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
+    extern __shared__ __align__(16) char smem[];
+    constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
+    const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
+    const int t = xcd_tile(E * mt * nt);
+    if (t < 0) return;
+    const int e = t / (mt * nt);
+    const int m0 = ((t / nt) % mt) * TM, n0 = (t % nt) * NB;
+    const int lo = off[e], hi = off[e + 1];
+    const int K = hi - lo;
+    const int mrows = M - m0 < TM ? M - m0 : TM, ncols = N - n0 < NB ? N - n0 : NB;
+    const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+    f32x16_t acc[4][2];
+    zero_acc(acc);
+    if (K > 0) {
+        Operand a = col_op(P + (long)lo * M + m0, M, mrows, K);
+        Operand b;
+        if (DUAL) {
+            b.p_lo = Q1 + (long)lo * N + n0;
+            b.p_hi = Q2 + (long)lo * N + n0;
+            b.ld = N;
+            b.n_lo = b.n_hi = ncols;
+            b.k_valid = K;
+        } else {
+            b = col_op(Q1 + (long)lo * N + n0, N, ncols, K);
+        }
+        const int wcol = DUAL ? wn * 32 : wn * 64;
+        const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
+        mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem);
+    }
+    char* strip = smem + wave * kStripBytes;
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+        const int r0 = wm * 128 + mi * 32;
+        float x0[16], x1[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            x0[v] = acc[mi][0][v];
+            x1[v] = acc[mi][1][v];
+        }
+        strip_put(strip, 0, x0);
+        strip_put(strip, 32, x1);
+        __syncthreads();
+        if (DUAL) {
+            const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 32;
+            strip_flush<32>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 32);
+            strip_flush<32>(strip, 32, dW2 + o, N, mrows - r0, ncols - wn * 32);
+        } else {
+            const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 64;
+            strip_flush<64>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 64);
+        }
+        __syncthreads();
+    }
+}
+
+// =========================================================================================================
+// host side
+// =========================================================================================================
+bool ffn_dma_supported(const FfnArgs& a) {
+    if (a.dt != XMOE_BF16) return false;
+    if (a.d % 64 != 0 || a.f % 64 != 0) return false;
+    const void* ptrs[] = {a.xd, a.wg, a.wu, a.wd, a.g, a.u, a.y, a.dy, a.dxd, a.dwg, a.dwu, a.dwd, a.act, a.dg, a.du};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+
+static inline unsigned round_up8(long v) { return (unsigned)((v + 7) / 8 * 8); }
+
+template <class Kern>
+static int allow_big_lds(Kern k) {
+    // kernels of this family use 128 KiB of dynamic LDS, above the 64 KiB default limit
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kLdsBytes) == hipSuccess
+               ? XMOE_OK
+               : XMOE_ERR_HIP;
+}
+
+static int init_once() {
+    static int state = -1;
+    if (state < 0) {
+        int st = allow_big_lds(ffn_gateup_dma_kernel);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true>);
+        state = st;
+    }
+    return state;
+}
+
+int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
+    int st = init_once();
+    if (st != XMOE_OK) return st;
+    const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, s);
+    if (st != XMOE_OK) return st;
+    const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
+                 *wd = (const bf16_t*)a.wd;
+    const int ntg = (a.f + 127) / 128, ntd = (a.d + TN - 1) / TN;
+    XMOE_LAUNCH(K_FFN_GATEUP_MFMA, s,
+                hipLaunchKernelGGL(ffn_gateup_dma_kernel, dim3(round_up8((long)max_tiles * ntg)), dim3(512), kLdsBytes,
+                                   s, xd, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g, (bf16_t*)a.u, (bf16_t*)a.act));
+    XMOE_LAUNCH(K_FFN_DOWN_MFMA, s,
+                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
+                                   kLdsBytes, s, (const bf16_t*)a.act, a.off, a.map, a.f, a.d, wd, (bf16_t*)a.y, nullptr,
+                                   nullptr, nullptr, nullptr, nullptr));
+    return XMOE_OK;
+}
+
+int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
+    int st = init_once();
+    if (st != XMOE_OK) return st;
+    const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, s);
+    if (st != XMOE_OK) return st;
+    const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
+                 *wd = (const bf16_t*)a.wd, *dy = (const bf16_t*)a.dy;
+    bf16_t *dg = (bf16_t*)a.dg, *du = (bf16_t*)a.du, *act = (bf16_t*)a.act;
+    const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
+    XMOE_LAUNCH(K_FFN_DACT_MFMA, s,
+                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntf)), dim3(512),
+                                   kLdsBytes, s, dy, a.off, a.map, a.d, a.f, wd, nullptr, (const bf16_t*)a.g,
+                                   (const bf16_t*)a.u, dg, du, act));
+    XMOE_LAUNCH(K_FFN_DX_MFMA, s,
+                hipLaunchKernelGGL(ffn_dx_dma_kernel, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
+                                   du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd));
+    // dWd [f, d] = A^T dY
+    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
+    XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
+                hipLaunchKernelGGL(ffn_wgrad_dma_kernel<false>, dim3(round_up8((long)a.E * mtf * ntd)), dim3(512),
+                                   kLdsBytes, s, act, dy, nullptr, a.off, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
+    // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
+    const int ntf2 = (a.f + 127) / 128;
+    XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
+                hipLaunchKernelGGL(ffn_wgrad_dma_kernel<true>, dim3(round_up8((long)a.E * mtd * ntf2)), dim3(512),
+                                   kLdsBytes, s, xd, dg, du, a.off, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+    return XMOE_OK;
+}
+
+}  // namespace xmoe
