@@ -118,6 +118,9 @@ struct Loader {
             } else {
                 if (kt >= nk) p = reinterpret_cast<const bf16_t*>(kZero16);
             }
+#ifdef XMOE_PROBE_NOLOAD
+            p = reinterpret_cast<const bf16_t*>(kZero16);
+#endif
             __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, 0);
         }
     }
@@ -157,27 +160,32 @@ __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int base, int ks
 template <bool DUAL>
 __device__ __forceinline__ int b_col(int wn, int ni) { return DUAL ? ni * 128 + wn * 32 : wn * 64 + ni * 32; }
 
-// acc[mi][ni][v] holds C(row = wm*128 + mi*32 + lane%32, col = b_col(wn, ni) + 8*(v/4) + 4*(lane/32) + v%4)
+// the 6 fragments (4 of A, 2 of B) a wave needs for one 16-wide k-step
+struct Frags {
+    bf16x8_t a[4], b[2];
+};
+
 template <bool A_COL, bool B_COL, bool DUAL>
-__device__ __forceinline__ void stage_mma(f32x16_t (&acc)[4][2], const char* ta, const char* tb) {
+__device__ __forceinline__ void read_frags(Frags& f, const char* ta, const char* tb, int ks) {
     const int wave = threadIdx.x >> 6;
     const int wm = wave >> 2, wn = wave & 3;
-    // all fragment reads of the k-tile first, then 16 MFMAs back to back
-    bf16x8_t a[TK / 16][4], b[TK / 16][2];
 #pragma unroll
-    for (int ks = 0; ks < TK / 16; ++ks) {
+    for (int ni = 0; ni < 2; ++ni) f.b[ni] = read_frag<B_COL>(tb, b_col<DUAL>(wn, ni), ks);
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) b[ks][ni] = read_frag<B_COL>(tb, b_col<DUAL>(wn, ni), ks);
+    for (int mi = 0; mi < 4; ++mi) f.a[mi] = read_frag<A_COL>(ta, wm * 128 + mi * 32, ks);
+}
+
+// acc[mi][ni][v] holds C(row = wm*128 + mi*32 + lane%32, col = b_col(wn, ni) + 8*(v/4) + 4*(lane/32) + v%4)
+__device__ __forceinline__ void mma_step(f32x16_t (&acc)[4][2], const Frags& f) {
+#ifdef XMOE_PROBE_NOMMA
+    if (f.a[0][0] == (__bf16)123.0f) acc[0][0][0] += 1.0f;   // keeps the fragment reads alive
+    return;
+#endif
 #pragma unroll
-        for (int mi = 0; mi < 4; ++mi) a[ks][mi] = read_frag<A_COL>(ta, wm * 128 + mi * 32, ks);
-    }
+    for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
-    for (int ks = 0; ks < TK / 16; ++ks)
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks][ni], a[ks][mi], acc[mi][ni], 0, 0, 0);
+        for (int ni = 0; ni < 2; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
 }
 
 // waits until at most N of this wave's vector-memory operations are outstanding, then joins the workgroup barrier.
@@ -211,28 +219,35 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         la.issue(smem + s * kStageBytes, s);
         lb.issue(smem + s * kStageBytes + kOpBytes, s);
     }
+    // Invariant at the top of iteration kt (established by the barrier before it): k-tiles <= kt+1 have landed
+    // for every thread, and every wave is done reading k-tile kt-1.  So the stage of tile kt-1 can be refilled,
+    // and the fragments of the first k-step of tile kt+1 can be fetched while the MFMAs of tile kt still run -
+    // the LDS latency after each barrier is hidden behind the previous tile's matrix work.
+    wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
     if (mi_count > 0) {
+        Frags f0, f1;
+        read_frags<A_COL, B_COL, DUAL>(f0, smem, smem + kOpBytes, 0);
         for (int kt = 0; kt < nk; ++kt) {
-            // everything but the newest (kStages-2) k-tiles of this thread has landed, and after the barrier that
-            // holds for every thread; all waves are also done reading stage (kt-1), which is refilled next
-            wait_loads_and_barrier<(kStages - 2) * kLoadsPerTile>();
             const int nt = kt + kStages - 1;
             char* st_next = smem + (nt % kStages) * kStageBytes;
-            // past the end these fetch zeros into a stage that is not read any more: the count of outstanding
-            // loads stays uniform
             la.issue(st_next, nt);
             lb.issue(st_next + kOpBytes, nt);
             const char* st = smem + (kt % kStages) * kStageBytes;
-            stage_mma<A_COL, B_COL, DUAL>(acc, st, st + kOpBytes);
+            read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
+            mma_step(acc, f0);
+            const char* st1 = smem + ((kt + 1) % kStages) * kStageBytes;
+            read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
+            mma_step(acc, f1);
+            wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
         }
     } else {
         // a wave whose rows (or columns) all lie past the ragged tail: it only feeds the ring and keeps the barriers
         for (int kt = 0; kt < nk; ++kt) {
-            wait_loads_and_barrier<(kStages - 2) * kLoadsPerTile>();
             const int nt = kt + kStages - 1;
             char* st_next = smem + (nt % kStages) * kStageBytes;
             la.issue(st_next, nt);
             lb.issue(st_next + kOpBytes, nt);
+            wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
         }
     }
     wait_vmcnt<0>();
@@ -244,6 +259,21 @@ __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& o
                                          int mi_count, char* smem) {
     mainloop2<A_COL, B_COL, DUAL, false>(acc, oa, ob, K, oa, ob, 0, mi_count, smem);
 }
+
+#ifdef XMOE_PROBE_NOEPI
+// probe build: skips the epilogue but keeps the accumulators alive
+#define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)                                   \
+    {                                                                         \
+        float s_ = 0.f;                                                       \
+        for (int mi_ = 0; mi_ < 4; ++mi_)                                     \
+            for (int ni_ = 0; ni_ < 2; ++ni_)                                 \
+                for (int v_ = 0; v_ < 16; ++v_) s_ += acc[mi_][ni_][v_];      \
+        if (s_ == 123.456f) (ptr)[0].bits = 1;                                \
+        return;                                                               \
+    }
+#else
+#define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)
+#endif
 
 __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[4][2]) {
 #pragma unroll
@@ -264,6 +294,10 @@ __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
     return make_uint2((uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16),
                       (uint32_t)float_to_bf16_bits(c) | ((uint32_t)float_to_bf16_bits(d) << 16));
 }
+
+// A strip belongs to one wave, and a wave's LDS operations execute in order, so a strip needs no workgroup
+// barrier: waiting for the wave's own LDS traffic (and keeping the compiler from moving accesses across) is enough.
+__device__ __forceinline__ void strip_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // writes this lane's 16 values of one 32 x 32 accumulator tile at columns col0 .. col0+31 of the strip
 __device__ __forceinline__ void strip_put(char* strip, int col0, const float (&x)[16]) {
@@ -372,6 +406,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     zero_acc(acc);
     const int mi_count = wave_mi_count(rt.rows);
     mainloop<false, true, true>(acc, a, b, d, mi_count, smem);
+    XMOE_PROBE_SKIP_EPILOGUE(acc, G)
 
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
     char* strip = smem + wave * kStripBytes;
@@ -390,14 +425,14 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
         const long base = (long)(rt.row0 + r0) * f + n0 + wn * 32;
         strip_put(strip, 0, g);
         strip_put(strip, 32, u);
-        __syncthreads();
+        strip_sync();
         strip_flush<32>(strip, 0, G + base, f, rows_valid, cols_valid);
         strip_flush<32>(strip, 32, U + base, f, rows_valid, cols_valid);
-        __syncthreads();
+        strip_sync();
         strip_put(strip, 0, s);
-        __syncthreads();
+        strip_sync();
         strip_flush<32>(strip, 0, A + base, f, rows_valid, cols_valid);
-        __syncthreads();
+        strip_sync();
     }
 }
 
@@ -434,6 +469,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
         Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
         mainloop<false, true, false>(acc, a, b, K, mi_count, smem);
     }
+    XMOE_PROBE_SKIP_EPILOGUE(acc, dG ? dG : Y)
     char* strip = smem + wave * kStripBytes;
     const int lane = threadIdx.x & 63;
     const int cols_valid = ncols - wn * 64;
@@ -451,46 +487,68 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             }
             strip_put(strip, 0, x0);
             strip_put(strip, 32, x1);
-            __syncthreads();
+            strip_sync();
             strip_flush<64>(strip, 0, Y + base, N, rows_valid, cols_valid);
-            __syncthreads();
+            strip_sync();
         } else {
-            const int m = lane & 31;
+            // nothing here: the dAct epilogue is handled after the loop (it pipelines its G/U loads over all rounds)
+        }
+    }
+    if (DACT) {
+        // 8 rounds (mi, ni) of 32 x 32 outputs.  G and U of round r+1 are fetched while round r is computed and
+        // stored, so that only the first round pays the memory latency.
+        const int m = lane & 31;
+        uint2 gq[2][4], uq[2][4];
+        auto fetch = [&](int r, uint2 (&g4)[4], uint2 (&u4)[4]) {
+            const int mi = r >> 1, ni = r & 1;
+            const int r0 = wm * 128 + mi * 32;
+            const int rows_valid = rt.rows - r0;
+            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                float dg[16], du[16], av[16];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c = ni * 32 + 8 * q + 4 * (lane >> 5);
-                    uint2 gq = make_uint2(0, 0), uq = make_uint2(0, 0);
-                    if (m < rows_valid && c < cols_valid) {
-                        gq = *reinterpret_cast<const uint2*>(G + base + (long)m * N + c);
-                        uq = *reinterpret_cast<const uint2*>(U + base + (long)m * N + c);
-                    }
-                    const uint32_t gw[2] = {gq.x, gq.y}, uw[2] = {uq.x, uq.y};
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
-                        const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
-                        const float g = __uint_as_float(gb), u = __uint_as_float(ub);
-                        const float da = acc[mi][ni][4 * q + j];
-                        const float sg = sigmoidf_(g);
-                        const float sl = g * sg;
-                        dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
-                        du[4 * q + j] = da * sl;
-                        av[4 * q + j] = sl * u;
-                    }
+            for (int q = 0; q < 4; ++q) {
+                const int c = ni * 32 + 8 * q + 4 * (lane >> 5);
+                g4[q] = make_uint2(0, 0);
+                u4[q] = make_uint2(0, 0);
+                if (m < rows_valid && c < cols_valid) {
+                    g4[q] = *reinterpret_cast<const uint2*>(G + base + (long)m * N + c);
+                    u4[q] = *reinterpret_cast<const uint2*>(U + base + (long)m * N + c);
                 }
-                strip_put(strip, 0, dg);
-                strip_put(strip, 32, du);
-                strip_put(strip, 64, av);
-                __syncthreads();
-                const long o = base + ni * 32;
-                strip_flush<32>(strip, 0, dG + o, N, rows_valid, cols_valid - ni * 32);
-                strip_flush<32>(strip, 32, dU + o, N, rows_valid, cols_valid - ni * 32);
-                strip_flush<32>(strip, 64, A + o, N, rows_valid, cols_valid - ni * 32);
-                __syncthreads();
             }
+        };
+        fetch(0, gq[0], uq[0]);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int mi = r >> 1, ni = r & 1;
+            if (r + 1 < 8) fetch(r + 1, gq[(r + 1) & 1], uq[(r + 1) & 1]);
+            const int r0 = wm * 128 + mi * 32;
+            const int rows_valid = rt.rows - r0;
+            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
+            float dg[16], du[16], av[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t gw[2] = {gq[r & 1][q].x, gq[r & 1][q].y}, uw[2] = {uq[r & 1][q].x, uq[r & 1][q].y};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
+                    const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
+                    const float g = __uint_as_float(gb), u = __uint_as_float(ub);
+                    const float da = acc[mi][ni][4 * q + j];
+                    const float sg = sigmoidf_(g);
+                    const float sl = g * sg;
+                    dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
+                    du[4 * q + j] = da * sl;
+                    av[4 * q + j] = sl * u;
+                }
+            }
+            strip_put(strip, 0, dg);
+            strip_put(strip, 32, du);
+            strip_put(strip, 64, av);
+            strip_sync();
+            const long o = base + ni * 32;
+            strip_flush<32>(strip, 0, dG + o, N, rows_valid, cols_valid - ni * 32);
+            strip_flush<32>(strip, 32, dU + o, N, rows_valid, cols_valid - ni * 32);
+            strip_flush<32>(strip, 64, A + o, N, rows_valid, cols_valid - ni * 32);
+            strip_sync();
         }
     }
 }
@@ -521,6 +579,7 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         Operand b2 = row_op(wu + (long)rt.e * d * f + (long)n0 * f, f, ncols);
         mainloop2<false, false, false, true>(acc, a1, b1, f, a2, b2, f, mi_count, smem);
     }
+    XMOE_PROBE_SKIP_EPILOGUE(acc, dXd)
     char* strip = smem + wave * kStripBytes;
     const int cols_valid = ncols - wn * 64;
 #pragma unroll
@@ -534,9 +593,9 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         }
         strip_put(strip, 0, x0);
         strip_put(strip, 32, x1);
-        __syncthreads();
+        strip_sync();
         strip_flush<64>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
-        __syncthreads();
+        strip_sync();
     }
 }
 
@@ -579,6 +638,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
         mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem);
     }
+    XMOE_PROBE_SKIP_EPILOGUE(acc, dW1)
     char* strip = smem + wave * kStripBytes;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
@@ -591,7 +651,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         strip_put(strip, 0, x0);
         strip_put(strip, 32, x1);
-        __syncthreads();
+        strip_sync();
         if (DUAL) {
             const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 32;
             strip_flush<32>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 32);
@@ -600,7 +660,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
             const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 64;
             strip_flush<64>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 64);
         }
-        __syncthreads();
+        strip_sync();
     }
 }
 
