@@ -38,6 +38,58 @@ constexpr int kNumXcd = 8;
 
 __device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
 
+#ifdef XMOE_PROBE_TIMING
+// probe build only: per-tile phase timestamps (100 MHz clock) written by thread 0 of each workgroup
+struct ProbeRec {
+    int kind, block, tile, rows;
+    unsigned long long t[4];   // tile start, first k-tile ready, main loop done, epilogue done
+    unsigned long long c[2];   // shader-clock counter at tile start / main loop done
+};
+__device__ ProbeRec g_probe[1 << 17];
+__device__ int g_probe_n;
+#define PROBE_BEGIN(kind_, tile_, rows_)                                                  \
+    int pr_ = -1;                                                                         \
+    if (threadIdx.x == 0) {                                                               \
+        pr_ = atomicAdd(&g_probe_n, 1);                                                   \
+        if (pr_ < (1 << 17)) {                                                            \
+            g_probe[pr_].kind = (kind_);                                                  \
+            g_probe[pr_].block = blockIdx.x;                                              \
+            g_probe[pr_].tile = (tile_);                                                  \
+            g_probe[pr_].rows = (rows_);                                                  \
+            g_probe[pr_].t[0] = wall_clock64();                                           \
+            g_probe[pr_].c[0] = clock64();                                                \
+        } else {                                                                          \
+            pr_ = -1;                                                                     \
+        }                                                                                 \
+    }
+#define PROBE_MARK(idx_, i_)                                  \
+    if ((idx_) >= 0) {                                        \
+        g_probe[idx_].t[i_] = wall_clock64();                 \
+        if ((i_) == 2) g_probe[idx_].c[1] = clock64();        \
+    }
+#define PROBE_IDX pr_
+#else
+#define PROBE_BEGIN(kind_, tile_, rows_)
+#define PROBE_MARK(idx_, i_)
+#define PROBE_IDX -1
+#endif
+
+#ifdef XMOE_PROBE_ONE_EXPERT
+#define PROBE_E(e_) 0   // probe build: every expert reads expert 0's weights (they then stay cache-resident)
+#else
+#define PROBE_E(e_) (e_)
+#endif
+#ifdef XMOE_PROBE_NOLOAD_A
+constexpr bool kProbeNoA = true;
+#else
+constexpr bool kProbeNoA = false;
+#endif
+#ifdef XMOE_PROBE_NOLOAD_B
+constexpr bool kProbeNoB = true;
+#else
+constexpr bool kProbeNoB = false;
+#endif
+
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -104,7 +156,7 @@ struct Loader {
     }
 
     // issues the two loads of k-tile kt into `tile` (LDS address of this operand's tile in the target stage)
-    __device__ __forceinline__ void issue(char* tile, int kt) const {
+    __device__ __forceinline__ void issue(char* tile, int kt, bool probe_zero = false) const {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const bf16_t* p;
@@ -121,6 +173,7 @@ struct Loader {
 #ifdef XMOE_PROBE_NOLOAD
             p = reinterpret_cast<const bf16_t*>(kZero16);
 #endif
+            if (probe_zero) p = reinterpret_cast<const bf16_t*>(kZero16);
             __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, 0);
         }
     }
@@ -195,6 +248,8 @@ template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
+// workgroup barrier that waits only for the wave's LDS traffic (result stores stay in flight)
+__device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
@@ -203,7 +258,7 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
 __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                           const Operand& oa2, const Operand& ob2, int K2, int mi_count,
-                                          char* smem) {
+                                          char* smem, int probe_idx = -1) {
     const int nk1 = (K + TK - 1) / TK;
     const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
     if (nk <= 0) return;
@@ -216,24 +271,29 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     // number of outstanding loads uniform)
 #pragma unroll
     for (int s = 0; s < kStages - 1; ++s) {
-        la.issue(smem + s * kStageBytes, s);
-        lb.issue(smem + s * kStageBytes + kOpBytes, s);
+        la.issue(smem + s * kStageBytes, s, kProbeNoA);
+        lb.issue(smem + s * kStageBytes + kOpBytes, s, kProbeNoB);
     }
     // Invariant at the top of iteration kt (established by the barrier before it): k-tiles <= kt+1 have landed
     // for every thread, and every wave is done reading k-tile kt-1.  So the stage of tile kt-1 can be refilled,
     // and the fragments of the first k-step of tile kt+1 can be fetched while the MFMAs of tile kt still run -
     // the LDS latency after each barrier is hidden behind the previous tile's matrix work.
     wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
+    PROBE_MARK(probe_idx, 1)
     if (mi_count > 0) {
         Frags f0, f1;
         read_frags<A_COL, B_COL, DUAL>(f0, smem, smem + kOpBytes, 0);
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
             char* st_next = smem + (nt % kStages) * kStageBytes;
-            la.issue(st_next, nt);
-            lb.issue(st_next + kOpBytes, nt);
+            la.issue(st_next, nt, kProbeNoA);
+            lb.issue(st_next + kOpBytes, nt, kProbeNoB);
             const char* st = smem + (kt % kStages) * kStageBytes;
+#ifdef XMOE_PROBE_HALFLDS
+            f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
+#else
             read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
+#endif
             mma_step(acc, f0);
             const char* st1 = smem + ((kt + 1) % kStages) * kStageBytes;
             read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
@@ -245,19 +305,19 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
             char* st_next = smem + (nt % kStages) * kStageBytes;
-            la.issue(st_next, nt);
-            lb.issue(st_next + kOpBytes, nt);
+            la.issue(st_next, nt, kProbeNoA);
+            lb.issue(st_next + kOpBytes, nt, kProbeNoB);
             wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
         }
     }
-    wait_vmcnt<0>();
-    __syncthreads();
+    // all loads of this tile (and the dummy ones past its end) have landed before the ring is reused as staging
+    wait_loads_and_barrier<0>();
 }
 
 template <bool A_COL, bool B_COL, bool DUAL>
 __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
-                                         int mi_count, char* smem) {
-    mainloop2<A_COL, B_COL, DUAL, false>(acc, oa, ob, K, oa, ob, 0, mi_count, smem);
+                                         int mi_count, char* smem, int probe_idx = -1) {
+    mainloop2<A_COL, B_COL, DUAL, false>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
 }
 
 #ifdef XMOE_PROBE_NOEPI
@@ -269,7 +329,7 @@ __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& o
             for (int ni_ = 0; ni_ < 2; ++ni_)                                 \
                 for (int v_ = 0; v_ < 16; ++v_) s_ += acc[mi_][ni_][v_];      \
         if (s_ == 123.456f) (ptr)[0].bits = 1;                                \
-        return;                                                               \
+        continue;                                                               \
     }
 #else
 #define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)
@@ -328,13 +388,23 @@ __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t*
     }
 }
 
-// Each XCD gets a contiguous run of the `total` logical tiles.  Returns -1 for a workgroup with nothing to do.
-__device__ __forceinline__ int xcd_tile(int total) {
-    const int b = blockIdx.x;
+// Workgroups are persistent: the launch has at most one workgroup per CU and each walks a list of tiles.  Each XCD
+// (workgroups are dealt to XCDs round-robin) owns a contiguous run [first, end) of the `total` logical tiles; its
+// nloc workgroups take first + local, first + local + nloc, ...  So at any moment an XCD's workgroups sit on
+// consecutive tiles that share operand panels through that XCD's L2, and a tile's result stores drain while the
+// workgroup already fills the ring for its next tile.
+struct TileRange {
+    int first, end, stride;
+};
+__device__ __forceinline__ TileRange tile_range(int total) {
     const int chunk = (total + kNumXcd - 1) / kNumXcd;
-    const int within = b / kNumXcd;
-    const int t = (b % kNumXcd) * chunk + within;
-    return (within < chunk && t < total) ? t : -1;
+    const int xcd = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
+    TileRange r;
+    r.stride = gridDim.x / kNumXcd;
+    r.first = xcd * chunk + local;
+    const int e = (xcd + 1) * chunk;
+    r.end = e < total ? e : total;
+    return r;
 }
 
 struct RowTile {
@@ -390,22 +460,24 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
                                                              bf16_t* __restrict__ U, bf16_t* __restrict__ A) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (f + 127) / 128;
-    const int t = xcd_tile(map[0] * nt);
-    if (t < 0) return;
+    const TileRange tr = tile_range(map[0] * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
     const RowTile rt = get_row_tile(map, off, t / nt);
+    PROBE_BEGIN(0, t, rt.rows)
     const int n0 = (t % nt) * 128;
     const int ncols = f - n0 < 128 ? f - n0 : 128;
     Operand a = row_op(xd + (long)rt.row0 * d, d, rt.rows);
     Operand b;
-    b.p_lo = wg + (long)rt.e * d * f + n0;
-    b.p_hi = wu + (long)rt.e * d * f + n0;
+    b.p_lo = wg + (long)PROBE_E(rt.e) * d * f + n0;
+    b.p_hi = wu + (long)PROBE_E(rt.e) * d * f + n0;
     b.ld = f;
     b.n_lo = b.n_hi = ncols;
     b.k_valid = d;
     f32x16_t acc[4][2];
     zero_acc(acc);
     const int mi_count = wave_mi_count(rt.rows);
-    mainloop<false, true, true>(acc, a, b, d, mi_count, smem);
+    mainloop<false, true, true>(acc, a, b, d, mi_count, smem, PROBE_IDX);
+    PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, G)
 
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
@@ -434,6 +506,10 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
         strip_flush<32>(strip, 0, A + base, f, rows_valid, cols_valid);
         strip_sync();
     }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
+        PROBE_MARK(PROBE_IDX, 3)
+    }
 }
 
 // =========================================================================================================
@@ -450,13 +526,14 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                                                               bf16_t* __restrict__ dU, bf16_t* __restrict__ A) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (N + TN - 1) / TN;
-    const int t = xcd_tile(map[0] * nt);
-    if (t < 0) return;
+    const TileRange tr = tile_range(map[0] * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
     const RowTile rt = get_row_tile(map, off, t / nt);
+    PROBE_BEGIN(DACT ? 2 : 1, t, rt.rows)
     const int n0 = (t % nt) * TN;
     const int ncols = N - n0 < TN ? N - n0 : TN;
     Operand a = row_op(X + (long)rt.row0 * K, K, rt.rows);
-    const bf16_t* We = W + (long)rt.e * K * N;
+    const bf16_t* We = W + (long)PROBE_E(rt.e) * K * N;
     f32x16_t acc[4][2];
     zero_acc(acc);
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
@@ -464,11 +541,12 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
     if (DACT) {
         Operand b = row_op(We + (long)n0 * K, K, ncols);   // Wd is [f, d]: its rows are the output columns
-        mainloop<false, false, false>(acc, a, b, K, mi_count, smem);
+        mainloop<false, false, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     } else {
         Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
-        mainloop<false, true, false>(acc, a, b, K, mi_count, smem);
+        mainloop<false, true, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
+    PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dG ? dG : Y)
     char* strip = smem + wave * kStripBytes;
     const int lane = threadIdx.x & 63;
@@ -551,6 +629,10 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             strip_sync();
         }
     }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
+        PROBE_MARK(PROBE_IDX, 3)
+    }
 }
 
 // =========================================================================================================
@@ -563,9 +645,10 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
                                                          bf16_t* __restrict__ dXd) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (d + TN - 1) / TN;
-    const int t = xcd_tile(map[0] * nt);
-    if (t < 0) return;
+    const TileRange tr = tile_range(map[0] * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
     const RowTile rt = get_row_tile(map, off, t / nt);
+    PROBE_BEGIN(3, t, rt.rows)
     const int n0 = (t % nt) * TN;
     const int ncols = d - n0 < TN ? d - n0 : TN;
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
@@ -574,11 +657,12 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
     zero_acc(acc);
     {
         Operand a1 = row_op(dG + (long)rt.row0 * f, f, rt.rows);
-        Operand b1 = row_op(wg + (long)rt.e * d * f + (long)n0 * f, f, ncols);
+        Operand b1 = row_op(wg + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols);
         Operand a2 = row_op(dU + (long)rt.row0 * f, f, rt.rows);
-        Operand b2 = row_op(wu + (long)rt.e * d * f + (long)n0 * f, f, ncols);
-        mainloop2<false, false, false, true>(acc, a1, b1, f, a2, b2, f, mi_count, smem);
+        Operand b2 = row_op(wu + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols);
+        mainloop2<false, false, false, true>(acc, a1, b1, f, a2, b2, f, mi_count, smem, PROBE_IDX);
     }
+    PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dXd)
     char* strip = smem + wave * kStripBytes;
     const int cols_valid = ncols - wn * 64;
@@ -597,6 +681,10 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         strip_flush<64>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
         strip_sync();
     }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
+        PROBE_MARK(PROBE_IDX, 3)
+    }
 }
 
 // =========================================================================================================
@@ -612,12 +700,13 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
     extern __shared__ __align__(16) char smem[];
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
-    const int t = xcd_tile(E * mt * nt);
-    if (t < 0) return;
+    const TileRange tr = tile_range(E * mt * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
     const int e = t / (mt * nt);
     const int m0 = ((t / nt) % mt) * TM, n0 = (t % nt) * NB;
     const int lo = off[e], hi = off[e + 1];
     const int K = hi - lo;
+    PROBE_BEGIN(DUAL ? 5 : 4, t, K)
     const int mrows = M - m0 < TM ? M - m0 : TM, ncols = N - n0 < NB ? N - n0 : NB;
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
     f32x16_t acc[4][2];
@@ -636,8 +725,9 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         const int wcol = DUAL ? wn * 32 : wn * 64;
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
-        mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem);
+        mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
+    PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dW1)
     char* strip = smem + wave * kStripBytes;
 #pragma unroll
@@ -662,6 +752,10 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         strip_sync();
     }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
+        PROBE_MARK(PROBE_IDX, 3)
+    }
 }
 
 // =========================================================================================================
@@ -676,7 +770,15 @@ bool ffn_dma_supported(const FfnArgs& a) {
     return true;
 }
 
-static inline unsigned round_up8(long v) { return (unsigned)((v + 7) / 8 * 8); }
+static int g_num_cu = 0;
+
+// persistent launch: one workgroup per CU, but never more than there are tiles (host-side upper bound); a
+// multiple of the XCD count
+static inline unsigned round_up8(long v) {
+    long g = (v + 7) / 8 * 8;
+    if (g_num_cu > 0 && g > g_num_cu) g = g_num_cu;
+    return (unsigned)(g < 8 ? 8 : g);
+}
 
 template <class Kern>
 static int allow_big_lds(Kern k) {
@@ -690,6 +792,10 @@ static int allow_big_lds(Kern k) {
 static int init_once() {
     static int state = -1;
     if (state < 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            g_num_cu = prop.multiProcessorCount / kNumXcd * kNumXcd;
         int st = allow_big_lds(ffn_gateup_dma_kernel);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true>);
@@ -751,3 +857,19 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
 }
 
 }  // namespace xmoe
+
+#ifdef XMOE_PROBE_TIMING
+extern "C" int xmoe_probe_dump(void* host_recs, int max_recs, int reset) {
+    int n = 0;
+    if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(xmoe::g_probe_n), sizeof(int)) != hipSuccess) return -1;
+    int m = n < max_recs ? n : max_recs;
+    if (m > (1 << 17)) m = 1 << 17;
+    if (m > 0 && hipMemcpyFromSymbol(host_recs, HIP_SYMBOL(xmoe::g_probe), (size_t)m * sizeof(xmoe::ProbeRec)) != hipSuccess)
+        return -1;
+    if (reset) {
+        int z = 0;
+        if (hipMemcpyToSymbol(HIP_SYMBOL(xmoe::g_probe_n), &z, sizeof(int)) != hipSuccess) return -1;
+    }
+    return m;
+}
+#endif
