@@ -44,16 +44,17 @@ def get_cfg(name):
 
 def kernel_work(cfg):
     """Algorithmic work of one step per kernel: flops for the GEMM kernels, bytes for the row movers.
-    rows*f summed over the routed call (B rows, width f) and the shared call (T rows, width E_s*f)."""
+    The expert MLP runs on R = B + E_s*T rows (the shared experts' segments are copies of x)."""
     s = 4 if cfg.dtype == "f32" else 2
     T, d, E, k, f, B = cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.B
-    rf = B * f + (T * cfg.E_s * f if cfg.E_s else 0)
+    Ts = cfg.E_s * T
+    rf = (B + Ts) * f
     flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf}
-    n_add_fwd = 1 if cfg.E_s else 0
     bytes_ = {
-        "dispatch_kernel": (T + B) * d * s,                                   # unique rows read once + rows written
-        "combine_kernel": (B + T) * d * s + n_add_fwd * T * d * s             # forward combine
-                          + (B + T) * d * s + (1 + n_add_fwd) * T * d * s,    # + dispatch backward (same kernel)
+        # forward: unique rows read once + rows written; backward (E_s > 0): dout copied to the shared segments
+        "dispatch_kernel": (T + B + Ts) * d * s + ((T + Ts) * d * s if Ts else 0),
+        "combine_kernel": (B + Ts + T) * d * s                                # forward combine
+                          + (B + Ts + 2 * T) * d * s,                         # + dispatch backward (same kernel)
         "combine_bwd_kernel": (T + 2 * B) * d * s,
         "route_kernel": T * E * 4 + T * k * 8,
         "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
@@ -90,17 +91,16 @@ def main():
     w = {"w_router": dev(wr_np), "bias": None if bias_np is None else torch.from_numpy(bias_np).cuda()}
     for key in ("wg", "wu", "wd"):
         # expert by expert, so that the large workloads never hold a second host copy of a whole tensor
-        shape = (cfg.E, cfg.d, cfg.f) if key != "wd" else (cfg.E, cfg.f, cfg.d)
+        Ea = cfg.E + cfg.E_s   # the shared experts' weights follow the routed ones
+        shape = (Ea, cfg.d, cfg.f) if key != "wd" else (Ea, cfg.f, cfg.d)
         w[key] = torch.empty(shape, dtype=tdt, device="cuda")
         for e, a in xi.iter_expert_weights(cfg, key):
             w[key][e].copy_(dev(a))
         if cfg.E_s:
-            w["shared_" + key] = xm.fuse_shared(dev(xi.make_shared_weights(cfg, key)), key)
+            w[key][cfg.E:].copy_(dev(xi.make_shared_weights(cfg, key)))
     grads = {"dw_router": torch.empty_like(w["w_router"])}
     for key in ("wg", "wu", "wd"):
         grads["d" + key] = torch.empty_like(w[key])
-        if cfg.E_s:
-            grads["dshared_" + key] = torch.empty_like(w["shared_" + key])
     x, dout = dev(x_np), dev(dout_np)
     layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
     t_gen = time.time() - t_gen

@@ -111,8 +111,10 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
  *   G = Xd_e Wg_e,  U = Xd_e Wu_e,  A = silu(G) * U,  Y_e = A Wd_e          (SwiGLU, no biases)
  * xd [B,d]; wg, wu [E,d,f]; wd [E,f,d] ("in x out"); expert_offsets [E+1] int32 on the device with
  * offsets[0] = 0 and offsets[E] = B.  Outputs: y [B,d]; g_save, u_save [B,f] (kept for backward).
- * An expert with no rows reads no weights.  Shared experts are served by the same call on x itself with
- * E = 1, offsets {0,T} and the E_s experts concatenated along f (wg, wu [1,d,E_s*f]; wd [1,E_s*f,d]).
+ * An expert with no rows reads no weights.  Shared experts are served by the same call as E_s further experts
+ * whose segments are all T tokens: x is appended E_s times after the B routed rows (xmoe_dispatch with token ids
+ * 0..T-1), expert_offsets continues with B+T, B+2T, ..., and the weights of the shared experts follow the routed
+ * ones.  (A single call on x itself with E = 1 and offsets {0,T} works too.)
  * ws: XMOE_WS_FFN_FWD bytes.
  */
 int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, int E, int d, int f,
@@ -134,12 +136,15 @@ int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, 
 
 /* Combine (Section 4.1.2 / Appendix B.4 scatter kernel, which must accumulate since k rows share a token),
  * written as a gather-reduce so that no atomics are needed and the sum order is fixed:
- *   out[t,:] = sum_{j<k} topk_w[t,j] * y[row_of_slot[t*k+j],:]  (+ addend[t,:]) (+ addend2[t,:])
- * accumulated in float32 in slot order, rounded once.  topk_w == NULL means all weights are 1 (this is then
- * the backward of dispatch).  addend / addend2 [T,d] dt or NULL (e.g. the shared experts' output).
+ *   out[t,:] = sum_{j<k} topk_w[t,j] * y[row_of_slot[t*k+j],:]
+ *              + sum_{s<n_shared} shared_rows[s*T + t,:]   (+ addend[t,:])
+ * accumulated in float32 in this order, rounded once.  topk_w == NULL means all weights are 1 (this is then the
+ * backward of dispatch).  shared_rows [n_shared*T, d] dt or NULL with n_shared = 0: outputs of experts that every
+ * token visits with weight 1 (shared experts run as extra experts whose segment is all T tokens).  addend [T,d]
+ * dt or NULL.
  */
-int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
-                 const void* addend, const void* addend2, int T, int k, int d, int dt, void* out, void* stream);
+int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* shared_rows,
+                 int n_shared, const void* addend, int T, int k, int d, int dt, void* out, void* stream);
 
 /* Backward of combine:
  *   dy[row_of_slot[t*k+j],:] = topk_w[t,j] * dout[t,:];     dw[t,j] = <dout[t,:], y[row_of_slot[t*k+j],:]>
@@ -148,10 +153,10 @@ int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
 int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w,
                      int T, int k, int d, int dt, void* dy, float* dw, void* stream);
 
-/* Backward of dispatch: dx[t,:] = sum_j dxd[row_of_slot[t*k+j],:] (+ addend) (+ addend2).
+/* Backward of dispatch: dx[t,:] = sum_j dxd[row_of_slot[t*k+j],:] + sum_s shared_rows[s*T + t,:] (+ addend).
  * Same kernel as xmoe_combine with unit weights. */
-int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* addend, const void* addend2,
-                      int T, int k, int d, int dt, void* dx, void* stream);
+int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* shared_rows, int n_shared,
+                      const void* addend, int T, int k, int d, int dt, void* dx, void* stream);
 
 /* Backward of softmax + top-k with the indices held constant:
  *   dp[t,e] = dw[t,j] if e == topk_idx[t,j] else 0;   dlogits = p * (dp - sum_e p*dp),  p = softmax(logits).

@@ -140,13 +140,18 @@ def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd,
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")
 
 
-def xmoe_combine(y, row_of_slot, topk_w, addend, addend2, k: int, out) -> None:
+def xmoe_combine(y, row_of_slot, topk_w, shared_rows, addend, k: int, out) -> None:
+    """shared_rows: None or an [n_shared*T, d] tensor (rows of experts every token visits with weight 1)."""
     T, d = out.shape
     dt = out.dtype
     assert y.shape[1] == d and row_of_slot.numel() == T * k
+    n_shared = 0
+    if shared_rows is not None:
+        assert shared_rows.shape[1] == d and shared_rows.shape[0] % T == 0
+        n_shared = shared_rows.shape[0] // T
     _check(lib().xmoe_combine(_ptr(y, dt, "y"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
-                              _ptr(topk_w, torch.float32, "topk_w"), _ptr(addend, dt, "addend"),
-                              _ptr(addend2, dt, "addend2"), T, k, d, dtype_code(dt), _ptr(out, None, "out"),
+                              _ptr(topk_w, torch.float32, "topk_w"), _ptr(shared_rows, dt, "shared_rows"), n_shared,
+                              _ptr(addend, dt, "addend"), T, k, d, dtype_code(dt), _ptr(out, None, "out"),
                               _stream()), "xmoe_combine")
 
 
@@ -161,12 +166,16 @@ def xmoe_combine_bwd(dout, y, row_of_slot, topk_w, dy, dw) -> None:
                                   _ptr(dw, torch.float32, "dw"), _stream()), "xmoe_combine_bwd")
 
 
-def xmoe_dispatch_bwd(dxd, row_of_slot, addend, addend2, k: int, dx) -> None:
+def xmoe_dispatch_bwd(dxd, row_of_slot, shared_rows, addend, k: int, dx) -> None:
     T, d = dx.shape
     dt = dx.dtype
     assert tuple(dxd.shape) == (T * k, d)
+    n_shared = 0
+    if shared_rows is not None:
+        assert shared_rows.shape[1] == d and shared_rows.shape[0] % T == 0
+        n_shared = shared_rows.shape[0] // T
     _check(lib().xmoe_dispatch_bwd(_ptr(dxd, dt, "dxd"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
-                                   _ptr(addend, dt, "addend"), _ptr(addend2, dt, "addend2"), T, k, d,
+                                   _ptr(shared_rows, dt, "shared_rows"), n_shared, _ptr(addend, dt, "addend"), T, k, d,
                                    dtype_code(dt), _ptr(dx, None, "dx"), _stream()), "xmoe_dispatch_bwd")
 
 

@@ -16,10 +16,12 @@ struct FfnArgs {
     void *dxd, *dwg, *dwu, *dwd;
     // workspace carve-up
     int32_t* map;                // tile map
+    int32_t* sched;              // experts by descending row count [E], then kSchedCounters counters
     void *act, *dg, *du;         // A = silu(G)*U, dG, dU   [B,f]
 };
 
-int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, hipStream_t s);
+int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, int32_t* sched,
+                    hipStream_t s);
 
 int ffn_fwd_simt(const FfnArgs& a, hipStream_t s);
 int ffn_bwd_simt(const FfnArgs& a, hipStream_t s);

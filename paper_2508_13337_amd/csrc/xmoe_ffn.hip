@@ -52,6 +52,7 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, in
     a.g = g_save; a.u = u_save; a.y = y;
     char* p = (char*)ws;
     a.map = (int32_t*)p;
+    a.sched = a.map + ffn_sched_offset(B, E);
     p += ffn_tilemap_bytes(B, E);
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
@@ -79,6 +80,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, 
     a.dxd = dxd; a.dwg = dwg; a.dwu = dwu; a.dwd = dwd;
     char* p = (char*)ws;
     a.map = (int32_t*)p;
+    a.sched = a.map + ffn_sched_offset(B, E);
     p += ffn_tilemap_bytes(B, E);
     a.dg = p;
     p += ffn_act_bytes(B, f, dt);

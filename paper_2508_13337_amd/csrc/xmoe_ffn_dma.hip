@@ -298,6 +298,30 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
             const char* st1 = smem + ((kt + 1) % kStages) * kStageBytes;
             read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
             mma_step(acc, f1);
+            if (A_COL || B_COL) {
+            // instruction order: every MFMA is followed by a share of the k-tile's direct-to-LDS loads and LDS
+            // fragment reads (0x008 = MFMA, 0x020 = VMEM read, 0x100 = LDS read)
+            constexpr int kReadsPerStep = (A_COL ? 8 : 4) + (B_COL ? 4 : 2);   // LDS reads of one k-step
+            constexpr int kRd = (kReadsPerStep + 5) / 6;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+            for (int j = 0; j < 6; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            }
             wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
         }
     } else {
@@ -406,6 +430,36 @@ __device__ __forceinline__ TileRange tile_range(int total) {
     r.end = e < total ? e : total;
     return r;
 }
+
+// Tiles of unequal length (the weight gradients: K = an expert's row count) are handed out at run time instead.
+// The tile list, longest experts first, is cut into groups of kQueueGroup consecutive tiles (neighbours share
+// operand panels); group g belongs to the list of XCD g % 8, and each list has a counter.  A workgroup draws from
+// its own XCD's list and, once that is empty, from the next XCD's, and so on round the ring; it stops after it
+// has found all eight lists empty.  Only thread 0 touches the counters.
+constexpr int kQueueGroup = 16;
+__device__ __forceinline__ int queue_len(int total, int x) {
+    const int ng = (total + kQueueGroup - 1) / kQueueGroup;
+    return ((ng - x + kNumXcd - 1) / kNumXcd) * kQueueGroup;
+}
+struct TileQueue {
+    int32_t* cnt;   // kNumXcd counters, zero at launch
+    int total, victim, hops;
+    // v: a value already drawn from cnt[victim], or -1.  Returns a tile index, or -1 when everything is taken.
+    __device__ __forceinline__ int pop(int v) {
+        for (;;) {
+            if (v < 0) v = atomicAdd(&cnt[victim], 1);
+            if (v < queue_len(total, victim)) {
+                const int t = ((v / kQueueGroup) * kNumXcd + victim) * kQueueGroup + v % kQueueGroup;
+                if (t < total) return t;
+                v = -1;   // a hole in the last, partial group: draw again
+                continue;
+            }
+            if (++hops >= kNumXcd) return -1;
+            victim = (victim + 1) % kNumXcd;
+            v = -1;
+        }
+    }
+};
 
 struct RowTile {
     int e, row0, rows;   // expert, first row, valid rows (1..256)
@@ -695,14 +749,29 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
 template <bool DUAL>
 __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P, const bf16_t* __restrict__ Q1,
                                                             const bf16_t* __restrict__ Q2,
-                                                            const int32_t* __restrict__ off, int E, int M, int N,
+                                                            const int32_t* __restrict__ off,
+                                                            const int32_t* __restrict__ order,
+                                                            int32_t* __restrict__ counters, int E, int M, int N,
                                                             bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     extern __shared__ __align__(16) char smem[];
+    __shared__ int s_next[2];
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
-    const TileRange tr = tile_range(E * mt * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
-    const int e = t / (mt * nt);
+    TileQueue q;
+    q.cnt = counters;
+    q.total = E * mt * nt;
+    q.victim = blockIdx.x % kNumXcd;
+    q.hops = 0;
+    if (threadIdx.x == 0) s_next[0] = q.pop(-1);
+    __syncthreads();
+    int t = s_next[0];
+    // between tiles: every wave has left its staging strip before the next tile's loads land in the ring, and
+    // thread 0's hand-over is visible
+    for (int it = 0; t >= 0; lds_done_and_barrier(), ++it, t = s_next[it & 1]) {
+    // thread 0 draws the next tile now and looks at the answer only after the main loop
+    int drawn = -1;
+    if (threadIdx.x == 0) drawn = atomicAdd(&q.cnt[q.victim], 1);
+    const int e = order[t / (mt * nt)];
     const int m0 = ((t / nt) % mt) * TM, n0 = (t % nt) * NB;
     const int lo = off[e], hi = off[e + 1];
     const int K = hi - lo;
@@ -727,6 +796,9 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
         mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
+    // double-buffered hand-over: the slot written here was last read before the barrier that ended the
+    // previous tile
+    if (threadIdx.x == 0) s_next[(it + 1) & 1] = q.pop(drawn);
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dW1)
     char* strip = smem + wave * kStripBytes;
@@ -752,9 +824,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         strip_sync();
     }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
-        PROBE_MARK(PROBE_IDX, 3)
+PROBE_MARK(PROBE_IDX, 3)
     }
 }
 
@@ -811,7 +881,7 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
     int st = init_once();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
-    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, s);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd;
@@ -830,7 +900,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
     int st = init_once();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
-    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, s);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd, *dy = (const bf16_t*)a.dy;
@@ -847,12 +917,14 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
                 hipLaunchKernelGGL(ffn_wgrad_dma_kernel<false>, dim3(round_up8((long)a.E * mtf * ntd)), dim3(512),
-                                   kLdsBytes, s, act, dy, nullptr, a.off, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
+                                   kLdsBytes, s, act, dy, nullptr, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                                   (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     const int ntf2 = (a.f + 127) / 128;
     XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
                 hipLaunchKernelGGL(ffn_wgrad_dma_kernel<true>, dim3(round_up8((long)a.E * mtd * ntf2)), dim3(512),
-                                   kLdsBytes, s, xd, dg, du, a.off, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+                                   kLdsBytes, s, xd, dg, du, a.off, a.sched, a.sched + a.E + kNumXcd, a.E, a.d, a.f,
+                                   (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     return XMOE_OK;
 }
 

@@ -412,7 +412,7 @@ static inline unsigned round_up8(long v) { return (unsigned)((v + 7) / 8 * 8); }
 
 int ffn_fwd_mfma(const FfnArgs& a, hipStream_t s) {
     const int max_tiles = ffn_max_tiles(a.B, a.E, BM);
-    int st = launch_tile_map(a.off, a.E, BM, max_tiles, a.map, s);
+    int st = launch_tile_map(a.off, a.E, BM, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd;
@@ -429,7 +429,7 @@ int ffn_fwd_mfma(const FfnArgs& a, hipStream_t s) {
 
 int ffn_bwd_mfma(const FfnArgs& a, hipStream_t s) {
     const int max_tiles = ffn_max_tiles(a.B, a.E, BM);
-    int st = launch_tile_map(a.off, a.E, BM, max_tiles, a.map, s);
+    int st = launch_tile_map(a.off, a.E, BM, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd, *dy = (const bf16_t*)a.dy;

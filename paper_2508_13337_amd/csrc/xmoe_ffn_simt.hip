@@ -8,20 +8,34 @@
 namespace xmoe {
 
 // ---------------------------------------------------------------------------------------------------------
-// tile map: header {total tiles, 0, 0, 0} then (expert, first row) per row tile; unused entries have expert -1
+// tile map: header {total tiles, 0, 0, 0} then (expert, first row) per row tile; unused entries have expert -1.
+// sched: the experts sorted by descending row count (ties: lower index first), then kSchedCounters zeroed counters
+// (the weight-gradient kernels hand out their tiles longest first from these).
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void tile_map_kernel(const int32_t* __restrict__ off, int E, int tile_rows,
-                                                       int max_tiles, int32_t* __restrict__ map) {
+                                                       int max_tiles, int32_t* __restrict__ map,
+                                                       int32_t* __restrict__ sched) {
     __shared__ int start[XMOE_MAX_EXPERTS + 1];
+    __shared__ int count[XMOE_MAX_EXPERTS];
     const int e = threadIdx.x;
-    int nt = 0, lo = 0;
+    int nt = 0, lo = 0, m = 0;
     if (e < E) {
         lo = off[e];
-        int m = off[e + 1] - lo;
+        m = off[e + 1] - lo;
         nt = m > 0 ? (m + tile_rows - 1) / tile_rows : 0;
         start[e] = nt;
+        count[e] = m;
     }
     __syncthreads();
+    if (e < E) {
+        int rank = 0;
+        for (int i = 0; i < E; ++i) {
+            const int c = count[i];
+            rank += (c > m || (c == m && i < e)) ? 1 : 0;
+        }
+        sched[rank] = e;
+    }
+    if (threadIdx.x < kSchedCounters) sched[E + threadIdx.x] = 0;
     if (threadIdx.x == 0) {
         int run = 0;
         for (int i = 0; i < E; ++i) {
@@ -49,9 +63,10 @@ __global__ __launch_bounds__(512) void tile_map_kernel(const int32_t* __restrict
     }
 }
 
-int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, hipStream_t s) {
-    XMOE_LAUNCH(K_TILE_MAP, s,
-                hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(512), 0, s, off, E, tile_rows, max_tiles, map));
+int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, int32_t* sched,
+                    hipStream_t s) {
+    XMOE_LAUNCH(K_TILE_MAP, s, hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(512), 0, s, off, E, tile_rows,
+                                                  max_tiles, map, sched));
     return XMOE_OK;
 }
 
@@ -227,7 +242,7 @@ __global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict
 template <typename T>
 static int fwd_simt(const FfnArgs& a, hipStream_t s) {
     const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
-    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, s);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     dim3 g1(max_tiles, (a.f + kSimtTile - 1) / kSimtTile), g2(max_tiles, (a.d + kSimtTile - 1) / kSimtTile);
     XMOE_LAUNCH(K_FFN_GATEUP_SIMT, s,
@@ -242,7 +257,7 @@ static int fwd_simt(const FfnArgs& a, hipStream_t s) {
 template <typename T>
 static int bwd_simt(const FfnArgs& a, hipStream_t s) {
     const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
-    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, s);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, a.sched, s);
     if (st != XMOE_OK) return st;
     const int tf = (a.f + kSimtTile - 1) / kSimtTile, td = (a.d + kSimtTile - 1) / kSimtTile;
     XMOE_LAUNCH(K_FFN_DACT_SIMT, s,

@@ -68,9 +68,9 @@ __global__ __launch_bounds__(256) void dispatch_kernel(const T* __restrict__ x, 
 // =========================================================================================================
 template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, const int32_t* __restrict__ row_of_slot,
-                                                      const float* __restrict__ topk_w, const T* __restrict__ add1,
-                                                      const T* __restrict__ add2, int Tn, int k, int d, int B,
-                                                      T* __restrict__ out) {
+                                                      const float* __restrict__ topk_w, const T* __restrict__ shared,
+                                                      int n_shared, const T* __restrict__ add, int Tn, int k, int d,
+                                                      int B, T* __restrict__ out) {
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= Tn) return;
@@ -90,15 +90,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, c
 #pragma unroll
                 for (int i = 0; i < N; ++i) acc[i] = fmaf(w, v[i], acc[i]);
             }
-            if (add1) {
+            for (int s = 0; s < n_shared; ++s) {
                 float v[N];
-                Vec16<T>::unpack(reinterpret_cast<const uint4*>(add1 + (size_t)t * d)[c], v);
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(shared + ((size_t)s * Tn + t) * d)[c], v);
 #pragma unroll
                 for (int i = 0; i < N; ++i) acc[i] += v[i];
             }
-            if (add2) {
+            if (add) {
                 float v[N];
-                Vec16<T>::unpack(reinterpret_cast<const uint4*>(add2 + (size_t)t * d)[c], v);
+                Vec16<T>::unpack(reinterpret_cast<const uint4*>(add + (size_t)t * d)[c], v);
 #pragma unroll
                 for (int i = 0; i < N; ++i) acc[i] += v[i];
             }
@@ -113,8 +113,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, c
                 const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.0f;
                 acc = fmaf(w, to_float(y[(size_t)r * d + c]), acc);
             }
-            if (add1) acc += to_float(add1[(size_t)t * d + c]);
-            if (add2) acc += to_float(add2[(size_t)t * d + c]);
+            for (int s = 0; s < n_shared; ++s) acc += to_float(shared[((size_t)s * Tn + t) * d + c]);
+            if (add) acc += to_float(add[(size_t)t * d + c]);
             out[(size_t)t * d + c] = from_float<T>(acc);
         }
     }
@@ -185,16 +185,16 @@ static int launch_dispatch(const void* x, const int32_t* token_ids, int Tn, int 
 }
 
 template <typename T>
-static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* a1, const void* a2, int Tn,
-                          int k, int d, void* out, hipStream_t s) {
+static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* sh, int nsh, const void* add,
+                          int Tn, int k, int d, void* out, hipStream_t s) {
     dim3 grid((Tn + 3) / 4), block(256);
     const int B = Tn * k;
-    if (can_vec<T>(d, {y, a1, a2, out}))
+    if (can_vec<T>(d, {y, sh, add, out}))
         XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, true>), grid, block, 0, s, (const T*)y, ros, w,
-                                                     (const T*)a1, (const T*)a2, Tn, k, d, B, (T*)out));
+                                                     (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
     else
         XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, false>), grid, block, 0, s, (const T*)y, ros,
-                                                     w, (const T*)a1, (const T*)a2, Tn, k, d, B, (T*)out));
+                                                     w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
     return XMOE_OK;
 }
 
@@ -235,20 +235,22 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
                           : launch_dispatch<bf16_t>(x, token_ids, T, B, d, xd, s);
 }
 
-int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* addend,
-                 const void* addend2, int T, int k, int d, int dt, void* out, void* stream) {
+int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* shared_rows,
+                 int n_shared, const void* addend, int T, int k, int d, int dt, void* out, void* stream) {
     int st = check_rows_args(T, k, d, dt);
     if (st != XMOE_OK) return st;
+    if (n_shared < 0 || (n_shared > 0 && !shared_rows)) return XMOE_ERR_INVALID_ARG;
     if (T == 0) return XMOE_OK;
     if (!y || !row_of_slot || !out) return XMOE_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
-    return dt == XMOE_F32 ? launch_combine<float>(y, row_of_slot, topk_w, addend, addend2, T, k, d, out, s)
-                          : launch_combine<bf16_t>(y, row_of_slot, topk_w, addend, addend2, T, k, d, out, s);
+    return dt == XMOE_F32
+               ? launch_combine<float>(y, row_of_slot, topk_w, shared_rows, n_shared, addend, T, k, d, out, s)
+               : launch_combine<bf16_t>(y, row_of_slot, topk_w, shared_rows, n_shared, addend, T, k, d, out, s);
 }
 
-int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* addend, const void* addend2, int T,
-                      int k, int d, int dt, void* dx, void* stream) {
-    return xmoe_combine(dxd, row_of_slot, nullptr, addend, addend2, T, k, d, dt, dx, stream);
+int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* shared_rows, int n_shared,
+                      const void* addend, int T, int k, int d, int dt, void* dx, void* stream) {
+    return xmoe_combine(dxd, row_of_slot, nullptr, shared_rows, n_shared, addend, T, k, d, dt, dx, stream);
 }
 
 int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w, int T, int k,

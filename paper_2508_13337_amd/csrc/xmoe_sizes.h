@@ -20,9 +20,13 @@ static inline size_t eri_ws_bytes(int T, int E, int k) {
 // Sized for the smallest row tile any kernel uses (kMinRowTile rows): at most ceil(B/tile) + E tiles.
 constexpr int kMinRowTile = 64;
 static inline int ffn_max_tiles(int B, int E, int tile_rows) { return (B + tile_rows - 1) / tile_rows + E; }
+// After the pairs comes the schedule block of the weight-gradient kernels: the experts in order of descending row
+// count (E ints), then kSchedCounters work counters.
+constexpr int kSchedCounters = 16;
+static inline size_t ffn_sched_offset(int B, int E) { return 4 + 2 * (size_t)ffn_max_tiles(B, E, kMinRowTile); }
 static inline size_t ffn_tilemap_bytes(int B, int E) {
-    // header of 4 ints (total tiles, ...) followed by (expert, row0) pairs
-    return align_up((size_t)(4 + 2 * (size_t)ffn_max_tiles(B, E, kMinRowTile)) * sizeof(int32_t), 256);
+    // header of 4 ints (total tiles, ...) followed by (expert, row0) pairs, then the schedule block
+    return align_up((ffn_sched_offset(B, E) + (size_t)E + kSchedCounters) * sizeof(int32_t), 256);
 }
 static inline size_t ffn_act_bytes(int B, int f, int dt) { return align_up((size_t)B * (size_t)f * dtype_size(dt), 256); }
 

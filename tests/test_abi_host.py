@@ -84,8 +84,11 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.xmoe_expert_ffn_fwd(p, p, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
     assert lib.xmoe_expert_ffn_fwd(p, null, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 1 << 30, null) == INVALID
     assert lib.xmoe_expert_ffn_bwd(p, p, p, p, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
-    assert lib.xmoe_combine(p, p, p, null, null, 16, 0, 64, 1, p, null) == INVALID
-    assert lib.xmoe_combine(null, p, p, null, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(p, p, p, null, 0, null, 16, 0, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(null, p, p, null, 0, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(p, p, p, null, 2, null, 16, 2, 64, 1, p, null) == INVALID     # shared rows missing
+    assert lib.xmoe_combine(p, p, p, p, -1, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_dispatch_bwd(p, p, null, 1, null, 16, 2, 64, 1, p, null) == INVALID
     assert lib.xmoe_combine_bwd(p, p, p, null, 16, 2, 64, 1, p, p, null) == INVALID
     assert lib.xmoe_route_bwd(p, p, p, 16, 8, 9, p, null) == INVALID
     assert lib.xmoe_gate_logits_bwd(p, p, p, 16, 64, 8, 1, p, p, null, 0, null) == WORKSPACE
@@ -96,7 +99,7 @@ def test_empty_inputs_are_ok_without_a_launch(lib):
     assert lib.xmoe_route(p, 0, 8, 2, p, p, None) == 0
     assert lib.xmoe_gate_logits(p, p, None, p, 0, 32, 8, 1, None) == 0
     assert lib.xmoe_dispatch(p, p, 16, 0, 64, 1, p, None) == 0
-    assert lib.xmoe_combine(p, p, p, None, None, 0, 2, 64, 1, p, None) == 0
+    assert lib.xmoe_combine(p, p, p, None, 0, None, 0, 2, 64, 1, p, None) == 0
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -28,17 +28,16 @@ def build_gpu_layer(cfg):
     bias = xi.make_gate_bias(cfg)
     w["bias"] = None if bias is None else f32(bias)
     for key in ("wg", "wu", "wd"):
-        shape = (cfg.E, cfg.d, cfg.f) if key != "wd" else (cfg.E, cfg.f, cfg.d)
+        Ea = cfg.E + cfg.E_s   # the shared experts' weights follow the routed ones
+        shape = (Ea, cfg.d, cfg.f) if key != "wd" else (Ea, cfg.f, cfg.d)
         w[key] = torch.empty(shape, dtype=tdt, device="cuda")
         for e, a in xi.iter_expert_weights(cfg, key):
             w[key][e].copy_(to_dev(a, dt))
         if cfg.E_s:
-            w["shared_" + key] = m.fuse_shared(to_dev(xi.make_shared_weights(cfg, key), dt), key)
+            w[key][cfg.E:].copy_(to_dev(xi.make_shared_weights(cfg, key), dt))
     grads = {"dw_router": torch.empty_like(w["w_router"])}
     for key in ("wg", "wu", "wd"):
         grads["d" + key] = torch.empty_like(w[key])
-        if cfg.E_s:
-            grads["dshared_" + key] = torch.empty_like(w["shared_" + key])
     x_np, dout_np = xi.make_x(cfg), xi.make_dout(cfg)
     x, dout = to_dev(x_np, dt), to_dev(dout_np, dt)
     layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
@@ -151,7 +150,7 @@ def verify_sampled(cfg, n_experts, n_tokens, seed=0):
     e_dx = assert_close_chain(to_host(dx[tsel]), want_dx, dt, "dx rows")
     print(cfg.name, "experts", chosen, "tokens", len(toks), "out", e_out, "dx", e_dx)
     # activation footprint held for backward (Xd, Y, G, U) equals the closed form s*T*k*(2d+2f)
-    held = sum(t_.numel() * t_.element_size() for t_ in (layer.xd, layer.y, layer.g, layer.u))
+    held = sum(t_.numel() * t_.element_size() for t_ in (layer.xd[:layer.B], layer.y[:layer.B], layer.g[:layer.B], layer.u[:layer.B]))
     assert held == oracle.activation_bytes(T, k, cfg.d, cfg.f, 2 if dt == "bf16" else 4)
 
 

@@ -144,8 +144,12 @@ def test_dispatch_combine_and_backward(name):
     want = oracle.combine(Y.astype(np.float64), eri["token_ids"], eri["combine_weights"].astype(np.float32), cfg.T)
     assert_close(to_host(out), want, dt, "combine", scale=0.5, floor="row")
     add = xi.round_to_storage(inp["dout"], dt)
-    m.xmoe_combine(to_dev(Y, dt), ros, tw, to_dev(add, dt), to_dev(inp["x"], dt), cfg.k, out)
-    assert_close(to_host(out), want + add + inp["x"], dt, "combine+addends", scale=0.5, floor="row")
+    m.xmoe_combine(to_dev(Y, dt), ros, tw, None, to_dev(add, dt), cfg.k, out)
+    assert_close(to_host(out), want + add, dt, "combine+addend", scale=0.5, floor="row")
+    # two all-token experts' rows (stand-ins: dout and x stacked) plus an addend
+    sh = np.concatenate([add, inp["x"]], axis=0)
+    m.xmoe_combine(to_dev(Y, dt), ros, tw, to_dev(sh, dt), to_dev(add, dt), cfg.k, out)
+    assert_close(to_host(out), want + 2 * add + inp["x"], dt, "combine+shared+addend", scale=0.5, floor="row")
 
     # combine backward
     dy = torch.empty((cfg.B, cfg.d), dtype=x.dtype, device="cuda")
@@ -236,14 +240,11 @@ def run_layer(cfg, inp):
     dt = cfg.dtype
     tdt = torch_dtype(dt)
     layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
-    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"]),
-         "wg": to_dev(inp["wg"], dt), "wu": to_dev(inp["wu"], dt), "wd": to_dev(inp["wd"], dt)}
-    grads = {"dw_router": torch.empty_like(w["w_router"]), "dwg": torch.empty_like(w["wg"]),
-             "dwu": torch.empty_like(w["wu"]), "dwd": torch.empty_like(w["wd"])}
-    if cfg.E_s > 0:
-        for k_ in ("wg", "wu", "wd"):
-            w["shared_" + k_] = m.fuse_shared(to_dev(inp["shared_" + k_], dt), k_)
-            grads["dshared_" + k_] = torch.empty_like(w["shared_" + k_])
+    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"])}
+    grads = {"dw_router": torch.empty_like(w["w_router"])}
+    for k_ in ("wg", "wu", "wd"):
+        w[k_] = m.append_shared(to_dev(inp[k_], dt), to_dev(inp["shared_" + k_], dt) if cfg.E_s > 0 else None)
+        grads["d" + k_] = torch.empty_like(w[k_])
     x, dout = to_dev(inp["x"], dt), to_dev(inp["dout"], dt)
     out = layer.forward(x, w)
     dx = layer.backward(x, w, dout, grads)
@@ -263,16 +264,16 @@ def check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads):
     assert rel_err(to_host(layer.combine_weights), eri["combine_weights"]) <= 1e-5
     errs = {}
     errs["out"] = assert_close_chain(to_host(out), fwd["out"], dt, "out")
-    errs["Y"] = assert_close_chain(to_host(layer.y), fwd["Y"], dt, "Y")
+    errs["Y"] = assert_close_chain(to_host(layer.y[:cfg.B]), fwd["Y"], dt, "Y")
     errs["dx"] = assert_close_chain(to_host(dx), bwd["dx"], dt, "dx")
     errs["dw_router"] = assert_close_chain(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router", floor="tensor",
                                            norm="tensor")
     for k_ in ("dwg", "dwu", "dwd"):
-        errs[k_] = assert_close_chain(to_host(grads[k_]), bwd[k_], dt, k_, floor="row")
-    if cfg.E_s > 0:
+        errs[k_] = assert_close_chain(to_host(grads[k_][:cfg.E]), bwd[k_], dt, k_, floor="row")
+    if cfg.E_s > 0:   # the shared experts' gradients follow the routed ones
         for k_ in ("wg", "wu", "wd"):
-            got = m.unfuse_shared_grad(grads["dshared_" + k_], k_, cfg.E_s)
-            errs["dshared_" + k_] = assert_close_chain(to_host(got), bwd["dshared_" + k_], dt, "dshared_" + k_, floor="row")
+            errs["dshared_" + k_] = assert_close_chain(to_host(grads["d" + k_][cfg.E:]), bwd["dshared_" + k_], dt,
+                                                       "dshared_" + k_, floor="row")
     return errs
 
 
