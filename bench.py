@@ -31,7 +31,10 @@ def parse_args():
     ap.add_argument("--workload", default="dsmoe16b",
                     help="dsmoe16b (default, the config the metric is quoted on), dsmoe16b_skew, large, longseq[-T<N>], ...")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run the library's plain copy kernel once over 1 GiB (a kernel of known traffic, "
+                         "for scaling hardware byte counters under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -49,7 +52,8 @@ def kernel_work(cfg):
     T, d, E, k, f, B = cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.B
     Ts = cfg.E_s * T
     rf = (B + Ts) * f
-    flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf}
+    flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf,
+             "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf}
     bytes_ = {
         # forward: unique rows read once + rows written; backward (E_s > 0): dout copied to the shared segments
         "dispatch_kernel": (T + B + Ts) * d * s + ((T + Ts) * d * s if Ts else 0),
@@ -60,6 +64,29 @@ def kernel_work(cfg):
         "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
     }
     return flops, bytes_
+
+
+# profiler kernel name -> entry of kernel_work()'s flop table
+GEMM_WORK = {
+    "ffn_gateup_dma_kernel": "gateup", "ffn_rowgemm_dma_kernel<false>": "down",
+    "ffn_rowgemm_dma_kernel<true>": "dact", "ffn_dx_dma_kernel": "dx",
+    "ffn_wgrad_dma_kernel<false>": "wgrad_wd", "ffn_wgrad_dma_kernel<true>": "wgrad_wg_wu",
+}
+for _fam in ("mfma", "simt"):
+    for _k in ("gateup", "down", "dact", "dx", "wgrad"):
+        GEMM_WORK[f"ffn_{_k}_{_fam}_kernel"] = _k
+
+# HBM bytes per launch of the dominant kernel read from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
+# the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
+MEASURED_TRAFFIC_BYTES = {
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3244168167,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1344159724,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2504781123,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2798530131,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1499797249,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3342241753,
+}
 
 
 def main():
@@ -109,6 +136,13 @@ def main():
         layer.forward(x, w)
         layer.backward(x, w, dout, grads)
 
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        xm.xmoe_prof_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -145,24 +179,23 @@ def main():
         per_step_ms = total_ms / args.steps
         ent = {"launches_per_step": launches / args.steps, "ms_per_step": round(per_step_ms, 5),
                "avg_launch_us": round(total_ms * 1e3 / launches, 3)}
-        for key, fl in flops.items():
-            if name.startswith("ffn_" + key + "_"):
-                ent["tflops"] = round(fl / (per_step_ms * 1e-3) / 1e12, 3)
-                ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
+        if name in GEMM_WORK:
+            ent["tflops"] = round(flops[GEMM_WORK[name]] / (per_step_ms * 1e-3) / 1e12, 3)
+            ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
         if name in bytes_:
             ent["gbs"] = round(bytes_[name] / (per_step_ms * 1e-3) / 1e9, 2)
             ent["frac_hbm_peak"] = round(ent["gbs"] / PEAK_HBM_GBS, 5)
         kernels[name] = ent
     gemm_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith("ffn_"))
-    total_flops = sum(flops.values())
+    total_flops = sum(flops[k_] for k_ in ("gateup", "down", "dact", "dx", "wgrad"))
     dom = max((n for n in kernels if n.startswith("ffn_")), key=lambda n: kernels[n]["ms_per_step"])
-    dom_key = dom.split("_")[1]
+    dom_key = GEMM_WORK[dom]
     roofline = {
         "bound": "mfma", "kernel": dom,
         "achieved": kernels[dom].get("tflops"), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
         "frac": round(kernels[dom].get("tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS, 5),
-        "traffic": None,
-        "flops_per_step": flops[dom_key], "launches_per_step": kernels[dom]["launches_per_step"],
+        "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
+        "flops_per_launch": flops[dom_key] / kernels[dom]["launches_per_step"], "launches_per_step": kernels[dom]["launches_per_step"],
         "avg_launch_us": kernels[dom]["avg_launch_us"],
         "all_gemm_tflops": round(total_flops / (gemm_ms * 1e-3) / 1e12, 3),
         "all_gemm_frac": round(total_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 5),

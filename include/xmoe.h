@@ -181,6 +181,10 @@ int xmoe_prof_num_kernels(void);                  /* number of kernel ids */
 const char* xmoe_prof_kernel_name(int kernel_id); /* name of the __global__ function behind a kernel id */
 /* Waits for all recorded events, then returns launches and total milliseconds of one kernel id. */
 int xmoe_prof_get(int kernel_id, int* launches, double* total_ms);
+/* A plain copy kernel, dst[0..bytes) = src[0..bytes): exactly `bytes` read and `bytes` written, the yardstick
+ * that hardware byte counters are scaled by.  Device pointers, 16-byte aligned; bytes a multiple of 16; the
+ * ranges must not overlap. */
+int xmoe_prof_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

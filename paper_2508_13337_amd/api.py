@@ -20,7 +20,7 @@ __all__ = [
     "XMoEError", "xmoe_version", "xmoe_workspace_bytes", "xmoe_gate_logits", "xmoe_route", "xmoe_build_eri",
     "xmoe_dispatch", "xmoe_expert_ffn_fwd", "xmoe_expert_ffn_bwd", "xmoe_combine", "xmoe_combine_bwd",
     "xmoe_dispatch_bwd", "xmoe_route_bwd", "xmoe_gate_logits_bwd", "xmoe_prof_enable", "xmoe_prof_reset",
-    "xmoe_prof_read", "dtype_code", "alloc_workspace",
+    "xmoe_prof_read", "xmoe_prof_copy", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD",
 ]
 
@@ -205,6 +205,13 @@ def xmoe_prof_enable(on: bool) -> None:
 
 def xmoe_prof_reset() -> None:
     lib().xmoe_prof_reset()
+
+
+def xmoe_prof_copy(src, dst) -> None:
+    """dst = src through the library's plain copy kernel (counter calibration)."""
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(lib().xmoe_prof_copy(_ptr(src, None, "src"), _ptr(dst, None, "dst"), src.numel() * src.element_size(),
+                                _stream()), "xmoe_prof_copy")
 
 
 def xmoe_prof_read() -> dict:

@@ -43,6 +43,13 @@ const char* const kKernelNames[K_COUNT] = {
     "ffn_dact_mfma_kernel",
     "ffn_dx_mfma_kernel",
     "ffn_wgrad_mfma_kernel",
+    "ffn_gateup_dma_kernel",
+    "ffn_rowgemm_dma_kernel<false>",
+    "ffn_rowgemm_dma_kernel<true>",
+    "ffn_dx_dma_kernel",
+    "ffn_wgrad_dma_kernel<false>",
+    "ffn_wgrad_dma_kernel<true>",
+    "prof_copy_kernel",
 };
 
 hipEvent_t get_event() {
@@ -56,6 +63,13 @@ hipEvent_t get_event() {
     return e;
 }
 }  // namespace
+
+// A copy whose traffic is known exactly (bytes read + bytes written): the yardstick for hardware byte counters.
+__global__ __launch_bounds__(256) void prof_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                        size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
 
 void prof_begin(int kid, hipStream_t s) {
     (void)kid;
@@ -136,6 +150,20 @@ int xmoe_prof_get(int kernel_id, int* launches, double* total_ms) {
     }
     *launches = n;
     *total_ms = ms;
+    return XMOE_OK;
+}
+
+int xmoe_prof_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (bytes == 0) return XMOE_OK;
+    if (!src || !dst || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15u) ||
+        (reinterpret_cast<uintptr_t>(dst) & 15u))
+        return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 255) / 256;
+    const unsigned grid = (unsigned)(want < 8192 ? want : 8192);
+    XMOE_LAUNCH(K_PROF_COPY, s, hipLaunchKernelGGL(prof_copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src,
+                                                   (uint4*)dst, n16));
     return XMOE_OK;
 }
 

@@ -886,10 +886,10 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd;
     const int ntg = (a.f + 127) / 128, ntd = (a.d + TN - 1) / TN;
-    XMOE_LAUNCH(K_FFN_GATEUP_MFMA, s,
+    XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
                 hipLaunchKernelGGL(ffn_gateup_dma_kernel, dim3(round_up8((long)max_tiles * ntg)), dim3(512), kLdsBytes,
                                    s, xd, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g, (bf16_t*)a.u, (bf16_t*)a.act));
-    XMOE_LAUNCH(K_FFN_DOWN_MFMA, s,
+    XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.act, a.off, a.map, a.f, a.d, wd, (bf16_t*)a.y, nullptr,
                                    nullptr, nullptr, nullptr, nullptr));
@@ -906,22 +906,22 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                  *wd = (const bf16_t*)a.wd, *dy = (const bf16_t*)a.dy;
     bf16_t *dg = (bf16_t*)a.dg, *du = (bf16_t*)a.du, *act = (bf16_t*)a.act;
     const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
-    XMOE_LAUNCH(K_FFN_DACT_MFMA, s,
+    XMOE_LAUNCH(K_FFN_DACT_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntf)), dim3(512),
                                    kLdsBytes, s, dy, a.off, a.map, a.d, a.f, wd, nullptr, (const bf16_t*)a.g,
                                    (const bf16_t*)a.u, dg, du, act));
-    XMOE_LAUNCH(K_FFN_DX_MFMA, s,
+    XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
                                    du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd));
     // dWd [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
-    XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
+    XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                 hipLaunchKernelGGL(ffn_wgrad_dma_kernel<false>, dim3(round_up8((long)a.E * mtf * ntd)), dim3(512),
                                    kLdsBytes, s, act, dy, nullptr, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
                                    (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     const int ntf2 = (a.f + 127) / 128;
-    XMOE_LAUNCH(K_FFN_WGRAD_MFMA, s,
+    XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                 hipLaunchKernelGGL(ffn_wgrad_dma_kernel<true>, dim3(round_up8((long)a.E * mtd * ntf2)), dim3(512),
                                    kLdsBytes, s, xd, dg, du, a.off, a.sched, a.sched + a.E + kNumXcd, a.E, a.d, a.f,
                                    (bf16_t*)a.dwg, (bf16_t*)a.dwu));

@@ -35,6 +35,13 @@ enum KernelId : int {
     K_FFN_DACT_MFMA,
     K_FFN_DX_MFMA,
     K_FFN_WGRAD_MFMA,
+    K_FFN_GATEUP_DMA,
+    K_FFN_DOWN_DMA,
+    K_FFN_DACT_DMA,
+    K_FFN_DX_DMA,
+    K_FFN_WGRAD_DMA,
+    K_FFN_WGRAD_DUAL_DMA,
+    K_PROF_COPY,
     K_COUNT
 };
 
