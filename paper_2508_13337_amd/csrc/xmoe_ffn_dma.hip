@@ -251,6 +251,51 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // workgroup barrier that waits only for the wave's LDS traffic (result stores stay in flight)
 __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// One k-tile of the main loop: refill stage `st_next` with k-tile nt, finish reading the current tile `st` (second
+// 16-wide k-step) and fetch the first k-step of the next tile `st1` while the MFMAs run.  The three stages are
+// distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS read may observe a
+// direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0)) before each transposing
+// read, which serialises the ring.
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
+__device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1, const Loader<A_COL, TWO>& la,
+                                      const Loader<B_COL, TWO>& lb, char* __restrict__ st_next,
+                                      const char* __restrict__ st, const char* __restrict__ st1, int nt) {
+    la.issue(st_next, nt, kProbeNoA);
+    lb.issue(st_next + kOpBytes, nt, kProbeNoB);
+#ifdef XMOE_PROBE_HALFLDS
+    f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
+#else
+    read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
+#endif
+    mma_step(acc, f0);
+    read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
+    mma_step(acc, f1);
+    if (A_COL || B_COL) {
+        // instruction order: every MFMA is followed by a share of the k-tile's direct-to-LDS loads and LDS
+        // fragment reads (0x008 = MFMA, 0x010 = vector memory, 0x100 = LDS read)
+        constexpr int kReadsPerStep = (A_COL ? 8 : 4) + (B_COL ? 4 : 2);   // LDS reads of one k-step
+        constexpr int kRd = (kReadsPerStep + 5) / 6;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+}
+
 // acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
 // 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
@@ -285,43 +330,9 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         read_frags<A_COL, B_COL, DUAL>(f0, smem, smem + kOpBytes, 0);
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
-            char* st_next = smem + (nt % kStages) * kStageBytes;
-            la.issue(st_next, nt, kProbeNoA);
-            lb.issue(st_next + kOpBytes, nt, kProbeNoB);
-            const char* st = smem + (kt % kStages) * kStageBytes;
-#ifdef XMOE_PROBE_HALFLDS
-            f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
-#else
-            read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
-#endif
-            mma_step(acc, f0);
-            const char* st1 = smem + ((kt + 1) % kStages) * kStageBytes;
-            read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
-            mma_step(acc, f1);
-            if (A_COL || B_COL) {
-            // instruction order: every MFMA is followed by a share of the k-tile's direct-to-LDS loads and LDS
-            // fragment reads (0x008 = MFMA, 0x020 = VMEM read, 0x100 = LDS read)
-            constexpr int kReadsPerStep = (A_COL ? 8 : 4) + (B_COL ? 4 : 2);   // LDS reads of one k-step
-            constexpr int kRd = (kReadsPerStep + 5) / 6;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-#pragma unroll
-            for (int j = 0; j < 6; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, kRd, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            }
+            kstep<A_COL, B_COL, DUAL, TWO>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
+                                           smem + (kt % kStages) * kStageBytes,
+                                           smem + ((kt + 1) % kStages) * kStageBytes, nt);
             wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
         }
     } else {
