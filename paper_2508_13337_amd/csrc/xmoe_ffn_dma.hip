@@ -370,6 +370,12 @@ __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& o
 #define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)
 #endif
 
+// sigmoid with the hardware exp2 and reciprocal (each good to about 1 ulp): the results are rounded to bf16, and
+// the library-grade expf and IEEE division cost as much as a quarter of a tile's main loop in the fused epilogues.
+__device__ __forceinline__ float fast_sigmoid(float g) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * g));
+}
+
 __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[4][2]) {
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
@@ -384,6 +390,7 @@ __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[4][2]) {
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kStripStride = 200;                 // bytes per staged row (96 columns + 8 bytes: conflict-free)
 constexpr int kStripBytes = 32 * kStripStride;    // per wave
+constexpr int kInBytes = 2 * 32 * 64;             // per wave: 32 x 32 bf16 of G and of U (dAct epilogue)
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
     return make_uint2((uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16),
@@ -555,7 +562,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
         for (int v = 0; v < 16; ++v) {
             g[v] = acc[mi][0][v];
             u[v] = acc[mi][1][v];
-            s[v] = siluf_(g[v]) * u[v];
+            s[v] = g[v] * fast_sigmoid(g[v]) * u[v];
         }
         const int r0 = wm * 128 + mi * 32;
         const int rows_valid = rt.rows - r0;
@@ -638,23 +645,26 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
         }
     }
     if (DACT) {
-        // 8 rounds (mi, ni) of 32 x 32 outputs.  G and U of round r+1 are fetched while round r is computed and
-        // stored, so that only the first round pays the memory latency.
+        // 8 rounds (mi, ni) of 32 x 32 outputs.  G and U of a round are fetched as full 64-byte row pieces (4 lanes
+        // per row, 16 rows per instruction) while the previous round is computed and stored, then turned into the
+        // accumulator layout through a wave-private LDS buffer (rows of 64 bytes, 16-byte chunks XOR-swizzled).
         const int m = lane & 31;
-        uint2 gq[2][4], uq[2][4];
-        auto fetch = [&](int r, uint2 (&g4)[4], uint2 (&u4)[4]) {
+        char* inbuf = smem + 8 * kStripBytes + wave * kInBytes;   // G rows, then U rows
+        uint4 gq[2][2], uq[2][2];
+        const int frow = lane >> 2, fchunk = lane & 3;
+        auto fetch = [&](int r, uint4 (&g2)[2], uint4 (&u2)[2]) {
             const int mi = r >> 1, ni = r & 1;
             const int r0 = wm * 128 + mi * 32;
             const int rows_valid = rt.rows - r0;
-            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
+            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64 + ni * 32;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = ni * 32 + 8 * q + 4 * (lane >> 5);
-                g4[q] = make_uint2(0, 0);
-                u4[q] = make_uint2(0, 0);
-                if (m < rows_valid && c < cols_valid) {
-                    g4[q] = *reinterpret_cast<const uint2*>(G + base + (long)m * N + c);
-                    u4[q] = *reinterpret_cast<const uint2*>(U + base + (long)m * N + c);
+            for (int i = 0; i < 2; ++i) {
+                const int row = 16 * i + frow;
+                g2[i] = make_uint4(0, 0, 0, 0);
+                u2[i] = make_uint4(0, 0, 0, 0);
+                if (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid) {
+                    g2[i] = *reinterpret_cast<const uint4*>(G + base + (long)row * N + fchunk * 8);
+                    u2[i] = *reinterpret_cast<const uint4*>(U + base + (long)row * N + fchunk * 8);
                 }
             }
         };
@@ -662,21 +672,36 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int mi = r >> 1, ni = r & 1;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = 16 * i + frow;
+                const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
+                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = gq[r & 1][i];
+                *reinterpret_cast<uint4*>(inbuf + 2048 + row * 64 + pos) = uq[r & 1][i];
+            }
             if (r + 1 < 8) fetch(r + 1, gq[(r + 1) & 1], uq[(r + 1) & 1]);
+            strip_sync();
             const int r0 = wm * 128 + mi * 32;
             const int rows_valid = rt.rows - r0;
             const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
+            uint2 gv[4], uv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
+                const int off = m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5);
+                gv[q] = *reinterpret_cast<const uint2*>(inbuf + off);
+                uv[q] = *reinterpret_cast<const uint2*>(inbuf + 2048 + off);
+            }
             float dg[16], du[16], av[16];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint32_t gw[2] = {gq[r & 1][q].x, gq[r & 1][q].y}, uw[2] = {uq[r & 1][q].x, uq[r & 1][q].y};
+                const uint32_t gw[2] = {gv[q].x, gv[q].y}, uw[2] = {uv[q].x, uv[q].y};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
                     const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
                     const float g = __uint_as_float(gb), u = __uint_as_float(ub);
                     const float da = acc[mi][ni][4 * q + j];
-                    const float sg = sigmoidf_(g);
+                    const float sg = fast_sigmoid(g);
                     const float sl = g * sg;
                     dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
                     du[4 * q + j] = da * sl;
