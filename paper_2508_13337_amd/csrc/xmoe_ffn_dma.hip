@@ -217,6 +217,13 @@ __device__ __forceinline__ int b_col(int wn, int ni) { return DUAL ? ni * 128 + 
 struct Frags {
     bf16x8_t a[4], b[2];
 };
+__device__ __forceinline__ void zero_frags(Frags& f) {
+    const s16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f.a[i] = __builtin_bit_cast(bf16x8_t, z);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) f.b[i] = __builtin_bit_cast(bf16x8_t, z);
+}
 
 template <bool A_COL, bool B_COL, bool DUAL>
 __device__ __forceinline__ void read_frags(Frags& f, const char* ta, const char* tb, int ks) {
@@ -241,35 +248,41 @@ __device__ __forceinline__ void mma_step(f32x16_t (&acc)[4][2], const Frags& f) 
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
 }
 
-// waits until at most N of this wave's vector-memory operations are outstanding, then joins the workgroup barrier.
+// waits until at most N of this wave's vector-memory operations are outstanding and all of its LDS reads have
+// returned (fragments carried across the barrier must be out of the stage that is refilled after it), then joins
+// the workgroup barrier.
 // Written as one asm block: __syncthreads() would make the compiler wait for ALL outstanding direct-to-LDS loads
 // (they are memory writes the fence has to cover) and so serialise the load ring.
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 // workgroup barrier that waits only for the wave's LDS traffic (result stores stay in flight)
 __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// One k-tile of the main loop: refill stage `st_next` with k-tile nt, finish reading the current tile `st` (second
-// 16-wide k-step) and fetch the first k-step of the next tile `st1` while the MFMAs run.  The three stages are
-// distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS read may observe a
-// direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0)) before each transposing
-// read, which serialises the ring.
+// One k-tile of the main loop.  On entry k-tile kt has landed in `st`, every wave has finished reading the stage
+// `st_next` (k-tile kt-1), and f1 still holds the second 16-wide k-step of k-tile kt-1.  The body refills st_next
+// with k-tile nt = kt+3, fetches the first k-step of k-tile kt while the MFMAs of the carried f1 run, then fetches
+// the second k-step while the MFMAs of the first run; the second k-step's MFMAs are carried into the next call.
+// Carrying work, rather than fragments of the NEXT tile, across the barrier keeps three k-tiles of loads in
+// flight instead of two, which is what the loop is bound by (memory latency / tiles in flight).
+// The two stages are distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS
+// read may observe a direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0))
+// before each transposing read, which serialises the ring.
 template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
 __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1, const Loader<A_COL, TWO>& la,
                                       const Loader<B_COL, TWO>& lb, char* __restrict__ st_next,
-                                      const char* __restrict__ st, const char* __restrict__ st1, int nt) {
+                                      const char* __restrict__ st, int nt) {
     la.issue(st_next, nt, kProbeNoA);
     lb.issue(st_next + kOpBytes, nt, kProbeNoB);
+    read_frags<A_COL, B_COL, DUAL>(f0, st, st + kOpBytes, 0);
+    mma_step(acc, f1);
 #ifdef XMOE_PROBE_HALFLDS
     f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
 #else
     read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
 #endif
     mma_step(acc, f0);
-    read_frags<A_COL, B_COL, DUAL>(f0, st1, st1 + kOpBytes, 0);   // tile kt+1 (zeros past the end)
-    mma_step(acc, f1);
     if (A_COL || B_COL) {
         // instruction order: every MFMA is followed by a share of the k-tile's direct-to-LDS loads and LDS
         // fragment reads (0x008 = MFMA, 0x010 = vector memory, 0x100 = LDS read)
@@ -319,22 +332,22 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         la.issue(smem + s * kStageBytes, s, kProbeNoA);
         lb.issue(smem + s * kStageBytes + kOpBytes, s, kProbeNoB);
     }
-    // Invariant at the top of iteration kt (established by the barrier before it): k-tiles <= kt+1 have landed
-    // for every thread, and every wave is done reading k-tile kt-1.  So the stage of tile kt-1 can be refilled,
-    // and the fragments of the first k-step of tile kt+1 can be fetched while the MFMAs of tile kt still run -
-    // the LDS latency after each barrier is hidden behind the previous tile's matrix work.
-    wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
+    // Invariant at the top of iteration kt (established by the barrier before it): k-tiles <= kt have landed for
+    // every thread, and every wave is done reading k-tile kt-1, so that stage can be refilled with k-tile kt+3:
+    // k-tiles kt+1 .. kt+3 are in flight while k-tile kt is multiplied.
+    constexpr int kInFlight = (kStages - 2) * kLoadsPerTile;   // loads that may still be outstanding at the barrier
+    wait_loads_and_barrier<kInFlight>();
     PROBE_MARK(probe_idx, 1)
     if (mi_count > 0) {
         Frags f0, f1;
-        read_frags<A_COL, B_COL, DUAL>(f0, smem, smem + kOpBytes, 0);
+        zero_frags(f1);   // the first call multiplies the carried fragments: zeros
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
             kstep<A_COL, B_COL, DUAL, TWO>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
-                                           smem + (kt % kStages) * kStageBytes,
-                                           smem + ((kt + 1) % kStages) * kStageBytes, nt);
-            wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
+                                           smem + (kt % kStages) * kStageBytes, nt);
+            wait_loads_and_barrier<kInFlight>();
         }
+        mma_step(acc, f1);   // second k-step of the last k-tile
     } else {
         // a wave whose rows (or columns) all lie past the ragged tail: it only feeds the ring and keeps the barriers
         for (int kt = 0; kt < nk; ++kt) {
@@ -342,7 +355,7 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
             char* st_next = smem + (nt % kStages) * kStageBytes;
             la.issue(st_next, nt, kProbeNoA);
             lb.issue(st_next + kOpBytes, nt, kProbeNoB);
-            wait_loads_and_barrier<(kStages - 3) * kLoadsPerTile>();
+            wait_loads_and_barrier<kInFlight>();
         }
     }
     // all loads of this tile (and the dummy ones past its end) have landed before the ring is reused as staging
