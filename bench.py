@@ -80,12 +80,12 @@ for _fam in ("mfma", "simt"):
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3244168167,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1344159724,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2504781123,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2798530131,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1499797249,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3342241753,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3437606157,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1426612227,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2454799955,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2815407890,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1563306155,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3336312843,
 }
 
 
