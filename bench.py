@@ -63,6 +63,13 @@ def kernel_work(cfg):
         "route_kernel": T * E * 4 + T * k * 8,
         "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
     }
+    # algorithmic bytes of the GEMM kernels: every operand read once, every result written once
+    R, W = B + Ts, (E + cfg.E_s) * d * f * s
+    gemm_bytes = {"gateup": R * d * s + 2 * W + 3 * R * f * s, "down": R * f * s + W + R * d * s,
+                  "dact": R * d * s + W + 5 * R * f * s, "dx": 2 * R * f * s + 2 * W + R * d * s,
+                  "wgrad_wd": R * f * s + R * d * s + W, "wgrad_wg_wu": R * d * s + 2 * R * f * s + 2 * W}
+    gemm_bytes["wgrad"] = gemm_bytes["wgrad_wd"] + gemm_bytes["wgrad_wg_wu"]
+    bytes_.update({"gemm:" + k_: v for k_, v in gemm_bytes.items()})
     return flops, bytes_
 
 
@@ -182,6 +189,8 @@ def main():
         if name in GEMM_WORK:
             ent["tflops"] = round(flops[GEMM_WORK[name]] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
+        if name in GEMM_WORK:
+            ent["algorithmic_gbs"] = round(bytes_["gemm:" + GEMM_WORK[name]] / (per_step_ms * 1e-3) / 1e9, 1)
         if name in bytes_:
             ent["gbs"] = round(bytes_[name] / (per_step_ms * 1e-3) / 1e9, 2)
             ent["frac_hbm_peak"] = round(ent["gbs"] / PEAK_HBM_GBS, 5)
@@ -190,12 +199,22 @@ def main():
     total_flops = sum(flops[k_] for k_ in ("gateup", "down", "dact", "dx", "wgrad"))
     dom = max((n for n in kernels if n.startswith("ffn_")), key=lambda n: kernels[n]["ms_per_step"])
     dom_key = GEMM_WORK[dom]
+    # which roof binds the dominant kernel: the one that needs longer at its peak for the kernel's algorithmic work
+    dom_flops = flops[dom_key] / kernels[dom]["launches_per_step"]
+    dom_bytes = bytes_["gemm:" + dom_key] / kernels[dom]["launches_per_step"]
+    dom_s = kernels[dom]["avg_launch_us"] * 1e-6
+    hbm_bound = dom_bytes / (PEAK_HBM_GBS * 1e9) > dom_flops / (PEAK_BF16_MFMA_TFLOPS * 1e12)
     roofline = {
-        "bound": "mfma", "kernel": dom,
-        "achieved": kernels[dom].get("tflops"), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(kernels[dom].get("tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS, 5),
+        "bound": "hbm" if hbm_bound else "mfma", "kernel": dom,
+        "achieved": round(dom_bytes / dom_s / 1e9, 2) if hbm_bound else kernels[dom].get("tflops"),
+        "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_MFMA_TFLOPS, "unit": "GB/s" if hbm_bound else "TFLOP/s",
+        "frac": round(dom_bytes / dom_s / 1e9 / PEAK_HBM_GBS, 5) if hbm_bound
+                else round(kernels[dom].get("tflops", 0.0) / PEAK_BF16_MFMA_TFLOPS, 5),
         "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, dom)),
-        "flops_per_launch": flops[dom_key] / kernels[dom]["launches_per_step"], "launches_per_step": kernels[dom]["launches_per_step"],
+        "flops_per_launch": dom_flops, "algorithmic_bytes_per_launch": dom_bytes,
+        "frac_mfma_peak": round(dom_flops / dom_s / 1e12 / PEAK_BF16_MFMA_TFLOPS, 5),
+        "frac_hbm_peak": round(dom_bytes / dom_s / 1e9 / PEAK_HBM_GBS, 5),
+        "launches_per_step": kernels[dom]["launches_per_step"],
         "avg_launch_us": kernels[dom]["avg_launch_us"],
         "all_gemm_tflops": round(total_flops / (gemm_ms * 1e-3) / 1e12, 3),
         "all_gemm_frac": round(total_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 5),
@@ -209,6 +228,10 @@ def main():
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "E_s": cfg.E_s, "k": cfg.k, "f": cfg.f,
                    "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
         "fwd_only_ms": round(fwd_ms, 4),
+        "fwd_only_tokens_per_s": round(cfg.T / (fwd_ms * 1e-3), 1),
+        # what stays allocated between forward and backward for the routed rows: Xd, Y, G, U
+        "activation_bytes_held": sum(t_[:layer.B].numel() * t_.element_size()
+                                     for t_ in (layer.xd, layer.y, layer.g, layer.u)),
         "layer_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "grouped_gemm_pct_mfma_peak": round(100 * roofline["all_gemm_frac"], 3),
         "roofline": roofline,
