@@ -125,6 +125,51 @@ def build_eri(topk_idx: np.ndarray, topk_w: np.ndarray, E: int) -> dict:
     }
 
 
+def build_eri_capped(topk_idx: np.ndarray, topk_w: np.ndarray, E: int, max_token_count: int) -> dict:
+    """PFT construction with token dropping (Listing 1 PFT_construction(); Appendix B.2): every expert keeps at
+    most max_token_count of the rows routed to it, the ones with the largest combine weights.
+
+    The steps are the listing's, in its order: (1) sort the flat assignments by expert; (2) order the flat entries
+    by combine weight, one-hot encode their experts, running count per expert down that order (rank_in_expert), keep
+    an entry while its expert's count has not passed max_token_count; prune the arrays of step 1 to the retained
+    entries; histogram.  Readings: the order by weight is descending (the largest weights are kept, Appendix B.2),
+    entries of equal weight keep the lower flat index first, and the rank test is inclusive (rank <= max_token_count,
+    as in the listing).  row_of_slot[n] is the retained row of flat entry n, or -1 if the entry was dropped."""
+    T, k = topk_idx.shape
+    B = T * k
+    C = int(max_token_count)
+    # step 1: expert ids and token ids of all entries, sorted by expert (stable)
+    flat_top_experts = topk_idx.reshape(-1).astype(np.int64)
+    by_expert = np.argsort(flat_top_experts, kind="stable")
+    token_ids = (by_expert // k).astype(np.int32)
+    expert_ids = flat_top_experts[by_expert].astype(np.int32)
+    # step 2: which entries survive
+    flat_combine_weights = np.asarray(topk_w).reshape(-1)
+    sorted_indices = np.argsort(-flat_combine_weights, kind="stable")        # heaviest first, ties: lower index
+    sorted_top_experts = flat_top_experts[sorted_indices]
+    one_hot_enc = np.zeros((B, E), dtype=np.int64)
+    one_hot_enc[np.arange(B), sorted_top_experts] = 1
+    rank_in_expert = np.cumsum(one_hot_enc, axis=0)
+    weight_mask = ((rank_in_expert <= C) & (one_hot_enc == 1)).any(axis=1)
+    filtered_indices = sorted_indices[weight_mask]                           # retained flat entries
+    retained = np.zeros(B, dtype=bool)
+    retained[filtered_indices] = True
+    retained_rows = retained[by_expert]                                      # in the order of step 1
+    kept = by_expert[retained_rows]
+    token_ids = token_ids[retained_rows]
+    expert_ids = expert_ids[retained_rows]
+    combine_weights = flat_combine_weights[kept]
+    tokens_per_expert = np.bincount(expert_ids, minlength=E).astype(np.int32)
+    expert_offsets = np.zeros(E + 1, dtype=np.int32)
+    expert_offsets[1:] = np.cumsum(tokens_per_expert)
+    row_of_slot = np.full(B, -1, dtype=np.int32)
+    row_of_slot[kept] = np.arange(kept.size, dtype=np.int32)
+    return {
+        "token_ids": token_ids, "expert_ids": expert_ids, "tokens_per_expert": tokens_per_expert,
+        "expert_offsets": expert_offsets, "combine_weights": combine_weights, "row_of_slot": row_of_slot,
+    }
+
+
 # ----------------------------------------------------------------------------------------------------------
 # dispatch / mlp / combine (Listing 1; Section 4.1.2; Appendix B.4)
 # ----------------------------------------------------------------------------------------------------------
@@ -187,10 +232,11 @@ def shared_ffn_fwd(x, swg, swu, swd):
 # ----------------------------------------------------------------------------------------------------------
 # whole layer
 # ----------------------------------------------------------------------------------------------------------
-def moe_layer_fwd(inp: dict, k: int, logits_mode: str = "contract") -> dict:
+def moe_layer_fwd(inp: dict, k: int, logits_mode: str = "contract", max_token_count: Optional[int] = None) -> dict:
     """Listing 1's call(): gating -> PFT_construction -> dispatch -> mlp -> combine (+ shared experts).
 
-    inp: x [T,d], w_router [d,E], bias [E]|None, wg/wu [E,d,f], wd [E,f,d], shared_wg/wu/wd [E_s,...]."""
+    inp: x [T,d], w_router [d,E], bias [E]|None, wg/wu [E,d,f], wd [E,f,d], shared_wg/wu/wd [E_s,...].
+    max_token_count: None = dropless; else the per-expert capacity of the token-dropping PFT construction."""
     x = np.asarray(inp["x"], np.float64)
     T = x.shape[0]
     E = inp["wg"].shape[0]
@@ -199,7 +245,8 @@ def moe_layer_fwd(inp: dict, k: int, logits_mode: str = "contract") -> dict:
     else:
         logits = gate_logits_f64(inp["x"], inp["w_router"], inp.get("bias"))
     topk_idx, topk_w, p = route(logits, k)
-    eri = build_eri(topk_idx, topk_w, E)
+    eri = build_eri(topk_idx, topk_w, E) if max_token_count is None else \
+        build_eri_capped(topk_idx, topk_w, E, max_token_count)
     Xd = dispatch(x, eri["token_ids"])
     Y, G, U = expert_ffn_fwd(Xd, eri["expert_offsets"], inp["wg"], inp["wu"], inp["wd"])
     out = combine(Y, eri["token_ids"], eri["combine_weights"], T)
@@ -244,14 +291,17 @@ def moe_dense_definition(inp: dict, k: int, logits: np.ndarray) -> np.ndarray:
 # backward (derived: the paper only says it mirrors the forward, Section 4.3)
 # ----------------------------------------------------------------------------------------------------------
 def combine_bwd(dout, Y, token_ids, combine_weights, row_of_slot, k):
-    """dY[i] = combine_weights[i] * dOut[token_ids[i]];  dw[t,j] = <dOut[t], Y[row_of_slot[t*k+j]]>."""
+    """dY[i] = combine_weights[i] * dOut[token_ids[i]];  dw[t,j] = <dOut[t], Y[row_of_slot[t*k+j]]>, and 0 for a
+    dropped entry (row_of_slot < 0): the output does not depend on its weight."""
     dout = np.asarray(dout, np.float64)
     T = dout.shape[0]
     dY = combine_weights[:, None] * dout[token_ids]
     dw = np.zeros((T, k))
     for t in range(T):
         for j in range(k):
-            dw[t, j] = np.dot(dout[t], Y[row_of_slot[t * k + j]])
+            r = row_of_slot[t * k + j]
+            if r >= 0:
+                dw[t, j] = np.dot(dout[t], Y[r])
     return dY, dw
 
 
@@ -288,11 +338,13 @@ def expert_ffn_bwd(Xd, G, U, dY, expert_offsets, wg, wu, wd):
 
 
 def dispatch_bwd(dXd, row_of_slot, T, k):
-    """dx[t] = sum_j dXd[row_of_slot[t*k+j]] (transpose of the gather)."""
+    """dx[t] = sum_j dXd[row_of_slot[t*k+j]] over the retained entries (transpose of the gather)."""
     dx = np.zeros((T, dXd.shape[1]))
     for t in range(T):
         for j in range(k):
-            dx[t] += dXd[row_of_slot[t * k + j]]
+            r = row_of_slot[t * k + j]
+            if r >= 0:
+                dx[t] += dXd[r]
     return dx
 
 

@@ -373,6 +373,124 @@ def test_backward_matches_torch_autograd(skew):
         assert np.abs(bwd[gname] - want).max() <= 1e-11 * scale, name
 
 
+# ------------------------------------------------------------------------------------------------ token dropping
+def _capped_brute_force(topk_idx, topk_w, E, C):
+    """Per expert: its (weight, flat index) pairs sorted by weight descending then index ascending, the first C kept,
+    the kept ones listed again in ascending flat index.  Plain Python."""
+    T, k = topk_idx.shape
+    flat_e = [int(v) for v in topk_idx.reshape(-1)]
+    flat_w = [float(v) for v in np.asarray(topk_w).reshape(-1)]
+    rows = []
+    for e in range(E):
+        mine = [n for n in range(T * k) if flat_e[n] == e]
+        best = sorted(mine, key=lambda n: (-flat_w[n], n))[:C]
+        rows.append(sorted(best))
+    return rows
+
+
+@pytest.mark.parametrize("T,E,k,C,seed", [(40, 5, 2, 7, 0), (64, 8, 3, 1, 1), (33, 4, 4, 10, 2), (100, 16, 2, 5, 3),
+                                          (17, 3, 1, 0, 4)])
+def test_capped_eri_brute_force(T, E, k, C, seed):
+    rng = np.random.default_rng(seed)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    idx, w, _ = oracle.route(logits, k)
+    got = oracle.build_eri_capped(idx, w, E, C)
+    rows = _capped_brute_force(idx, w, E, C)
+    flat = [n for r in rows for n in r]
+    assert got["token_ids"].tolist() == [n // k for n in flat]
+    assert got["expert_ids"].tolist() == [e for e, r in enumerate(rows) for _ in r]
+    assert got["tokens_per_expert"].tolist() == [len(r) for r in rows]
+    assert np.array_equal(got["combine_weights"], np.asarray(w).reshape(-1)[flat])
+    ros = np.full(T * k, -1)
+    ros[flat] = np.arange(len(flat))
+    assert np.array_equal(got["row_of_slot"], ros)
+
+
+def test_capped_eri_limits_and_invariants():
+    rng = np.random.default_rng(7)
+    T, E, k = 300, 12, 3
+    logits = (rng.standard_normal((T, E)) + np.linspace(0, 2.5, E)).astype(np.float32)   # uneven load
+    idx, w, _ = oracle.route(logits, k)
+    full = oracle.build_eri(idx, w, E)
+    # capacity at or above the largest segment: nothing is dropped, identical arrays
+    big = oracle.build_eri_capped(idx, w, E, int(full["tokens_per_expert"].max()))
+    for key in full:
+        assert np.array_equal(big[key], full[key]), key
+    C = int(np.median(full["tokens_per_expert"]))
+    cap = oracle.build_eri_capped(idx, w, E, C)
+    assert np.array_equal(cap["tokens_per_expert"], np.minimum(full["tokens_per_expert"], C))
+    assert cap["expert_offsets"][-1] == cap["token_ids"].size == (cap["row_of_slot"] >= 0).sum()
+    flat_w = np.asarray(w).reshape(-1)
+    flat_e = idx.reshape(-1)
+    kept = cap["row_of_slot"] >= 0
+    for e in range(E):
+        mine = flat_e == e
+        if (mine & ~kept).any():     # every dropped entry is no heavier than every kept one of the same expert
+            assert flat_w[mine & ~kept].max() <= flat_w[mine & kept].min()
+    # retained rows keep the order of the dropless table
+    rows_full = full["row_of_slot"][kept]
+    assert np.array_equal(np.argsort(rows_full, kind="stable"), np.argsort(cap["row_of_slot"][kept], kind="stable"))
+    assert np.all(np.diff(cap["expert_ids"]) >= 0)
+    for e in range(E):
+        seg = cap["token_ids"][cap["expert_offsets"][e]:cap["expert_offsets"][e + 1]]
+        assert np.all(np.diff(seg) > 0)
+    # capacity 0 drops everything
+    none = oracle.build_eri_capped(idx, w, E, 0)
+    assert none["token_ids"].size == 0 and not none["tokens_per_expert"].any() and (none["row_of_slot"] == -1).all()
+
+
+def test_capped_eri_equal_weights_keep_the_lower_flat_index():
+    T, E, k, C = 20, 3, 2, 4
+    idx = np.stack([np.arange(T) % E, (np.arange(T) + 1) % E], axis=1).astype(np.int32)
+    w = np.full((T, k), 0.25, dtype=np.float32)
+    got = oracle.build_eri_capped(idx, w, E, C)
+    flat_e = idx.reshape(-1)
+    for e in range(E):
+        first = np.flatnonzero(flat_e == e)[:C]
+        seg = slice(got["expert_offsets"][e], got["expert_offsets"][e + 1])
+        assert np.array_equal(got["token_ids"][seg], first // k)
+
+
+def _torch_dense_layer_masked(inp, k, topk_idx, keep):
+    """Dense definition with a constant keep mask on the (token, slot) pairs."""
+    x = inp["x"]
+    logits = x @ inp["w_router"]
+    p = torch.softmax(logits, dim=1)
+    out = torch.zeros_like(x)
+    for t in range(x.shape[0]):
+        for j in range(k):
+            if keep[t, j]:
+                e = int(topk_idx[t, j])
+                y = (torch.nn.functional.silu(x[t] @ inp["wg"][e]) * (x[t] @ inp["wu"][e])) @ inp["wd"][e]
+                out[t] = out[t] + p[t, e] * y
+    for s in range(inp["shared_wg"].shape[0]):
+        out = out + (torch.nn.functional.silu(x @ inp["shared_wg"][s]) * (x @ inp["shared_wu"][s])) @ inp["shared_wd"][s]
+    return out
+
+
+def test_layer_with_token_dropping_matches_masked_dense_definition_and_autograd():
+    cfg = xi.MoEConfig("drop", T=48, d=16, E=6, k=3, f=8, dtype="f32", E_s=1, router_std=0.4, w_std=0.3,
+                       skew_alpha=1.5, seed=5)
+    raw = xi.make_layer_inputs(cfg)
+    raw["bias"] = None
+    inp = {k_: (None if v is None else np.asarray(v, np.float64)) for k_, v in raw.items()}
+    C = 10
+    fwd = oracle.moe_layer_fwd(inp, cfg.k, logits_mode="f64", max_token_count=C)
+    bwd = oracle.moe_layer_bwd(inp, fwd, cfg.k)
+    assert fwd["eri"]["tokens_per_expert"].max() == C and (fwd["eri"]["row_of_slot"] < 0).any()
+    keep = (fwd["eri"]["row_of_slot"] >= 0).reshape(cfg.T, cfg.k)
+    tin = {k_: (None if v is None else torch.from_numpy(v.copy()).requires_grad_(k_ != "dout"))
+           for k_, v in inp.items()}
+    out = _torch_dense_layer_masked(tin, cfg.k, fwd["topk_idx"], keep)
+    assert np.allclose(out.detach().numpy(), fwd["out"], rtol=1e-11, atol=1e-15)
+    (out * tin["dout"]).sum().backward()
+    for name, gname in [("x", "dx"), ("w_router", "dw_router"), ("wg", "dwg"), ("wu", "dwu"), ("wd", "dwd"),
+                        ("shared_wg", "dshared_wg")]:
+        want = tin[name].grad.numpy()
+        assert np.abs(bwd[gname] - want).max() <= 1e-11 * (np.abs(want).max() + 1e-30), name
+    assert not bwd["dw"][~keep].any()
+
+
 def test_backward_structure():
     cfg = xi.CONFIGS["mini_bf16_skew"]
     inp = xi.make_layer_inputs(cfg)
