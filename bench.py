@@ -32,6 +32,9 @@ def parse_args():
                     help="dsmoe16b (default, the config the metric is quoted on), dsmoe16b_skew, large, longseq[-T<N>], ...")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--max-token-count", type=int, default=None,
+                    help="run the layer with the token-dropping PFT construction at this per-expert capacity "
+                         "(default: dropless, the configuration the metric is quoted on)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel once over 1 GiB (a kernel of known traffic, "
                          "for scaling hardware byte counters under rocprofv3 --pmc)")
@@ -136,7 +139,7 @@ def main():
     for key in ("wg", "wu", "wd"):
         grads["d" + key] = torch.empty_like(w[key])
     x, dout = dev(x_np), dev(dout_np)
-    layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
+    layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s, max_token_count=args.max_token_count)
     t_gen = time.time() - t_gen
 
     def step():
@@ -226,7 +229,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "E_s": cfg.E_s, "k": cfg.k, "f": cfg.f,
-                   "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
+                   "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "max_token_count": args.max_token_count, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
         "fwd_only_ms": round(fwd_ms, 4),
         "fwd_only_tokens_per_s": round(cfg.T / (fwd_ms * 1e-3), 1),
         # what stays allocated between forward and backward for the routed rows: Xd, Y, G, U

@@ -52,7 +52,8 @@ typedef enum {
     XMOE_WS_BUILD_ERI = 0,      /* rows = T           */
     XMOE_WS_FFN_FWD = 1,        /* rows = B (FFN rows) */
     XMOE_WS_FFN_BWD = 2,        /* rows = B            */
-    XMOE_WS_GATE_BWD = 3        /* rows = T            */
+    XMOE_WS_GATE_BWD = 3,       /* rows = T            */
+    XMOE_WS_BUILD_ERI_CAPPED = 4 /* rows = T           */
 } xmoe_ws_op;
 
 /* Largest expert count the routing / ERI kernels accept. */
@@ -100,6 +101,23 @@ int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int T, int E, i
                    int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
                    int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* PFT construction with token dropping (Listing 1 PFT_construction(), step 2; Appendix B.2): as xmoe_build_eri,
+ * but every expert keeps at most max_token_count of the rows routed to it - those with the largest combine
+ * weights; among equal weights the lower flat entry n = t*k + j is kept first; retained rows keep the order they
+ * have in the dropless table.  The decision compares the float32 bit patterns of topk_w; no arithmetic is involved.
+ * The number of retained rows B_kept <= T*k exists on the device only:
+ *   tokens_per_expert[e] = min(rows routed to e, max_token_count);  expert_offsets[E] = B_kept;
+ *   rows [B_kept, T*k): token_ids = -1, expert_ids = E, combine_weights = 0;  row_of_slot[n] = -1 for a dropped entry.
+ * The other entry points run unchanged on such a table with T*k as the row count: xmoe_dispatch skips rows whose
+ * token id is -1, xmoe_combine / xmoe_dispatch_bwd skip entries whose row is -1, xmoe_combine_bwd writes dw = 0 for
+ * them, and the expert MLP takes its rows from expert_offsets.  max_token_count >= T reproduces xmoe_build_eri.
+ * ws: XMOE_WS_BUILD_ERI_CAPPED bytes.
+ */
+int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, int E, int k, int max_token_count,
+                          int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                          int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* Dispatch (Section 4.1.2 / Appendix B.4 gather kernel): xd[i,:] = x[token_ids[i],:], a bit copy.
  * x [T,d] dt; token_ids [B] int32 with values in [0,T); xd [B,d] dt (out).

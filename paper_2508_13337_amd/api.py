@@ -14,14 +14,14 @@ import torch
 from ._lib import lib
 
 XMOE_F32, XMOE_BF16 = 0, 1
-WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD = 0, 1, 2, 3
+WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD, WS_BUILD_ERI_CAPPED = 0, 1, 2, 3, 4
 
 __all__ = [
     "XMoEError", "xmoe_version", "xmoe_workspace_bytes", "xmoe_gate_logits", "xmoe_route", "xmoe_build_eri",
     "xmoe_dispatch", "xmoe_expert_ffn_fwd", "xmoe_expert_ffn_bwd", "xmoe_combine", "xmoe_combine_bwd",
     "xmoe_dispatch_bwd", "xmoe_route_bwd", "xmoe_gate_logits_bwd", "xmoe_prof_enable", "xmoe_prof_reset",
     "xmoe_prof_read", "xmoe_prof_copy", "dtype_code", "alloc_workspace",
-    "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD",
+    "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
 ]
 
 
@@ -101,6 +101,20 @@ def xmoe_build_eri(topk_idx, topk_w, E: int, tokens_per_expert, expert_offsets, 
         _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
         _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_build_eri")
+
+
+def xmoe_build_eri_capped(topk_idx, topk_w, E: int, max_token_count: int, tokens_per_expert, expert_offsets, token_ids,
+                          expert_ids, combine_weights, row_of_slot, ws) -> None:
+    T, k = topk_idx.shape
+    B = T * k
+    assert tokens_per_expert.numel() == E and expert_offsets.numel() == E + 1
+    assert token_ids.numel() == B and expert_ids.numel() == B and combine_weights.numel() == B
+    assert row_of_slot.numel() == B
+    _check(lib().xmoe_build_eri_capped(
+        _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"), T, E, k, int(max_token_count),
+        _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
+        _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_build_eri_capped")
 
 
 def xmoe_dispatch(x, token_ids, xd) -> None:

@@ -25,6 +25,7 @@ const char* const kKernelNames[K_COUNT] = {
     "eri_hist_kernel",
     "eri_scan_kernel",
     "eri_scatter_kernel",
+    "eri_cap_kernel",
     "dispatch_kernel",
     "combine_kernel",
     "combine_bwd_kernel",
@@ -115,6 +116,7 @@ size_t xmoe_workspace_bytes(int op, int rows, int d, int E, int k, int f, int dt
         case XMOE_WS_FFN_FWD: return ffn_fwd_ws_bytes(rows, E, d, f, dt);
         case XMOE_WS_FFN_BWD: return ffn_bwd_ws_bytes(rows, E, d, f, dt);
         case XMOE_WS_GATE_BWD: return gate_bwd_ws_bytes(rows, d, E);
+        case XMOE_WS_BUILD_ERI_CAPPED: return eri_capped_ws_bytes(rows, E, k);
         default: return 0;
     }
 }

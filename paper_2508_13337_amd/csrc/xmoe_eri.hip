@@ -57,6 +57,9 @@ __global__ __launch_bounds__(512) void eri_scan_kernel(int32_t* __restrict__ chu
     }
 }
 
+// FLAT: the intermediate table of the token-dropping construction: token_ids receives the flat entry n itself,
+// expert_ids and row_of_slot are not written.
+template <bool FLAT>
 __global__ __launch_bounds__(256) void eri_scatter_kernel(const int32_t* __restrict__ topk_idx,
                                                           const float* __restrict__ topk_w, int B, int E, int k,
                                                           int ebits, const int32_t* __restrict__ chunk_prefix,
@@ -108,10 +111,205 @@ __global__ __launch_bounds__(256) void eri_scatter_kernel(const int32_t* __restr
         const int e = my_e[r];
         if (n < B && (unsigned)e < (unsigned)E) {
             const int row = sub_count[sub * E + e] + my_rank[r];
-            token_ids[row] = n / k;
-            expert_ids[row] = e;
             combine_weights[row] = topk_w[n];
-            row_of_slot[n] = row;
+            if (FLAT) {
+                token_ids[row] = n;
+            } else {
+                token_ids[row] = n / k;
+                expert_ids[row] = e;
+                row_of_slot[n] = row;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Token dropping (paper: Listing 1 PFT_construction() step 2; Appendix B.2): every expert keeps at most C rows, the
+// ones with the largest combine weights, equal weights keeping the lower flat entry first.  Input is the dropless
+// table (rows sorted by expert, ascending flat entry inside an expert): so "lower flat entry" is "earlier row", and
+// the survivors, taken in row order, are already in their final order.
+// Block e < E handles expert e: a three-pass radix select over the order-preserving bit pattern of the weights
+// finds the C-th largest weight, then the segment is compacted in row order.  Blocks >= E write the sentinels of
+// the rows behind the last retained one.  No floating-point arithmetic takes part in the decision.
+// ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t weight_key(float w) {
+    const uint32_t u = __float_as_uint(w);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in w
+}
+
+// exclusive prefix of `flag` over the block's 256 threads in thread order; total in *total
+__device__ __forceinline__ int block_excl_count(bool flag, int* wave_tot, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long bal = __ballot(flag);
+    const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+    __syncthreads();   // wave_tot may still be read from the previous call
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    return before + in_wave;
+}
+
+// exclusive prefix of `v` over the block's 256 threads in thread order; total in *total
+__device__ __forceinline__ int block_excl_sum(int v, int* wave_tot, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += up;
+    }
+    __syncthreads();   // wave_tot may still be read from the previous call
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    return before + inc - v;
+}
+
+__global__ __launch_bounds__(256) void eri_cap_kernel(const int32_t* __restrict__ off0,      // dropless offsets [E+1]
+                                                      const int32_t* __restrict__ flat0,     // flat entry of row [B]
+                                                      const float* __restrict__ w0,          // weight of row [B]
+                                                      int B, int E, int k, int C,
+                                                      int32_t* __restrict__ tokens_per_expert,
+                                                      int32_t* __restrict__ expert_offsets,
+                                                      int32_t* __restrict__ token_ids,
+                                                      int32_t* __restrict__ expert_ids,
+                                                      float* __restrict__ combine_weights,
+                                                      int32_t* __restrict__ row_of_slot) {
+    __shared__ int hist[2048];
+    __shared__ int wave_tot[4];
+    __shared__ uint32_t s_prefix, s_mask;
+    __shared__ int s_remaining, s_new_lo, s_kept_total;
+    const int tid = threadIdx.x;
+    // retained rows before this block's expert, and in total: every block recomputes the short prefix it needs
+    {
+        int before_me = 0, all = 0;
+        for (int i = tid; i < E; i += 256) {
+            const int n = off0[i + 1] - off0[i];
+            const int c = n < C ? n : C;
+            all += c;
+            if (i < (int)blockIdx.x) before_me += c;
+        }
+        int tot_before, tot_all;
+        block_excl_sum(before_me, wave_tot, &tot_before);
+        block_excl_sum(all, wave_tot, &tot_all);
+        if (tid == 0) {
+            s_new_lo = tot_before;
+            s_kept_total = tot_all;
+        }
+    }
+    __syncthreads();
+    const int kept_total = s_kept_total;
+    if ((int)blockIdx.x >= E) {
+        // rows behind the last retained one
+        const int base = ((int)blockIdx.x - E) * kEriChunk;
+        for (int r = base + tid; r < base + kEriChunk && r < B; r += 256) {
+            if (r >= kept_total) {
+                token_ids[r] = -1;
+                expert_ids[r] = E;
+                combine_weights[r] = 0.0f;
+            }
+        }
+        return;
+    }
+    const int e = blockIdx.x;
+    const int lo = off0[e], n = off0[e + 1] - lo;
+    const int new_lo = s_new_lo;
+    const int keep_n = n < C ? n : C;
+    if (tid == 0) {
+        tokens_per_expert[e] = keep_n;
+        expert_offsets[e] = new_lo;
+        if (e == E - 1) expert_offsets[E] = kept_total;
+    }
+    // the C-th largest key of the segment (only needed when something is dropped)
+    uint32_t vstar = 0;
+    int need_eq = 0;   // how many rows with key == vstar are kept
+    if (n > C && C > 0) {
+        if (tid == 0) {
+            s_prefix = 0;
+            s_mask = 0;
+            s_remaining = C;
+        }
+        const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
+        for (int p = 0; p < 3; ++p) {
+            const int shift = shifts[p], nb = 1 << widths[p];
+            for (int i = tid; i < nb; i += 256) hist[i] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix, mask = s_mask;
+            for (int i = tid; i < n; i += 256) {
+                const uint32_t key = weight_key(w0[lo + i]);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1);
+            }
+            __syncthreads();
+            // which bin holds the `remaining`-th largest key: thread t owns the bins nb-1 - t*bpt .. (downwards);
+            // an exclusive prefix of the threads' sums, then the one thread whose range the target falls into
+            // walks its few bins
+            {
+                const int bpt = nb / 256;
+                const int hi = nb - 1 - tid * bpt;
+                int mine = 0;
+                for (int j = 0; j < bpt; ++j) mine += hist[hi - j];
+                int tot_unused;
+                const int before = block_excl_sum(mine, wave_tot, &tot_unused);
+                const int remaining = s_remaining;
+                __syncthreads();   // everyone has read s_remaining before the owner overwrites it
+                if (before < remaining && remaining <= before + mine) {
+                    int rem = remaining - before, b = hi;
+                    while (hist[b] < rem) {
+                        rem -= hist[b];
+                        --b;
+                    }
+                    s_remaining = rem;
+                    s_prefix = prefix | ((uint32_t)b << shift);
+                    s_mask = mask | ((uint32_t)(nb - 1) << shift);
+                }
+            }
+            __syncthreads();
+        }
+        vstar = s_prefix;
+        need_eq = s_remaining;
+    }
+    // compaction in row order
+    int eq_seen = 0, kept_seen = 0;
+    for (int base = 0; base < n; base += 256) {
+        const int i = base + tid;
+        const bool in = i < n;
+        uint32_t key = 0;
+        int flat = 0;
+        float w = 0.f;
+        if (in) {
+            w = w0[lo + i];
+            flat = flat0[lo + i];
+            key = weight_key(w);
+        }
+        bool keep;
+        if (n <= C) {
+            keep = in;
+        } else if (C <= 0) {
+            keep = false;
+        } else {
+            const bool eq = in && key == vstar;
+            int eq_total;
+            const int eq_rank = eq_seen + block_excl_count(eq, wave_tot, &eq_total);
+            eq_seen += eq_total;
+            keep = in && (key > vstar || (eq && eq_rank < need_eq));
+        }
+        int kept_total_chunk;
+        const int pos = kept_seen + block_excl_count(keep, wave_tot, &kept_total_chunk);
+        kept_seen += kept_total_chunk;
+        if (in) {
+            if (keep) {
+                const int row = new_lo + pos;
+                token_ids[row] = flat / k;
+                expert_ids[row] = e;
+                combine_weights[row] = w;
+                row_of_slot[flat] = row;
+            } else {
+                row_of_slot[flat] = -1;
+            }
         }
     }
 }
@@ -145,8 +343,53 @@ extern "C" int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int 
                                    expert_offsets));
     if (nchunks > 0)
         XMOE_LAUNCH(K_ERI_SCATTER, s,
-                    hipLaunchKernelGGL(eri_scatter_kernel, dim3(nchunks), dim3(256),
+                    hipLaunchKernelGGL(eri_scatter_kernel<false>, dim3(nchunks), dim3(256),
                                        (size_t)kSubPerChunk * E * sizeof(int), s, topk_idx, topk_w, B, E, k, ebits,
                                        counts, expert_offsets, token_ids, expert_ids, combine_weights, row_of_slot));
+    return XMOE_OK;
+}
+
+extern "C" int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                                     int max_token_count, int32_t* tokens_per_expert, int32_t* expert_offsets,
+                                     int32_t* token_ids, int32_t* expert_ids, float* combine_weights,
+                                     int32_t* row_of_slot, void* ws, size_t ws_bytes, void* stream) {
+    if (T < 0 || E < 1 || k < 1 || k > E || max_token_count < 0) return XMOE_ERR_INVALID_ARG;
+    if (E > XMOE_MAX_EXPERTS) return XMOE_ERR_UNSUPPORTED;
+    if ((long long)T * k >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (!tokens_per_expert || !expert_offsets) return XMOE_ERR_INVALID_ARG;
+    if (T > 0 && (!topk_idx || !topk_w || !token_ids || !expert_ids || !combine_weights || !row_of_slot))
+        return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < eri_capped_ws_bytes(T, E, k))
+        return XMOE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int B = T * k;
+    const int nchunks = eri_num_chunks(B);
+    // workspace: chunk histograms | dropless offsets [E+1] | dropless counts [E] | flat entry of row [B] | weight of row [B]
+    char* p = (char*)ws;
+    int32_t* counts = (int32_t*)p;
+    p += eri_ws_bytes(T, E, k);
+    int32_t* off0 = (int32_t*)p;
+    p += align_up((size_t)(E + 1) * sizeof(int32_t), 256);
+    int32_t* tpe0 = (int32_t*)p;
+    p += align_up((size_t)E * sizeof(int32_t), 256);
+    int32_t* flat0 = (int32_t*)p;
+    p += align_up((size_t)(B > 0 ? B : 1) * sizeof(int32_t), 256);
+    float* w0 = (float*)p;
+    int ebits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    if (nchunks > 0)
+        XMOE_LAUNCH(K_ERI_HIST, s,
+                    hipLaunchKernelGGL(eri_hist_kernel, dim3(nchunks), dim3(256), 0, s, topk_idx, B, E, counts));
+    XMOE_LAUNCH(K_ERI_SCAN, s,
+                hipLaunchKernelGGL(eri_scan_kernel, dim3(1), dim3(512), 0, s, counts, nchunks, E, tpe0, off0));
+    if (nchunks > 0)
+        XMOE_LAUNCH(K_ERI_SCATTER, s,
+                    hipLaunchKernelGGL(eri_scatter_kernel<true>, dim3(nchunks), dim3(256),
+                                       (size_t)kSubPerChunk * E * sizeof(int), s, topk_idx, topk_w, B, E, k, ebits,
+                                       counts, off0, flat0, nullptr, w0, nullptr));
+    XMOE_LAUNCH(K_ERI_CAP, s,
+                hipLaunchKernelGGL(eri_cap_kernel, dim3(E + nchunks), dim3(256), 0, s, off0, flat0, w0, B, E, k,
+                                   max_token_count, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                                   combine_weights, row_of_slot));
     return XMOE_OK;
 }

@@ -17,6 +17,7 @@ enum KernelId : int {
     K_ERI_HIST,
     K_ERI_SCAN,
     K_ERI_SCATTER,
+    K_ERI_CAP,
     K_DISPATCH,
     K_COMBINE,
     K_COMBINE_BWD,

@@ -135,7 +135,10 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
     constexpr int N = Vec16<T>::N;
     for (int j = 0; j < k; ++j) {
         const int r = row_of_slot[(size_t)t * k + j];
-        if ((unsigned)r >= (unsigned)B) continue;
+        if ((unsigned)r >= (unsigned)B) {   // a dropped entry: the output does not depend on its weight
+            if (lane == 0) dw[(size_t)t * k + j] = 0.f;
+            continue;
+        }
         const float w = topk_w[(size_t)t * k + j];
         float dot = 0.f;
         if (VEC) {

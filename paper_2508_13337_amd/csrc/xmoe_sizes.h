@@ -16,6 +16,14 @@ static inline size_t eri_ws_bytes(int T, int E, int k) {
     return align_up((size_t)(eri_num_chunks(B) > 0 ? eri_num_chunks(B) : 1) * (size_t)E * sizeof(int32_t), 256);
 }
 
+// token-dropping construction: the above, then the dropless table it selects from (offsets, counts, flat entry and
+// weight of every row)
+static inline size_t eri_capped_ws_bytes(int T, int E, int k) {
+    long long B = (long long)T * k;
+    return eri_ws_bytes(T, E, k) + align_up((size_t)(E + 1) * sizeof(int32_t), 256) +
+           align_up((size_t)E * sizeof(int32_t), 256) + 2 * align_up((size_t)(B > 0 ? B : 1) * sizeof(int32_t), 256);
+}
+
 // ----- ragged grouped GEMM: the tile map lists, for every row tile, its expert and first row -----
 // Sized for the smallest row tile any kernel uses (kMinRowTile rows): at most ceil(B/tile) + E tiles.
 constexpr int kMinRowTile = 64;

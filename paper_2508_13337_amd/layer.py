@@ -25,8 +25,13 @@ class XMoELayer:
     experts E .. E+E_s-1 whose segments are rows [B + s*T, B + (s+1)*T) = a copy of x, so the tail of
     expert_offsets and of token_ids is constant and written once here."""
 
-    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, E_s: int = 0, device="cuda"):
+    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, E_s: int = 0, device="cuda",
+                 max_token_count: Optional[int] = None):
         self.T, self.d, self.E, self.k, self.f, self.E_s = T, d, E, k, f, E_s
+        # None: dropless.  Else the per-expert capacity of the token-dropping PFT construction; the number of
+        # retained rows is then known on the device only, so the shared experts (whose segments would have to start
+        # right behind the retained rows) run as calls of their own on x.
+        self.max_token_count = max_token_count
         self.dtype, self.device = dtype, device
         B = T * k
         R = B + E_s * T          # rows of the expert MLP
@@ -66,6 +71,9 @@ class XMoELayer:
                  api.xmoe_workspace_bytes(api.WS_FFN_FWD, R, d, Ea, k, f, dt),
                  api.xmoe_workspace_bytes(api.WS_FFN_BWD, R, d, Ea, k, f, dt),
                  api.xmoe_workspace_bytes(api.WS_GATE_BWD, T, d, E, k, f, dt))
+        if max_token_count is not None:
+            ws = max(ws, api.xmoe_workspace_bytes(api.WS_BUILD_ERI_CAPPED, T, d, E, k, f, dt))
+            self.one_segment = torch.tensor([0, T], **i32)
         self.ws = api.alloc_workspace(ws, device)
 
     def _shared(self, rows: torch.Tensor) -> Optional[torch.Tensor]:
@@ -76,24 +84,47 @@ class XMoELayer:
     def forward(self, x: torch.Tensor, w: dict) -> torch.Tensor:
         api.xmoe_gate_logits(x, w["w_router"], w.get("bias"), self.logits)
         api.xmoe_route(self.logits, self.k, self.topk_idx, self.topk_w)
-        api.xmoe_build_eri(self.topk_idx, self.topk_w, self.E, self.tokens_per_expert, self.expert_offsets,
-                           self.token_ids, self.expert_ids, self.combine_weights, self.row_of_slot, self.ws)
-        api.xmoe_dispatch(x, self.token_ids_all, self.xd)
-        api.xmoe_expert_ffn_fwd(self.xd, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
-                                self.ws)
-        api.xmoe_combine(self.y[:self.B], self.row_of_slot, self.topk_w, self._shared(self.y), None, self.k,
-                         self.out)
+        B, E, T = self.B, self.E, self.T
+        if self.max_token_count is None:
+            api.xmoe_build_eri(self.topk_idx, self.topk_w, E, self.tokens_per_expert, self.expert_offsets,
+                               self.token_ids, self.expert_ids, self.combine_weights, self.row_of_slot, self.ws)
+            api.xmoe_dispatch(x, self.token_ids_all, self.xd)
+            api.xmoe_expert_ffn_fwd(self.xd, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
+                                    self.ws)
+        else:
+            api.xmoe_build_eri_capped(self.topk_idx, self.topk_w, E, self.max_token_count, self.tokens_per_expert,
+                                      self.expert_offsets, self.token_ids, self.expert_ids, self.combine_weights,
+                                      self.row_of_slot, self.ws)
+            api.xmoe_dispatch(x, self.token_ids, self.xd[:B])
+            api.xmoe_expert_ffn_fwd(self.xd[:B], self.expert_offsets, w["wg"][:E], w["wu"][:E], w["wd"][:E],
+                                    self.g[:B], self.u[:B], self.y[:B], self.ws)
+            for s in range(self.E_s):
+                seg = slice(B + s * T, B + (s + 1) * T)
+                api.xmoe_expert_ffn_fwd(x, self.one_segment, w["wg"][E + s:E + s + 1], w["wu"][E + s:E + s + 1],
+                                        w["wd"][E + s:E + s + 1], self.g[seg], self.u[seg], self.y[seg], self.ws)
+        api.xmoe_combine(self.y[:B], self.row_of_slot, self.topk_w, self._shared(self.y), None, self.k, self.out)
         return self.out
 
     def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
         """grads: preallocated dw_router, dwg, dwu, dwd in the layouts of the weights."""
-        api.xmoe_combine_bwd(dout, self.y[:self.B], self.row_of_slot, self.topk_w, self.dy[:self.B], self.dw)
-        if self.E_s > 0:   # dY of a shared expert's rows is dout itself
-            api.xmoe_dispatch(dout, self.token_ids_all[self.B:], self.dy[self.B:])
-        api.xmoe_expert_ffn_bwd(self.xd, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
-                                self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws)
+        B, E, T = self.B, self.E, self.T
+        api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, self.dy[:B], self.dw)
+        if self.max_token_count is None:
+            if self.E_s > 0:   # dY of a shared expert's rows is dout itself
+                api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
+            api.xmoe_expert_ffn_bwd(self.xd, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws)
+        else:
+            api.xmoe_expert_ffn_bwd(self.xd[:B], self.g[:B], self.u[:B], self.dy[:B], self.expert_offsets,
+                                    w["wg"][:E], w["wu"][:E], w["wd"][:E], self.dxd[:B], grads["dwg"][:E],
+                                    grads["dwu"][:E], grads["dwd"][:E], self.ws)
+            for s in range(self.E_s):
+                seg = slice(B + s * T, B + (s + 1) * T)
+                one = slice(E + s, E + s + 1)
+                api.xmoe_expert_ffn_bwd(x, self.g[seg], self.u[seg], dout, self.one_segment, w["wg"][one],
+                                        w["wu"][one], w["wd"][one], self.dxd[seg], grads["dwg"][one],
+                                        grads["dwu"][one], grads["dwd"][one], self.ws)
         api.xmoe_route_bwd(self.logits, self.topk_idx, self.dw, self.dlogits)
         api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
-        api.xmoe_dispatch_bwd(self.dxd[:self.B], self.row_of_slot, self._shared(self.dxd), self.dx_gate, self.k,
-                              self.dx)
+        api.xmoe_dispatch_bwd(self.dxd[:B], self.row_of_slot, self._shared(self.dxd), self.dx_gate, self.k, self.dx)
         return self.dx

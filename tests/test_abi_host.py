@@ -79,6 +79,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.xmoe_build_eri(p, p, 16, 8, 2, p, p, p, p, p, p, null, 0, null) == WORKSPACE
     assert lib.xmoe_build_eri(p, p, 4096, 8, 2, p, p, p, p, p, p, p, 16, null) == WORKSPACE
     assert lib.xmoe_build_eri(p, p, 16, 8, 2, p, p, p, p, p, p, ctypes.c_void_p(4100), 1 << 20, null) == WORKSPACE
+    assert lib.xmoe_build_eri_capped(p, p, 16, 8, 2, -1, p, p, p, p, p, p, p, 1 << 20, null) == INVALID   # capacity < 0
+    assert lib.xmoe_build_eri_capped(p, p, 16, 8, 2, 4, p, p, p, p, p, p, p, 16, null) == WORKSPACE
+    assert lib.xmoe_build_eri_capped(p, p, 16, 8, 2, 4, p, p, null, p, p, p, p, 1 << 20, null) == INVALID
     assert lib.xmoe_dispatch(p, p, 16, 32, 64, 9, p, null) == UNSUPPORTED
     assert lib.xmoe_dispatch(null, p, 16, 32, 64, 0, p, null) == INVALID
     assert lib.xmoe_expert_ffn_fwd(p, p, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE

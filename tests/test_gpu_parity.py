@@ -77,7 +77,7 @@ def test_route_bit_exact(T, E, k, seed, std):
 
 
 # ------------------------------------------------------------------------------------------------ ERI arrays
-def run_build_eri(topk_idx, topk_w, E):
+def run_build_eri(topk_idx, topk_w, E, max_token_count=None):
     T, k = topk_idx.shape
     B = T * k
     m = xm()
@@ -89,9 +89,15 @@ def run_build_eri(topk_idx, topk_w, E):
         "combine_weights": torch.full((B,), -7.0, dtype=torch.float32, device="cuda"),
         "row_of_slot": torch.full((B,), -7, dtype=torch.int32, device="cuda"),
     }
-    ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_BUILD_ERI, T, 0, E, k, 0, 0))
-    m.xmoe_build_eri(i32(topk_idx), f32(topk_w), E, out["tokens_per_expert"], out["expert_offsets"],
-                     out["token_ids"], out["expert_ids"], out["combine_weights"], out["row_of_slot"], ws)
+    if max_token_count is None:
+        ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_BUILD_ERI, T, 0, E, k, 0, 0))
+        m.xmoe_build_eri(i32(topk_idx), f32(topk_w), E, out["tokens_per_expert"], out["expert_offsets"],
+                         out["token_ids"], out["expert_ids"], out["combine_weights"], out["row_of_slot"], ws)
+    else:
+        ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_BUILD_ERI_CAPPED, T, 0, E, k, 0, 0))
+        m.xmoe_build_eri_capped(i32(topk_idx), f32(topk_w), E, max_token_count, out["tokens_per_expert"],
+                                out["expert_offsets"], out["token_ids"], out["expert_ids"], out["combine_weights"],
+                                out["row_of_slot"], ws)
     torch.cuda.synchronize()
     return out
 
@@ -120,6 +126,52 @@ def test_build_eri_bit_exact(T, E, k, seed, skew):
     ref = oracle.build_eri(idx, w32, E)
     out = run_build_eri(idx, w32, E)
     check_eri(out, ref, w32)
+
+
+def check_capped_eri(out, ref, E):
+    """Retained rows bit for bit; behind them the sentinels the header promises."""
+    nk = int(ref["expert_offsets"][-1])
+    for key in ("tokens_per_expert", "expert_offsets", "row_of_slot"):
+        assert np.array_equal(out[key].cpu().numpy(), ref[key]), key
+    for key in ("token_ids", "expert_ids"):
+        assert np.array_equal(out[key].cpu().numpy()[:nk], ref[key]), key
+    assert bits_equal(out["combine_weights"][:nk], ref["combine_weights"].astype(np.float32))
+    assert (out["token_ids"].cpu().numpy()[nk:] == -1).all()
+    assert (out["expert_ids"].cpu().numpy()[nk:] == E).all()
+    assert not out["combine_weights"].cpu().numpy()[nk:].any()
+
+
+# (T, E, k, seed, skew, capacity): capacity above the longest segment (nothing dropped), at the mean, tiny, zero;
+# segments longer than one 256-row pass of the selection; many experts
+CAPPED_CASES = [(256, 8, 2, 0, 0.0, 1000), (1000, 64, 6, 1, 0.0, 94), (4099, 64, 6, 2, 2.0, 300), (77, 7, 3, 3, 0.0, 5),
+                (700, 512, 8, 4, 0.0, 9), (10, 1, 1, 5, 0.0, 3), (2048, 256, 8, 6, 3.0, 1), (64, 4, 4, 7, 0.0, 0),
+                (8192, 64, 6, 8, 1.5, 768), (3000, 16, 2, 9, 1.0, 257)]
+
+
+@pytest.mark.parametrize("T,E,k,seed,skew,cap", CAPPED_CASES)
+def test_build_eri_capped_bit_exact(T, E, k, seed, skew, cap):
+    logits = xi.make_logits(T, E, seed=seed)
+    if skew:
+        logits = logits - np.float32(skew) * np.log(np.arange(1, E + 1, dtype=np.float32))[None, :]
+    idx, w, _ = oracle.route(logits, k)
+    w32 = w.astype(np.float32)
+    ref = oracle.build_eri_capped(idx, w32, E, cap)
+    out = run_build_eri(idx, w32, E, max_token_count=cap)
+    check_capped_eri(out, ref, E)
+
+
+def test_build_eri_capped_equal_weights_and_no_drop():
+    """Ties at the capacity boundary go to the lower flat entry; a capacity nobody reaches reproduces the dropless table."""
+    T, E, k = 900, 6, 2
+    idx = np.stack([np.arange(T) % E, (np.arange(T) + 1 + (np.arange(T) // E) % (E - 1)) % E], axis=1).astype(np.int32)
+    idx[:, 1] = np.where(idx[:, 1] == idx[:, 0], (idx[:, 0] + 1) % E, idx[:, 1])
+    w = np.full((T, k), 0.125, dtype=np.float32)
+    w[::7, 0] = 0.5                                     # some heavier entries, many exact ties below them
+    for cap in (40, 150, 299):
+        check_capped_eri(run_build_eri(idx, w, E, max_token_count=cap), oracle.build_eri_capped(idx, w, E, cap), E)
+    full = oracle.build_eri(idx, w, E)
+    out = run_build_eri(idx, w, E, max_token_count=T)
+    check_eri(out, full, w)
 
 
 # ------------------------------------------------------------------------------------------------ row movers
@@ -235,11 +287,11 @@ def test_expert_ffn_fwd_bwd(name):
 
 
 # ------------------------------------------------------------------------------------------------ whole layer
-def run_layer(cfg, inp):
+def run_layer(cfg, inp, max_token_count=None):
     m = xm()
     dt = cfg.dtype
     tdt = torch_dtype(dt)
-    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s, max_token_count=max_token_count)
     w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"])}
     grads = {"dw_router": torch.empty_like(w["w_router"])}
     for k_ in ("wg", "wu", "wd"):
@@ -275,6 +327,38 @@ def check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads):
             errs["dshared_" + k_] = assert_close_chain(to_host(grads["d" + k_][cfg.E:]), bwd["dshared_" + k_], dt,
                                                        "dshared_" + k_, floor="row")
     return errs
+
+
+@pytest.mark.parametrize("name,cap", [("tiny_f32", 40), ("mini_f32", 60), ("mini_bf16", 200), ("mini_bf16_skew", 150),
+                                      ("mid_bf16", 230), ("odd_bf16", 30)])
+def test_layer_with_token_dropping(name, cap):
+    """Per-expert capacity: the ERI-arrays of the retained rows bit for bit, outputs and gradients to the chain
+    tolerance, dropped entries contribute nothing and get no weight gradient."""
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe_layer_fwd(inp, cfg.k, max_token_count=cap)
+    bwd = oracle.moe_layer_bwd(inp, fwd, cfg.k)
+    eri = fwd["eri"]
+    nk = int(eri["expert_offsets"][-1])
+    assert nk < cfg.B and eri["tokens_per_expert"].max() == cap        # the case does drop rows
+    layer, out, dx, grads = run_layer(cfg, inp, max_token_count=cap)
+    dt = cfg.dtype
+    assert bits_equal(layer.logits, fwd["logits"])
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), fwd["topk_idx"])
+    for key in ("tokens_per_expert", "expert_offsets", "row_of_slot"):
+        assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
+    assert np.array_equal(layer.token_ids.cpu().numpy()[:nk], eri["token_ids"])
+    assert (layer.token_ids.cpu().numpy()[nk:] == -1).all()
+    assert_close_chain(to_host(out), fwd["out"], dt, "out")
+    assert_close_chain(to_host(layer.y[:nk]), fwd["Y"], dt, "Y")
+    assert_close_chain(to_host(dx), bwd["dx"], dt, "dx")
+    assert_close_chain(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router", floor="tensor", norm="tensor")
+    for k_ in ("dwg", "dwu", "dwd"):
+        assert_close_chain(to_host(grads[k_][:cfg.E]), bwd[k_], dt, k_, floor="row")
+        if cfg.E_s > 0:
+            assert_close_chain(to_host(grads[k_][cfg.E:]), bwd["dshared_" + k_[1:]], dt, "dshared_" + k_[1:], floor="row")
+    dropped = (eri["row_of_slot"] < 0).reshape(cfg.T, cfg.k)
+    assert not layer.dw.cpu().numpy()[dropped].any()
 
 
 @pytest.mark.parametrize("name", SMALL)
