@@ -58,8 +58,8 @@ def kernel_work(cfg):
     flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf,
              "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf}
     bytes_ = {
-        # forward: unique rows read once + rows written; backward (E_s > 0): dout copied to the shared segments
-        "dispatch_kernel": (T + B + Ts) * d * s + ((T + Ts) * d * s if Ts else 0),
+        # only use left in the layer: backward (E_s > 0), dout copied to the shared experts' dY rows
+        "dispatch_kernel": (T + Ts) * d * s if Ts else 0,
         "combine_kernel": (B + Ts + T) * d * s                                # forward combine
                           + (B + Ts + 2 * T) * d * s,                         # + dispatch backward (same kernel)
         "combine_bwd_kernel": (T + 2 * B) * d * s,
@@ -232,9 +232,10 @@ def main():
                    "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "max_token_count": args.max_token_count, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
         "fwd_only_ms": round(fwd_ms, 4),
         "fwd_only_tokens_per_s": round(cfg.T / (fwd_ms * 1e-3), 1),
-        # what stays allocated between forward and backward for the routed rows: Xd, Y, G, U
+        # what stays allocated between forward and backward for the routed rows: Y, G, U (no dispatched copy Xd:
+        # the gather is fused into the expert MLP's operand loads)
         "activation_bytes_held": sum(t_[:layer.B].numel() * t_.element_size()
-                                     for t_ in (layer.xd, layer.y, layer.g, layer.u)),
+                                     for t_ in (layer.y, layer.g, layer.u)),
         "layer_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "grouped_gemm_pct_mfma_peak": round(100 * roofline["all_gemm_frac"], 3),
         "roofline": roofline,

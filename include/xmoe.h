@@ -129,25 +129,32 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
  *   G = Xd_e Wg_e,  U = Xd_e Wu_e,  A = silu(G) * U,  Y_e = A Wd_e          (SwiGLU, no biases)
  * xd [B,d]; wg, wu [E,d,f]; wd [E,f,d] ("in x out"); expert_offsets [E+1] int32 on the device with
  * offsets[0] = 0 and offsets[E] = B.  Outputs: y [B,d]; g_save, u_save [B,f] (kept for backward).
- * An expert with no rows reads no weights.  Shared experts are served by the same call as E_s further experts
- * whose segments are all T tokens: x is appended E_s times after the B routed rows (xmoe_dispatch with token ids
- * 0..T-1), expert_offsets continues with B+T, B+2T, ..., and the weights of the shared experts follow the routed
- * ones.  (A single call on x itself with E = 1 and offsets {0,T} works too.)
+ * An expert with no rows reads no weights.
+ * row_index: NULL, or the gather of dispatch fused into the operand load (Section 4.1.2 names the dispatched copy
+ * as one of the two activation tensors worth removing): xd is then the token matrix x [T,d] itself, row_index [B]
+ * int32 holds token ids (token_ids of the ERI-arrays), and row i of the expert input is x[row_index[i]]; no [B,d]
+ * copy of the tokens exists.  Entries of rows outside every segment are never read.  Results are bit-identical to
+ * the call on the dispatched copy.
+ * Shared experts are served by the same call as E_s further experts whose segments are all T tokens: expert_offsets
+ * continues with B+T, B+2T, ..., the weights of the shared experts follow the routed ones, and the rows are x again
+ * (row_index continues with 0..T-1 per shared expert; or xmoe_dispatch makes the copies).  (A single call on x
+ * itself with E = 1 and offsets {0,T} works too.)
  * ws: XMOE_WS_FFN_FWD bytes.
  */
-int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, int E, int d, int f,
-                        const void* wg, const void* wu, const void* wd,
+int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t* expert_offsets, int B, int E,
+                        int d, int f, const void* wg, const void* wu, const void* wd,
                         void* g_save, void* u_save, void* y, int dt,
                         void* ws, size_t ws_bytes, void* stream);
 
 /* Backward of the expert MLP (derived; A is recomputed from the saved G and U):
  *   dA = dY Wd^T;  dWd_e = A_e^T dY_e;  dG = dA * U * silu'(G);  dU = dA * silu(G);
  *   dXd = dG Wg^T + dU Wu^T;  dWg_e = Xd_e^T dG_e;  dWu_e = Xd_e^T dU_e.
+ * xd, row_index: as in the forward call.
  * Outputs: dxd [B,d]; dwg, dwu [E,d,f]; dwd [E,f,d] - overwritten, all zero for an expert with no rows.
  * ws: XMOE_WS_FFN_BWD bytes.
  */
-int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, const void* dy,
-                        const int32_t* expert_offsets, int B, int E, int d, int f,
+int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
+                        const void* dy, const int32_t* expert_offsets, int B, int E, int d, int f,
                         const void* wg, const void* wu, const void* wd,
                         void* dxd, void* dwg, void* dwu, void* dwd, int dt,
                         void* ws, size_t ws_bytes, void* stream);

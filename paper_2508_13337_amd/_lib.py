@@ -22,9 +22,9 @@ SIGNATURES = {
     "xmoe_build_eri": (_c_int, [_c_void_p] * 2 + [_c_int] * 3 + [_c_void_p] * 7 + [_c_size_t, _c_void_p]),
     "xmoe_build_eri_capped": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_size_t, _c_void_p]),
     "xmoe_dispatch": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 2),
-    "xmoe_expert_ffn_fwd": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 6 + [_c_int, _c_void_p, _c_size_t,
+    "xmoe_expert_ffn_fwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 6 + [_c_int, _c_void_p, _c_size_t,
                                                                                         _c_void_p]),
-    "xmoe_expert_ffn_bwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_int, _c_void_p, _c_size_t,
+    "xmoe_expert_ffn_bwd": (_c_int, [_c_void_p] * 6 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_int, _c_void_p, _c_size_t,
                                                                                         _c_void_p]),
     "xmoe_combine": (_c_int, [_c_void_p] * 4 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_combine_bwd": (_c_int, [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p] * 3),

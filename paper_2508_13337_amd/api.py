@@ -125,22 +125,27 @@ def xmoe_dispatch(x, token_ids, xd) -> None:
                                dtype_code(x.dtype), _ptr(xd, None, "xd"), _stream()), "xmoe_dispatch")
 
 
-def xmoe_expert_ffn_fwd(xd, expert_offsets, wg, wu, wd, g_save, u_save, y, ws) -> None:
-    B, d = xd.shape
+def xmoe_expert_ffn_fwd(xd, expert_offsets, wg, wu, wd, g_save, u_save, y, ws, row_index=None) -> None:
+    """row_index: None, or token ids [B]: xd is then the token matrix x [T,d] and row i of the input is x[row_index[i]]."""
+    B = xd.shape[0] if row_index is None else row_index.numel()
+    d = xd.shape[1]
     E, d2, f = wg.shape
     dt = xd.dtype
     assert d2 == d and tuple(wu.shape) == (E, d, f) and tuple(wd.shape) == (E, f, d)
     assert expert_offsets.numel() == E + 1
     assert tuple(g_save.shape) == (B, f) and tuple(u_save.shape) == (B, f) and tuple(y.shape) == (B, d)
     _check(lib().xmoe_expert_ffn_fwd(
-        _ptr(xd, None, "xd"), _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f,
+        _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f,
         _ptr(wg, dt, "wg"), _ptr(wu, dt, "wu"), _ptr(wd, dt, "wd"), _ptr(g_save, dt, "g_save"),
         _ptr(u_save, dt, "u_save"), _ptr(y, dt, "y"), dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(),
         _stream()), "xmoe_expert_ffn_fwd")
 
 
-def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd, dwg, dwu, dwd, ws) -> None:
-    B, d = xd.shape
+def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd, dwg, dwu, dwd, ws,
+                        row_index=None) -> None:
+    B = xd.shape[0] if row_index is None else row_index.numel()
+    d = xd.shape[1]
     E, d2, f = wg.shape
     dt = xd.dtype
     assert d2 == d and tuple(wu.shape) == (E, d, f) and tuple(wd.shape) == (E, f, d)
@@ -148,7 +153,8 @@ def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd,
     assert tuple(g_save.shape) == (B, f) and tuple(u_save.shape) == (B, f)
     assert tuple(dy.shape) == (B, d) and tuple(dxd.shape) == (B, d)
     _check(lib().xmoe_expert_ffn_bwd(
-        _ptr(xd, None, "xd"), _ptr(g_save, dt, "g_save"), _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"),
+        _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(g_save, dt, "g_save"),
+        _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"),
         _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(wg, dt), _ptr(wu, dt), _ptr(wd, dt),
         _ptr(dxd, dt, "dxd"), _ptr(dwg, dt, "dwg"), _ptr(dwu, dt, "dwu"), _ptr(dwd, dt, "dwd"), dtype_code(dt),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")

@@ -10,6 +10,7 @@ struct FfnArgs {
     int B, E, d, f, dt;
     const int32_t* off;          // expert_offsets [E+1], device
     const void *xd, *wg, *wu, *wd;
+    const int32_t* row_index;    // NULL, or: xd is the token matrix and row i of the expert input is xd[row_index[i]]
     // forward: outputs g, u, y; backward: inputs g, u, dy and outputs dxd, dwg, dwu, dwd
     void *g, *u, *y;
     const void* dy;

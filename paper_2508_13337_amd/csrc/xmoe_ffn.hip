@@ -35,7 +35,8 @@ using namespace xmoe;
 
 extern "C" {
 
-int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg,
+int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t* expert_offsets, int B, int E, int d,
+                        int f, const void* wg,
                         const void* wu, const void* wd, void* g_save, void* u_save, void* y, int dt, void* ws,
                         size_t ws_bytes, void* stream) {
     int st = check_common(B, E, d, f, dt);
@@ -49,6 +50,7 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, in
     a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt;
     a.off = expert_offsets;
     a.xd = xd; a.wg = wg; a.wu = wu; a.wd = wd;
+    a.row_index = row_index;
     a.g = g_save; a.u = u_save; a.y = y;
     char* p = (char*)ws;
     a.map = (int32_t*)p;
@@ -57,12 +59,12 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* expert_offsets, int B, in
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
     if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_fwd_dma(a, s);
-    if (family_cap() <= FAM_REG && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
+    if (family_cap() <= FAM_REG && !row_index && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
     return ffn_fwd_simt(a, s);
 }
 
-int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, const void* dy,
-                        const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
+int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
+                        const void* dy, const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
                         const void* wd, void* dxd, void* dwg, void* dwu, void* dwd, int dt, void* ws,
                         size_t ws_bytes, void* stream) {
     int st = check_common(B, E, d, f, dt);
@@ -75,6 +77,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, 
     a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt;
     a.off = expert_offsets;
     a.xd = xd; a.wg = wg; a.wu = wu; a.wd = wd;
+    a.row_index = row_index;
     a.g = const_cast<void*>(g_save); a.u = const_cast<void*>(u_save);
     a.dy = dy;
     a.dxd = dxd; a.dwg = dwg; a.dwu = dwu; a.dwd = dwd;
@@ -89,7 +92,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const void* g_save, const void* u_save, 
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
     if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
-    if (family_cap() <= FAM_REG && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
+    if (family_cap() <= FAM_REG && !row_index && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
     return ffn_bwd_simt(a, s);
 }
 

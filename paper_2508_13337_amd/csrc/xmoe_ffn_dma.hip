@@ -111,13 +111,32 @@ struct Operand {
     long ld;
     int n_lo, n_hi;    // row tile: n_lo = valid rows (0..256); col tile: valid columns per 128-wide half
     int k_valid;       // col tile only
+    // gathered operand (loaders with GATHER): the tile's row r (row tile) or k-row r (col tile) is row gather[r] of
+    // the matrix at p_lo - the dispatched copy of the tokens is never made
+    const int32_t* gather;
 };
 
 // per-thread state of the two direct-to-LDS loads an operand needs per stage.  TWO: the K range is the
 // concatenation of two GEMMs (k-tiles [0, nk1) come from operand set 1, [nk1, nk) from set 2).
-template <bool COL, bool TWO>
+// GATHER: rows come through an index array (Operand::gather).  The indices are read with wave-uniform addresses, i.e.
+// through the scalar unit: a per-lane vector load would join the ordered queue of direct-to-LDS loads, and waiting
+// for it would drain the ring.
+template <bool COL, bool TWO, bool GATHER = false>
 struct Loader {
     const bf16_t* g[TWO ? 2 : 1][2];   // global address of this lane's 16 bytes for k-tile 0 (or kZero16)
+    const int32_t* gidx;  // GATHER: index array
+    int gmul[2];          // GATHER && COL: leading dimension of the gathered matrix (0 for lanes that fetch zeros)
+    // GATHER && COL: source rows of this wave's four k-rows of the k-tile that the next issue() loads; fetched one
+    // call ahead (issue() is called for k-tiles 0, 1, 2, ... in order) so their latency is off the critical path
+    mutable int gk[4];
+    __device__ __forceinline__ void fetch_rows(int kt) const {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = kt * TK + wave * 4 + r;
+            gk[r] = gidx[kk < k_valid ? kk : k_valid - 1];   // wave-uniform address
+        }
+    }
     long step[2];         // elements to advance per k-tile (0 for lanes that fetch zeros)
     int krow[2];          // col tile: k index inside the tile, for the k_valid test
     int lds_off[2];       // wave-uniform byte offset of the instruction's 1 KiB destination inside the tile
@@ -125,10 +144,21 @@ struct Loader {
     int nk1, nk;          // k-tiles of set 1, total k-tiles; tiles past the end fetch zeros
 
     __device__ __forceinline__ void init(const Operand& o, const Operand& o2, int num_k1, int num_k) {
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         k_valid = o.k_valid;
         nk1 = num_k1;
         nk = num_k;
+        gidx = o.gather;
+        gmul[0] = gmul[1] = 0;
+        int grow[2] = {0, 0};   // GATHER && !COL: source rows of this lane's two tile rows
+        if (GATHER && !COL) {
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int r = wave * 32 + j;
+                const int v = gidx[r < o.n_lo ? r : o.n_lo - 1];   // wave-uniform address
+                if ((lane >> 2) == (j & 15)) grow[j >> 4] = v;
+            }
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             if (!COL) {
@@ -136,7 +166,7 @@ struct Loader {
                 const int c = (lane & 3) ^ ((row >> 2) & 3);
                 const bool ok = row < o.n_lo;
                 const bf16_t* z = reinterpret_cast<const bf16_t*>(kZero16);
-                g[0][i] = ok ? o.p_lo + (long)row * o.ld + c * 8 : z;
+                g[0][i] = ok ? o.p_lo + (long)(GATHER ? grow[i] : row) * o.ld + c * 8 : z;
                 if (TWO) g[TWO ? 1 : 0][i] = ok ? o2.p_lo + (long)row * o2.ld + c * 8 : z;
                 step[i] = ok ? TK : 0;
                 krow[i] = 0;
@@ -147,20 +177,33 @@ struct Loader {
                 const int col = (c & 15) * 8;
                 const bool hi = c >= 16;
                 const bool ok = col < (hi ? o.n_hi : o.n_lo);
-                g[0][i] = ok ? (hi ? o.p_hi : o.p_lo) + (long)kr * o.ld + col : reinterpret_cast<const bf16_t*>(kZero16);
+                // GATHER: the address of the column inside row 0; the row is looked up per k-tile in issue()
+                g[0][i] = ok ? (hi ? o.p_hi : o.p_lo) + (GATHER ? 0 : (long)kr * o.ld) + col
+                             : reinterpret_cast<const bf16_t*>(kZero16);
                 step[i] = ok ? (long)TK * o.ld : 0;
+                gmul[i] = ok ? (int)o.ld : 0;
                 krow[i] = ok ? kr : (1 << 30);
                 lds_off[i] = (wave * 4 + i * 2) * 512;
             }
         }
+        if (GATHER && COL) fetch_rows(0);
     }
 
     // issues the two loads of k-tile kt into `tile` (LDS address of this operand's tile in the target stage)
     __device__ __forceinline__ void issue(char* tile, int kt, bool probe_zero = false) const {
+        int src_row[2] = {0, 0};
+        if (GATHER && COL) {
+            const int lane = threadIdx.x & 63;
+            src_row[0] = (lane >> 5) ? gk[1] : gk[0];
+            src_row[1] = (lane >> 5) ? gk[3] : gk[2];
+            fetch_rows(kt + 1);
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const bf16_t* p;
-            if (TWO) {
+            if (GATHER && COL) {
+                p = g[0][i] + (long)src_row[i] * gmul[i];
+            } else if (TWO) {
                 p = kt < nk1 ? g[0][i] + (long)kt * step[i] : g[TWO ? 1 : 0][i] + (long)(kt - nk1) * step[i];
             } else {
                 p = g[0][i] + (long)kt * step[i];
@@ -269,8 +312,9 @@ __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt
 // The two stages are distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS
 // read may observe a direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0))
 // before each transposing read, which serialises the ring.
-template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
-__device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1, const Loader<A_COL, TWO>& la,
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER>
+__device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1,
+                                      const Loader<A_COL, TWO, A_GATHER>& la,
                                       const Loader<B_COL, TWO>& lb, char* __restrict__ st_next,
                                       const char* __restrict__ st, int nt) {
     la.issue(st_next, nt, kProbeNoA);
@@ -313,7 +357,7 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
 // 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
 // accumulator registers around every iteration.)
-template <bool A_COL, bool B_COL, bool DUAL, bool TWO>
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER = false>
 __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                           const Operand& oa2, const Operand& ob2, int K2, int mi_count,
                                           char* smem, int probe_idx = -1) {
@@ -321,7 +365,8 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
     if (nk <= 0) return;
     mi_count = __builtin_amdgcn_readfirstlane(mi_count);
-    Loader<A_COL, TWO> la;
+    static_assert(!(A_GATHER && TWO), "a gathered operand cannot be the first of two concatenated ones");
+    Loader<A_COL, TWO, A_GATHER> la;
     Loader<B_COL, TWO> lb;
     la.init(oa, oa2, nk1, nk);
     lb.init(ob, ob2, nk1, nk);
@@ -343,7 +388,7 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         zero_frags(f1);   // the first call multiplies the carried fragments: zeros
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
-            kstep<A_COL, B_COL, DUAL, TWO>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
+            kstep<A_COL, B_COL, DUAL, TWO, A_GATHER>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
                                            smem + (kt % kStages) * kStageBytes, nt);
             wait_loads_and_barrier<kInFlight>();
         }
@@ -362,10 +407,10 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     wait_loads_and_barrier<0>();
 }
 
-template <bool A_COL, bool B_COL, bool DUAL>
+template <bool A_COL, bool B_COL, bool DUAL, bool A_GATHER = false>
 __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                          int mi_count, char* smem, int probe_idx = -1) {
-    mainloop2<A_COL, B_COL, DUAL, false>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
+    mainloop2<A_COL, B_COL, DUAL, false, A_GATHER>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
 }
 
 #ifdef XMOE_PROBE_NOEPI
@@ -511,6 +556,7 @@ __device__ __forceinline__ Operand row_op(const bf16_t* p, long ld, int rows) {
     o.ld = ld;
     o.n_lo = o.n_hi = rows;
     o.k_valid = 0;
+    o.gather = nullptr;
     return o;
 }
 __device__ __forceinline__ Operand col_op(const bf16_t* p, long ld, int cols, int k_valid) {
@@ -521,6 +567,7 @@ __device__ __forceinline__ Operand col_op(const bf16_t* p, long ld, int cols, in
     o.n_lo = cols < 128 ? cols : 128;
     o.n_hi = cols > 128 ? cols - 128 : 0;
     o.k_valid = k_valid;
+    o.gather = nullptr;
     return o;
 }
 
@@ -537,7 +584,11 @@ __device__ __forceinline__ int wave_mi_count(int rows) {
 // =========================================================================================================
 // forward 1: G = Xd Wg, U = Xd Wu, A = silu(G) * U.   Block tile: 256 rows x (128 gate + 128 up columns).
 // =========================================================================================================
+// GATHER: xd is the token matrix x and row i of the expert input is x[row_index[i]] (the gather of dispatch fused
+// into the operand load).
+template <bool GATHER>
 __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __restrict__ xd,
+                                                             const int32_t* __restrict__ row_index,
                                                              const int32_t* __restrict__ off,
                                                              const int32_t* __restrict__ map, int d, int f,
                                                              const bf16_t* __restrict__ wg,
@@ -551,7 +602,8 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     PROBE_BEGIN(0, t, rt.rows)
     const int n0 = (t % nt) * 128;
     const int ncols = f - n0 < 128 ? f - n0 : 128;
-    Operand a = row_op(xd + (long)rt.row0 * d, d, rt.rows);
+    Operand a = row_op(GATHER ? xd : xd + (long)rt.row0 * d, d, rt.rows);
+    if (GATHER) a.gather = row_index + rt.row0;
     Operand b;
     b.p_lo = wg + (long)PROBE_E(rt.e) * d * f + n0;
     b.p_hi = wu + (long)PROBE_E(rt.e) * d * f + n0;
@@ -561,7 +613,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     f32x16_t acc[4][2];
     zero_acc(acc);
     const int mi_count = wave_mi_count(rt.rows);
-    mainloop<false, true, true>(acc, a, b, d, mi_count, smem, PROBE_IDX);
+    mainloop<false, true, true, GATHER>(acc, a, b, d, mi_count, smem, PROBE_IDX);
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, G)
 
@@ -795,8 +847,10 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
 // operands are K-strided -> col tiles).  DUAL: two right-hand sides Q1, Q2 sharing P (dWg and dWu share Xd);
 // the block then covers 128 columns of each.  An expert with no rows gets zeros.
 // =========================================================================================================
-template <bool DUAL>
-__global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P, const bf16_t* __restrict__ Q1,
+template <bool DUAL, bool GATHER>
+__global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P,
+                                                            const int32_t* __restrict__ row_index,
+                                                            const bf16_t* __restrict__ Q1,
                                                             const bf16_t* __restrict__ Q2,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ order,
@@ -830,7 +884,9 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
     f32x16_t acc[4][2];
     zero_acc(acc);
     if (K > 0) {
-        Operand a = col_op(P + (long)lo * M + m0, M, mrows, K);
+        // GATHER: P is the token matrix and k-row r of the expert's P is P[row_index[lo + r]]
+        Operand a = col_op(GATHER ? P + m0 : P + (long)lo * M + m0, M, mrows, K);
+        if (GATHER) a.gather = row_index + lo;
         Operand b;
         if (DUAL) {
             b.p_lo = Q1 + (long)lo * N + n0;
@@ -843,7 +899,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         const int wcol = DUAL ? wn * 32 : wn * 64;
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
-        mainloop<true, true, DUAL>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<true, true, DUAL, GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
     // double-buffered hand-over: the slot written here was last read before the barrier that ended the
     // previous tile
@@ -915,12 +971,14 @@ static int init_once() {
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
             g_num_cu = prop.multiProcessorCount / kNumXcd * kNumXcd;
-        int st = allow_big_lds(ffn_gateup_dma_kernel);
+        int st = allow_big_lds(ffn_gateup_dma_kernel<false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
         state = st;
     }
     return state;
@@ -935,9 +993,16 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
     const bf16_t *xd = (const bf16_t*)a.xd, *wg = (const bf16_t*)a.wg, *wu = (const bf16_t*)a.wu,
                  *wd = (const bf16_t*)a.wd;
     const int ntg = (a.f + 127) / 128, ntd = (a.d + TN - 1) / TN;
-    XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
-                hipLaunchKernelGGL(ffn_gateup_dma_kernel, dim3(round_up8((long)max_tiles * ntg)), dim3(512), kLdsBytes,
-                                   s, xd, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g, (bf16_t*)a.u, (bf16_t*)a.act));
+    if (a.row_index)
+        XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
+                    hipLaunchKernelGGL(ffn_gateup_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
+                                       kLdsBytes, s, xd, a.row_index, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
+                                       (bf16_t*)a.u, (bf16_t*)a.act));
+    else
+        XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
+                    hipLaunchKernelGGL(ffn_gateup_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
+                                       kLdsBytes, s, xd, nullptr, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
+                                       (bf16_t*)a.u, (bf16_t*)a.act));
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.act, a.off, a.map, a.f, a.d, wd, (bf16_t*)a.y, nullptr,
@@ -965,15 +1030,21 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
     // dWd [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
-                hipLaunchKernelGGL(ffn_wgrad_dma_kernel<false>, dim3(round_up8((long)a.E * mtf * ntd)), dim3(512),
-                                   kLdsBytes, s, act, dy, nullptr, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
+                                   dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
                                    (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     const int ntf2 = (a.f + 127) / 128;
-    XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
-                hipLaunchKernelGGL(ffn_wgrad_dma_kernel<true>, dim3(round_up8((long)a.E * mtd * ntf2)), dim3(512),
-                                   kLdsBytes, s, xd, dg, du, a.off, a.sched, a.sched + a.E + kNumXcd, a.E, a.d, a.f,
-                                   (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+    if (a.row_index)
+        XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, a.off, a.sched,
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+    else
+        XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dg, du, a.off, a.sched,
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     return XMOE_OK;
 }
 

@@ -74,7 +74,9 @@ int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int
 // forward 1: G = Xd Wg, U = Xd Wu, A = silu(G) * U          rows: ragged, K = d, N = f
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void ffn_gateup_simt_kernel(const T* __restrict__ xd, const int32_t* __restrict__ off,
+__global__ __launch_bounds__(256) void ffn_gateup_simt_kernel(const T* __restrict__ xd,
+                                                              const int32_t* __restrict__ row_index,   // or NULL
+                                                              const int32_t* __restrict__ off,
                                                               const int32_t* __restrict__ map, int d, int f,
                                                               const T* __restrict__ wg, const T* __restrict__ wu,
                                                               T* __restrict__ G, T* __restrict__ U,
@@ -87,7 +89,12 @@ __global__ __launch_bounds__(256) void ffn_gateup_simt_kernel(const T* __restric
     const int n0 = blockIdx.y * kSimtTile;
     const T* wge = wg + (size_t)e * d * f;
     const T* wue = wu + (size_t)e * d * f;
-    auto loadA = [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(xd[(size_t)r * d + kk]) : 0.f; };
+    auto loadA = [&](int mm, int kk) {
+        int r = row0 + mm;
+        if (r >= row_end) return 0.f;
+        if (row_index) r = row_index[r];   // gather fused: row r of the expert input is row row_index[r] of xd
+        return to_float(xd[(size_t)r * d + kk]);
+    };
     float accg[4][4] = {}, accu[4][4] = {};
     simt_mainloop<true, true>(accg, d, sm, loadA,
                               [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wge[(size_t)kk * f + n]) : 0.f; });
@@ -214,7 +221,9 @@ __global__ __launch_bounds__(256) void ffn_dx_simt_kernel(const T* __restrict__ 
 //   dWd = A^T dY (M=f, N=d);  dWg = Xd^T dG, dWu = Xd^T dU (M=d, N=f).  Empty experts get zeros.
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict__ P, const T* __restrict__ Q,
+__global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict__ P,
+                                                             const int32_t* __restrict__ row_index,   // of P, or NULL
+                                                             const T* __restrict__ Q,
                                                              const int32_t* __restrict__ off, int M, int N,
                                                              T* __restrict__ dW) {
     __shared__ SimtSmem sm;
@@ -223,7 +232,13 @@ __global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict
     const int m0 = blockIdx.x * kSimtTile, n0 = blockIdx.y * kSimtTile;
     float acc[4][4] = {};
     simt_mainloop<false, true>(
-        acc, hi - lo, sm, [&](int mm, int kk) { int m = m0 + mm; return m < M ? to_float(P[(size_t)(lo + kk) * M + m]) : 0.f; },
+        acc, hi - lo, sm,
+        [&](int mm, int kk) {
+            int m = m0 + mm;
+            if (m >= M) return 0.f;
+            const int r = row_index ? row_index[lo + kk] : lo + kk;
+            return to_float(P[(size_t)r * M + m]);
+        },
         [&](int kk, int nn) { int n = n0 + nn; return n < N ? to_float(Q[(size_t)(lo + kk) * N + n]) : 0.f; });
     T* out = dW + (size_t)e * M * N;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -246,7 +261,8 @@ static int fwd_simt(const FfnArgs& a, hipStream_t s) {
     if (st != XMOE_OK) return st;
     dim3 g1(max_tiles, (a.f + kSimtTile - 1) / kSimtTile), g2(max_tiles, (a.d + kSimtTile - 1) / kSimtTile);
     XMOE_LAUNCH(K_FFN_GATEUP_SIMT, s,
-                hipLaunchKernelGGL(ffn_gateup_simt_kernel<T>, g1, dim3(256), 0, s, (const T*)a.xd, a.off, a.map, a.d,
+                hipLaunchKernelGGL(ffn_gateup_simt_kernel<T>, g1, dim3(256), 0, s, (const T*)a.xd, a.row_index, a.off,
+                                   a.map, a.d,
                                    a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.g, (T*)a.u, (T*)a.act));
     XMOE_LAUNCH(K_FFN_DOWN_SIMT, s,
                 hipLaunchKernelGGL(ffn_down_simt_kernel<T>, g2, dim3(256), 0, s, (const T*)a.act, a.off, a.map, a.d,
@@ -269,13 +285,13 @@ static int bwd_simt(const FfnArgs& a, hipStream_t s) {
                                    (const T*)a.du, a.off, a.map, a.d, a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.dxd));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(tf, td, a.E), dim3(256), 0, s, (const T*)a.act,
-                                   (const T*)a.dy, a.off, a.f, a.d, (T*)a.dwd));
+                                   nullptr, (const T*)a.dy, a.off, a.f, a.d, (T*)a.dwd));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
-                                   (const T*)a.dg, a.off, a.d, a.f, (T*)a.dwg));
+                                   a.row_index, (const T*)a.dg, a.off, a.d, a.f, (T*)a.dwg));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
-                                   (const T*)a.du, a.off, a.d, a.f, (T*)a.dwu));
+                                   a.row_index, (const T*)a.du, a.off, a.d, a.f, (T*)a.dwu));
     return XMOE_OK;
 }
 

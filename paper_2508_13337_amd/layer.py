@@ -21,8 +21,10 @@ def append_shared(w_routed: torch.Tensor, w_shared: Optional[torch.Tensor]) -> t
 class XMoELayer:
     """Buffers and call order for one layer of T tokens; weights are passed in by the caller.
 
+    The gather of dispatch is fused into the expert MLP's operand loads: the MLP reads x through token_ids, and no
+    [B,d] copy of the tokens exists (xmoe_dispatch itself is only used to copy dOut into the shared experts' dY rows).
     Shared experts (every token, weight 1) run inside the same grouped-GEMM launches as the routed ones: they are
-    experts E .. E+E_s-1 whose segments are rows [B + s*T, B + (s+1)*T) = a copy of x, so the tail of
+    experts E .. E+E_s-1 whose segments are rows [B + s*T, B + (s+1)*T) and read x[0..T-1], so the tail of
     expert_offsets and of token_ids is constant and written once here."""
 
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, E_s: int = 0, device="cuda",
@@ -55,7 +57,6 @@ class XMoELayer:
         self.expert_ids = torch.empty(B, **i32)
         self.combine_weights = torch.empty(B, **f32)
         self.row_of_slot = torch.empty(B, **i32)
-        self.xd = torch.empty((R, d), **act)
         self.g = torch.empty((R, f), **act)
         self.u = torch.empty((R, f), **act)
         self.y = torch.empty((R, d), **act)
@@ -88,16 +89,14 @@ class XMoELayer:
         if self.max_token_count is None:
             api.xmoe_build_eri(self.topk_idx, self.topk_w, E, self.tokens_per_expert, self.expert_offsets,
                                self.token_ids, self.expert_ids, self.combine_weights, self.row_of_slot, self.ws)
-            api.xmoe_dispatch(x, self.token_ids_all, self.xd)
-            api.xmoe_expert_ffn_fwd(self.xd, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
-                                    self.ws)
+            api.xmoe_expert_ffn_fwd(x, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
+                                    self.ws, row_index=self.token_ids_all)
         else:
             api.xmoe_build_eri_capped(self.topk_idx, self.topk_w, E, self.max_token_count, self.tokens_per_expert,
                                       self.expert_offsets, self.token_ids, self.expert_ids, self.combine_weights,
                                       self.row_of_slot, self.ws)
-            api.xmoe_dispatch(x, self.token_ids, self.xd[:B])
-            api.xmoe_expert_ffn_fwd(self.xd[:B], self.expert_offsets, w["wg"][:E], w["wu"][:E], w["wd"][:E],
-                                    self.g[:B], self.u[:B], self.y[:B], self.ws)
+            api.xmoe_expert_ffn_fwd(x, self.expert_offsets, w["wg"][:E], w["wu"][:E], w["wd"][:E],
+                                    self.g[:B], self.u[:B], self.y[:B], self.ws, row_index=self.token_ids)
             for s in range(self.E_s):
                 seg = slice(B + s * T, B + (s + 1) * T)
                 api.xmoe_expert_ffn_fwd(x, self.one_segment, w["wg"][E + s:E + s + 1], w["wu"][E + s:E + s + 1],
@@ -112,12 +111,13 @@ class XMoELayer:
         if self.max_token_count is None:
             if self.E_s > 0:   # dY of a shared expert's rows is dout itself
                 api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
-            api.xmoe_expert_ffn_bwd(self.xd, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
-                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws)
+            api.xmoe_expert_ffn_bwd(x, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
+                                    row_index=self.token_ids_all)
         else:
-            api.xmoe_expert_ffn_bwd(self.xd[:B], self.g[:B], self.u[:B], self.dy[:B], self.expert_offsets,
+            api.xmoe_expert_ffn_bwd(x, self.g[:B], self.u[:B], self.dy[:B], self.expert_offsets,
                                     w["wg"][:E], w["wu"][:E], w["wd"][:E], self.dxd[:B], grads["dwg"][:E],
-                                    grads["dwu"][:E], grads["dwd"][:E], self.ws)
+                                    grads["dwu"][:E], grads["dwd"][:E], self.ws, row_index=self.token_ids)
             for s in range(self.E_s):
                 seg = slice(B + s * T, B + (s + 1) * T)
                 one = slice(E + s, E + s + 1)

@@ -84,9 +84,9 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.xmoe_build_eri_capped(p, p, 16, 8, 2, 4, p, p, null, p, p, p, p, 1 << 20, null) == INVALID
     assert lib.xmoe_dispatch(p, p, 16, 32, 64, 9, p, null) == UNSUPPORTED
     assert lib.xmoe_dispatch(null, p, 16, 32, 64, 0, p, null) == INVALID
-    assert lib.xmoe_expert_ffn_fwd(p, p, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
-    assert lib.xmoe_expert_ffn_fwd(p, null, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 1 << 30, null) == INVALID
-    assert lib.xmoe_expert_ffn_bwd(p, p, p, p, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
+    assert lib.xmoe_expert_ffn_fwd(p, null, p, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
+    assert lib.xmoe_expert_ffn_fwd(p, null, null, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 1 << 30, null) == INVALID
+    assert lib.xmoe_expert_ffn_bwd(p, null, p, p, p, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
     assert lib.xmoe_combine(p, p, p, null, 0, null, 16, 0, 64, 1, p, null) == INVALID
     assert lib.xmoe_combine(null, p, p, null, 0, null, 16, 2, 64, 1, p, null) == INVALID
     assert lib.xmoe_combine(p, p, p, null, 2, null, 16, 2, 64, 1, p, null) == INVALID     # shared rows missing

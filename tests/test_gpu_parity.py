@@ -285,6 +285,17 @@ def test_expert_ffn_fwd_bwd(name):
         if tpe[e] == 0:
             assert not dwg[e].any() and not dwu[e].any() and not dwd[e].any()
 
+    # gather fused into the operand loads: the same calls on x itself through token_ids, bit-identical results
+    x, tok = to_dev(inp["x"], dt), i32(eri["token_ids"])
+    g2, u2, y2 = torch.empty_like(g), torch.empty_like(u), torch.empty_like(y)
+    m.xmoe_expert_ffn_fwd(x, off, wg, wu, wd, g2, u2, y2, ws, row_index=tok)
+    assert torch.equal(g2, g) and torch.equal(u2, u) and torch.equal(y2, y)
+    dxd2 = torch.empty_like(dxd)
+    dwg2, dwu2, dwd2 = torch.full_like(dwg, 5.0), torch.full_like(dwu, 5.0), torch.full_like(dwd, 5.0)
+    m.xmoe_expert_ffn_bwd(x, to_dev(G, dt), to_dev(U, dt), to_dev(dY, dt), off, wg, wu, wd, dxd2, dwg2, dwu2, dwd2, ws,
+                          row_index=tok)
+    assert torch.equal(dxd2, dxd) and torch.equal(dwg2, dwg) and torch.equal(dwu2, dwu) and torch.equal(dwd2, dwd)
+
 
 # ------------------------------------------------------------------------------------------------ whole layer
 def run_layer(cfg, inp, max_token_count=None):
