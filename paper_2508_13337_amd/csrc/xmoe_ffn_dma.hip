@@ -90,6 +90,9 @@ constexpr bool kProbeNoB = true;
 constexpr bool kProbeNoB = false;
 #endif
 
+#ifndef XMOE_DMA_AUX
+#define XMOE_DMA_AUX 0   // probe: cache-policy bits of the operand loads (bit 0 sc0, bit 1 nt, bit 4 sc1)
+#endif
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -217,7 +220,7 @@ struct Loader {
             p = reinterpret_cast<const bf16_t*>(kZero16);
 #endif
             if (probe_zero) p = reinterpret_cast<const bf16_t*>(kZero16);
-            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, XMOE_DMA_AUX);
         }
     }
 };

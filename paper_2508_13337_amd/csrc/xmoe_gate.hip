@@ -1,7 +1,6 @@
 // Gating of the padding-free MoE layer (paper: Listing 1 gating(); Appendix B.3 "Padding-free Gating"):
 // gate projection in a fixed float32 order, softmax + top-k routing, and their backward.
 #include "xmoe_internal.h"
-#include "xmoe_simt_gemm.h"
 #include "xmoe_sizes.h"
 
 namespace xmoe {
@@ -241,31 +240,70 @@ __global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict_
 // =========================================================================================================
 // backward of the gate projection
 // =========================================================================================================
+// Both GEMMs of the gate projection's backward run on the float32 matrix instruction v_mfma_f32_32x32x2_f32 (the
+// operands are dlogits, float32, and x / w_router widened exactly to float32, so nothing is rounded before the
+// float32 accumulation).  A lane supplies one element of each operand per instruction: lane l holds
+// A[row l%32][k = l/32] and B[k = l/32][column l%32], and ends up with 16 results
+// D[row 8*(v/4) + 4*(l/32) + v%4][column l%32], v = 0..15.
+typedef __attribute__((ext_vector_type(16))) float gate_f32x16_t;
+
 // partial[s][i][e] = sum over the s-th slice of tokens of x[t,i] * dlogits[t,e]
+// The summation index is the token, and both operands are stored token-major, so a half-wave reads 32 consecutive
+// elements of one token's row: no transposition.  A block owns 32 rows i x 64 columns e of one slice; its four
+// waves take interleaved runs of 16 tokens each (enough waves in flight to hide the loads' latency), and their
+// four partial tiles are added through LDS in wave order.  grid = (ceil(d/32), ceil(E/64), splits).
 template <typename T>
 __global__ __launch_bounds__(256) void gate_bwd_dw_kernel(const T* __restrict__ x, const float* __restrict__ dl,
                                                           float* __restrict__ partial, int Tn, int d, int E,
                                                           int t_per_split) {
-    __shared__ SimtSmem sm;
-    const int i0 = blockIdx.x * kSimtTile, e0 = blockIdx.y * kSimtTile;
+    __shared__ float red[4][32][64];   // [wave][accumulator register][lane]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i0 = blockIdx.x * 32, e0 = blockIdx.y * 64;
     const int tb = blockIdx.z * t_per_split;
     int te = tb + t_per_split;
     te = te < Tn ? te : Tn;
-    const int K = te > tb ? te - tb : 0;
-    float acc[4][4] = {};
-    simt_mainloop<false, true>(
-        acc, K, sm,
-        [&](int mm, int kk) { int i = i0 + mm; return i < d ? to_float(x[(size_t)(tb + kk) * d + i]) : 0.f; },
-        [&](int kk, int nn) { int e = e0 + nn; return e < E ? dl[(size_t)(tb + kk) * E + e] : 0.f; });
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int h = lane >> 5, c = lane & 31;
+    const bool ok_i = i0 + c < d, ok_e0 = e0 + c < E, ok_e1 = e0 + 32 + c < E;
+    const T* xa = x + (ok_i ? i0 + c : 0);
+    const float* b0 = dl + (ok_e0 ? e0 + c : 0);
+    const float* b1 = dl + (ok_e1 ? e0 + 32 + c : 0);
+    gate_f32x16_t acc0, acc1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+    constexpr int U = 8;   // instructions' worth of operands fetched before the first is used
+    for (int t0 = tb + wave * 2 * U; t0 < te; t0 += 4 * 2 * U) {
+        float av[U], bv0[U], bv1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + 2 * u + h;
+            const bool ok_t = t < te;
+            av[u] = (ok_t && ok_i) ? to_float(xa[(size_t)t * d]) : 0.f;
+            bv0[u] = (ok_t && ok_e0) ? b0[(size_t)t * E] : 0.f;
+            bv1[u] = (ok_t && ok_e1) ? b1[(size_t)t * E] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv0[u], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv1[u], acc1, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        red[wave][v][lane] = acc0[v];
+        red[wave][16 + v][lane] = acc1[v];
+    }
+    __syncthreads();
     float* out = partial + (size_t)blockIdx.z * d * E;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            int i = i0 + ty * 4 + a, e = e0 + tx * 4 + b;
-            if (i < d && e < E) out[(size_t)i * E + e] = acc[a][b];
-        }
+    for (int r = 0; r < 8; ++r) {
+        const int n = threadIdx.x + 256 * r;   // (accumulator register, lane) pair
+        const int reg = n >> 6, l = n & 63;
+        const float sum = ((red[0][reg][l] + red[1][reg][l]) + red[2][reg][l]) + red[3][reg][l];
+        const int v = reg & 15;
+        const int i = i0 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+        const int e = e0 + 32 * (reg >> 4) + (l & 31);
+        if (i < d && e < E) out[(size_t)i * E + e] = sum;
+    }
 }
 
 template <typename T>
@@ -279,24 +317,98 @@ __global__ __launch_bounds__(256) void gate_bwd_dw_reduce_kernel(const float* __
 }
 
 // dx_gate[t,i] = sum_e dlogits[t,e] * w[i,e]
+// The summation index e is contiguous in both operands.  The instruction sums over its two k-slots and the loop
+// over its steps, so any assignment of experts to (step, slot) gives the same sum: slot h of step q takes expert
+// 32*h + q of a chunk of 64, and a lane then reads 32 consecutive experts of its row with 16-byte loads.
+// One wave: 32 tokens x kDxCols columns i; the token rows of dlogits stay in registers across the columns.
+constexpr int kDxCols = 256;
+
+template <typename T>
+__device__ __forceinline__ void load_row32(const T* __restrict__ p, int n_valid, bool vec, float (&v)[32]);
+template <>
+__device__ __forceinline__ void load_row32<float>(const float* __restrict__ p, int n_valid, bool vec, float (&v)[32]) {
+    if (vec) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float4 f = reinterpret_cast<const float4*>(p)[q];
+            v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 32; ++q) v[q] = q < n_valid ? p[q] : 0.f;
+    }
+}
+template <>
+__device__ __forceinline__ void load_row32<bf16_t>(const bf16_t* __restrict__ p, int n_valid, bool vec,
+                                                   float (&v)[32]) {
+    if (vec) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint4 u4 = reinterpret_cast<const uint4*>(p)[q];
+            const uint32_t u[4] = {u4.x, u4.y, u4.z, u4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[8 * q + 2 * j] = __uint_as_float(u[j] << 16);
+                v[8 * q + 2 * j + 1] = __uint_as_float(u[j] & 0xffff0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 32; ++q) v[q] = q < n_valid ? to_float(p[q]) : 0.f;
+    }
+}
+
+// vec: E % 64 == 0 and both operands 16-byte aligned
 template <typename T>
 __global__ __launch_bounds__(256) void gate_bwd_dx_kernel(const float* __restrict__ dl, const T* __restrict__ w,
-                                                          T* __restrict__ dxg, int Tn, int d, int E) {
-    __shared__ SimtSmem sm;
-    const int t0 = blockIdx.x * kSimtTile, i0 = blockIdx.y * kSimtTile;
-    float acc[4][4] = {};
-    simt_mainloop<true, false>(
-        acc, E, sm,
-        [&](int mm, int kk) { int t = t0 + mm; return t < Tn ? dl[(size_t)t * E + kk] : 0.f; },
-        [&](int kk, int nn) { int i = i0 + nn; return i < d ? to_float(w[(size_t)i * E + kk]) : 0.f; });
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+                                                          T* __restrict__ dxg, int Tn, int d, int E, int vec) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = (blockIdx.x * 4 + wave) * 32;
+    if (t0 >= Tn) return;
+    const int h = lane >> 5, c = lane & 31;
+    const int ibeg = blockIdx.y * kDxCols;
+    const int iend = ibeg + kDxCols < d ? ibeg + kDxCols : d;
+    const bool ok_t = t0 + c < Tn;
+    const float* arow = dl + (size_t)(ok_t ? t0 + c : 0) * E + 32 * h;
+    const bool one_chunk = E <= 64;
+    float av[32];
+    if (one_chunk) load_row32<float>(arow, ok_t ? E - 32 * h : 0, vec && ok_t, av);
+    if (one_chunk && !ok_t) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int q = 0; q < 32; ++q) av[q] = 0.f;
+    }
+    for (int i0 = ibeg; i0 < iend; i0 += 32) {
+        const bool ok_i = i0 + c < d;
+        const T* brow = w + (size_t)(ok_i ? i0 + c : 0) * E + 32 * h;
+        gate_f32x16_t acc;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            int t = t0 + ty * 4 + a, i = i0 + tx * 4 + b;
-            if (t < Tn && i < d) dxg[(size_t)t * d + i] = from_float<T>(acc[a][b]);
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        for (int e0 = 0; e0 < E; e0 += 64) {
+            float bv[32];
+            const int n_valid = E - e0 - 32 * h;   // experts left in this lane's run of 32
+            if (!one_chunk) {
+                load_row32<float>(arow + e0, ok_t ? n_valid : 0, vec && ok_t, av);
+                if (!ok_t) {
+#pragma unroll
+                    for (int q = 0; q < 32; ++q) av[q] = 0.f;
+                }
+            }
+            load_row32<T>(brow + e0, ok_i ? n_valid : 0, vec && ok_i, bv);
+            if (!ok_i) {
+#pragma unroll
+                for (int q = 0; q < 32; ++q) bv[q] = 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 32; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[q], bv[q], acc, 0, 0, 0);
         }
+        if (ok_i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = t0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (t < Tn) dxg[(size_t)t * d + i0 + c] = from_float<T>(acc[v]);
+            }
+        }
+    }
 }
 
 template <typename T>
@@ -315,7 +427,7 @@ static int launch_gate_bwd(const void* x, const void* w, const float* dl, int Tn
                            void* dxg, float* partial, hipStream_t s) {
     const int splits = gate_bwd_splits(Tn);
     const int tps = (Tn + splits - 1) / splits;
-    dim3 g1((d + kSimtTile - 1) / kSimtTile, (E + kSimtTile - 1) / kSimtTile, splits);
+    dim3 g1((d + 31) / 32, (E + 63) / 64, splits);
     XMOE_LAUNCH(K_GATE_BWD_DW, s,
                 hipLaunchKernelGGL(gate_bwd_dw_kernel<T>, g1, dim3(256), 0, s, (const T*)x, dl, partial, Tn, d, E,
                                    tps));
@@ -323,9 +435,11 @@ static int launch_gate_bwd(const void* x, const void* w, const float* dl, int Tn
     XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, s,
                 hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
                                    s, partial, splits, n, (T*)dwr));
-    dim3 g2((Tn + kSimtTile - 1) / kSimtTile, (d + kSimtTile - 1) / kSimtTile);
+    dim3 g2((Tn + 127) / 128, (d + kDxCols - 1) / kDxCols);
+    const int vec = (E % 64 == 0) && aligned16(dl) && aligned16(w);
     XMOE_LAUNCH(K_GATE_BWD_DX, s,
-                hipLaunchKernelGGL(gate_bwd_dx_kernel<T>, g2, dim3(256), 0, s, dl, (const T*)w, (T*)dxg, Tn, d, E));
+                hipLaunchKernelGGL(gate_bwd_dx_kernel<T>, g2, dim3(256), 0, s, dl, (const T*)w, (T*)dxg, Tn, d, E,
+                                   vec));
     return XMOE_OK;
 }
 

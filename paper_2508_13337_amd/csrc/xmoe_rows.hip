@@ -57,38 +57,59 @@ __global__ __launch_bounds__(256) void dispatch_kernel(const T* __restrict__ x, 
         const int nv = d / Vec16<T>::N;
         const uint4* s4 = reinterpret_cast<const uint4*>(src);
         uint4* d4 = reinterpret_cast<uint4*>(dst);
-        for (int c = lane; c < nv; c += 64) d4[c] = s4[c];
+        int c = lane;
+        for (; c + 192 < nv; c += 256) {   // four independent 16-byte loads in flight per lane
+            const uint4 q0 = s4[c], q1 = s4[c + 64], q2 = s4[c + 128], q3 = s4[c + 192];
+            d4[c] = q0;
+            d4[c + 64] = q1;
+            d4[c + 128] = q2;
+            d4[c + 192] = q3;
+        }
+        for (; c < nv; c += 64) d4[c] = s4[c];
     } else {
         for (int c = lane; c < d; c += 64) dst[c] = src[c];
     }
 }
 
 // =========================================================================================================
-// combine: out[t,:] = sum_j w[t,j] * y[row_of_slot[t*k+j],:] (+ addend) (+ addend2)   one wave per token
+// combine: out[t,:] = sum_j w[t,j] * y[row_of_slot[t*k+j],:] (+ shared rows) (+ addend)
+// One block per token, consecutive threads on consecutive 16-byte pieces of the hidden dimension.  Slots are
+// taken KU at a time: the KU row pieces of a column chunk are fetched by independent loads before the first is
+// used.  The sum keeps the slot order j = 0 .. k-1, then the shared rows, then the addend.  An entry with
+// row_of_slot outside [0, B) (a dropped token) contributes nothing.
 // =========================================================================================================
-template <typename T, bool VEC>
+template <typename T, bool VEC, int KU>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, const int32_t* __restrict__ row_of_slot,
                                                       const float* __restrict__ topk_w, const T* __restrict__ shared,
                                                       int n_shared, const T* __restrict__ add, int Tn, int k, int d,
                                                       int B, T* __restrict__ out) {
-    const int lane = threadIdx.x & 63;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= Tn) return;
+    const int t = blockIdx.x;
     constexpr int N = Vec16<T>::N;
     if (VEC) {
         const int nv = d / N;
-        for (int c = lane; c < nv; c += 64) {
+        for (int c = threadIdx.x; c < nv; c += 256) {
             float acc[N];
 #pragma unroll
             for (int i = 0; i < N; ++i) acc[i] = 0.f;
-            for (int j = 0; j < k; ++j) {
-                const int r = row_of_slot[(size_t)t * k + j];
-                if ((unsigned)r >= (unsigned)B) continue;
-                const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.0f;
-                float v[N];
-                Vec16<T>::unpack(reinterpret_cast<const uint4*>(y + (size_t)r * d)[c], v);
+            for (int j0 = 0; j0 < k; j0 += KU) {
+                uint4 q[KU];
+                float w[KU];
 #pragma unroll
-                for (int i = 0; i < N; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+                for (int jj = 0; jj < KU; ++jj) {
+                    const int j = j0 + jj < k ? j0 + jj : k - 1;   // a slot past k re-reads the last one, weight 0
+                    const int r = row_of_slot[(size_t)t * k + j];
+                    const bool ok = j0 + jj < k && (unsigned)r < (unsigned)B;
+                    w[jj] = ok ? (topk_w ? topk_w[(size_t)t * k + j] : 1.0f) : 0.f;
+                    q[jj] = reinterpret_cast<const uint4*>(y + (size_t)(ok ? r : 0) * d)[c];
+                    if (!ok) q[jj] = make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int jj = 0; jj < KU; ++jj) {
+                    float v[N];
+                    Vec16<T>::unpack(q[jj], v);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[i] = fmaf(w[jj], v[i], acc[i]);
+                }
             }
             for (int s = 0; s < n_shared; ++s) {
                 float v[N];
@@ -105,7 +126,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, c
             reinterpret_cast<uint4*>(out + (size_t)t * d)[c] = Vec16<T>::pack(acc);
         }
     } else {
-        for (int c = lane; c < d; c += 64) {
+        for (int c = threadIdx.x; c < d; c += 256) {
             float acc = 0.f;
             for (int j = 0; j < k; ++j) {
                 const int r = row_of_slot[(size_t)t * k + j];
@@ -122,48 +143,76 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, c
 
 // =========================================================================================================
 // combine backward: dy[r,:] = w[t,j] * dout[t,:],  dw[t,j] = <dout[t,:], y[r,:]>,  r = row_of_slot[t*k+j]
-// one wave per token; dout[t,:] is read once per slot from cache
+// One block per token.  Slots in groups of KU: every chunk of dout[t,:] is read once per group and the group's
+// rows of y by independent loads.  A thread accumulates its chunks in ascending order; the 64 lanes of a wave are
+// folded by halving, and the four waves' sums are added in wave order.
 // =========================================================================================================
-template <typename T, bool VEC>
+template <typename T, bool VEC, int KU>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ y,
                                                           const int32_t* __restrict__ row_of_slot,
                                                           const float* __restrict__ topk_w, int Tn, int k, int d,
                                                           int B, T* __restrict__ dy, float* __restrict__ dw) {
-    const int lane = threadIdx.x & 63;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= Tn) return;
+    __shared__ float red[4][KU];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x;
     constexpr int N = Vec16<T>::N;
-    for (int j = 0; j < k; ++j) {
-        const int r = row_of_slot[(size_t)t * k + j];
-        if ((unsigned)r >= (unsigned)B) {   // a dropped entry: the output does not depend on its weight
-            if (lane == 0) dw[(size_t)t * k + j] = 0.f;
-            continue;
+    for (int j0 = 0; j0 < k; j0 += KU) {
+        int r8[KU];
+        float w8[KU], dot[KU];
+#pragma unroll
+        for (int jj = 0; jj < KU; ++jj) {
+            const int j = j0 + jj < k ? j0 + jj : k - 1;
+            const int r = row_of_slot[(size_t)t * k + j];
+            const bool ok = j0 + jj < k && (unsigned)r < (unsigned)B;
+            r8[jj] = ok ? r : -1;
+            w8[jj] = topk_w[(size_t)t * k + j];
+            dot[jj] = 0.f;   // stays 0 for a dropped entry: the output does not depend on its weight
         }
-        const float w = topk_w[(size_t)t * k + j];
-        float dot = 0.f;
         if (VEC) {
             const int nv = d / N;
-            for (int c = lane; c < nv; c += 64) {
-                float g[N], v[N], o[N];
+            for (int c = threadIdx.x; c < nv; c += 256) {
+                float g[N];
                 Vec16<T>::unpack(reinterpret_cast<const uint4*>(dout + (size_t)t * d)[c], g);
-                Vec16<T>::unpack(reinterpret_cast<const uint4*>(y + (size_t)r * d)[c], v);
+                uint4 q[KU];
 #pragma unroll
-                for (int i = 0; i < N; ++i) {
-                    dot = fmaf(g[i], v[i], dot);
-                    o[i] = w * g[i];
+                for (int jj = 0; jj < KU; ++jj)
+                    q[jj] = reinterpret_cast<const uint4*>(y + (size_t)(r8[jj] >= 0 ? r8[jj] : 0) * d)[c];
+#pragma unroll
+                for (int jj = 0; jj < KU; ++jj) {
+                    if (r8[jj] < 0) continue;   // block-uniform
+                    float v[N], o[N];
+                    Vec16<T>::unpack(q[jj], v);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) {
+                        dot[jj] = fmaf(g[i], v[i], dot[jj]);
+                        o[i] = w8[jj] * g[i];
+                    }
+                    reinterpret_cast<uint4*>(dy + (size_t)r8[jj] * d)[c] = Vec16<T>::pack(o);
                 }
-                reinterpret_cast<uint4*>(dy + (size_t)r * d)[c] = Vec16<T>::pack(o);
             }
         } else {
-            for (int c = lane; c < d; c += 64) {
+            for (int c = threadIdx.x; c < d; c += 256) {
                 const float g = to_float(dout[(size_t)t * d + c]);
-                dot = fmaf(g, to_float(y[(size_t)r * d + c]), dot);
-                dy[(size_t)r * d + c] = from_float<T>(w * g);
+#pragma unroll
+                for (int jj = 0; jj < KU; ++jj) {
+                    if (r8[jj] < 0) continue;
+                    dot[jj] = fmaf(g, to_float(y[(size_t)r8[jj] * d + c]), dot[jj]);
+                    dy[(size_t)r8[jj] * d + c] = from_float<T>(w8[jj] * g);
+                }
             }
         }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
-        if (lane == 0) dw[(size_t)t * k + j] = dot;
+        for (int jj = 0; jj < KU; ++jj) {
+            float v = dot[jj];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+            if (lane == 0) red[wave][jj] = v;
+        }
+        __syncthreads();
+        if (threadIdx.x < KU && j0 + threadIdx.x < k)
+            dw[(size_t)t * k + j0 + threadIdx.x] =
+                ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+        __syncthreads();
     }
 }
 
@@ -187,31 +236,51 @@ static int launch_dispatch(const void* x, const int32_t* token_ids, int Tn, int 
     return XMOE_OK;
 }
 
+// slots unrolled per group: the smallest of 2, 4, 6, 8 that covers k (8 for larger k)
+#define XMOE_DISPATCH_KU(k, CALL)  \
+    do {                           \
+        if ((k) <= 2) { CALL(2); } \
+        else if ((k) <= 4) { CALL(4); } \
+        else if ((k) <= 6) { CALL(6); } \
+        else { CALL(8); }          \
+    } while (0)
+
 template <typename T>
 static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* sh, int nsh, const void* add,
                           int Tn, int k, int d, void* out, hipStream_t s) {
-    dim3 grid((Tn + 3) / 4), block(256);
+    dim3 grid(Tn), block(256);
     const int B = Tn * k;
-    if (can_vec<T>(d, {y, sh, add, out}))
-        XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, true>), grid, block, 0, s, (const T*)y, ros, w,
-                                                     (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
-    else
-        XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, false>), grid, block, 0, s, (const T*)y, ros,
-                                                     w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
+    if (can_vec<T>(d, {y, sh, add, out})) {
+#define XMOE_CALL(KU)                                                                                                \
+    XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, true, KU>), grid, block, 0, s, (const T*)y, ros, \
+                                                 w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out))
+        XMOE_DISPATCH_KU(k, XMOE_CALL);
+#undef XMOE_CALL
+    } else {
+        XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, false, 8>), grid, block, 0, s, (const T*)y,
+                                                     ros, w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
+    }
     return XMOE_OK;
 }
 
 template <typename T>
 static int launch_combine_bwd(const void* dout, const void* y, const int32_t* ros, const float* w, int Tn, int k,
                               int d, void* dy, float* dw, hipStream_t s) {
-    dim3 grid((Tn + 3) / 4), block(256);
+    dim3 grid(Tn), block(256);
     const int B = Tn * k;
-    if (can_vec<T>(d, {dout, y, dy}))
-        XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, true>), grid, block, 0, s,
-                                                         (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw));
-    else
-        XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, false>), grid, block, 0, s,
-                                                         (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw));
+    if (can_vec<T>(d, {dout, y, dy})) {
+#define XMOE_CALL(KU)                                                                                      \
+    XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, true, KU>), grid, block, 0, s, \
+                                                     (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw))
+        XMOE_DISPATCH_KU(k, XMOE_CALL);
+#undef XMOE_CALL
+    } else {
+#define XMOE_CALL(KU)                                                                                       \
+    XMOE_LAUNCH(K_COMBINE_BWD, s, hipLaunchKernelGGL((combine_bwd_kernel<T, false, KU>), grid, block, 0, s, \
+                                                     (const T*)dout, (const T*)y, ros, w, Tn, k, d, B, (T*)dy, dw))
+        XMOE_DISPATCH_KU(k, XMOE_CALL);
+#undef XMOE_CALL
+    }
     return XMOE_OK;
 }
 
