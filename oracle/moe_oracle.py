@@ -25,6 +25,11 @@ Readings of the paper that this oracle fixes (the paper is silent or garbled on 
     reproducible bit for bit; an all-float64 mode exists for finite-difference checks.
   * backward is not described in the paper beyond mirroring the forward; it is derived here by calculus with
     the top-k indices held constant.
+  * the paper's own expert (Listing 1 mlp(): two sequential GeMMs w1, w2; Table 1 counts 2 h' h parameters per
+    expert; Table 3's totals need two matrices per expert) is also provided: Y = act(X W1) W2.  The listing
+    prints no activation between the two GeMMs while Section 3.1 speaks of two intermediate activations between
+    the FFN sub-layers; act is therefore a parameter: "identity" (the listing as printed), "gelu" (x Phi(x), the
+    exact erf form: the default of the Megatron-style MLP that the paper's framework trains) or "silu".
 """
 from __future__ import annotations
 
@@ -227,6 +232,144 @@ def shared_ffn_fwd(x, swg, swu, swd):
         G.append(g)
         U.append(u)
     return out, G, U
+
+
+# ----------------------------------------------------------------------------------------------------------
+# the paper's own expert: two-matrix MLP (Listing 1 mlp(w1, w2); Tables 1 and 3)
+# ----------------------------------------------------------------------------------------------------------
+def activation(name: str, h):
+    """act(h) for the two-matrix expert: identity | gelu (h * Phi(h), exact erf form) | silu."""
+    h = np.asarray(h, np.float64)
+    if name == "identity":
+        return h
+    if name == "gelu":
+        from scipy.special import erf          # library primitive
+        return 0.5 * h * (1.0 + erf(h / np.sqrt(2.0)))
+    if name == "silu":
+        return silu(h)
+    raise ValueError(name)
+
+
+def activation_grad(name: str, h):
+    """d act(h) / dh."""
+    h = np.asarray(h, np.float64)
+    if name == "identity":
+        return np.ones_like(h)
+    if name == "gelu":
+        from scipy.special import erf
+        Phi = 0.5 * (1.0 + erf(h / np.sqrt(2.0)))
+        phi = np.exp(-0.5 * h * h) / np.sqrt(2.0 * np.pi)
+        return Phi + h * phi
+    if name == "silu":
+        sig = 1.0 / (1.0 + np.exp(-h))
+        return sig * (1.0 + h * (1.0 - sig))
+    raise ValueError(name)
+
+
+def mlp2_ffn(X, w1, w2, act: str):
+    """One two-matrix expert on its rows: H = X W1 (inter_activ of the listing), Y = act(H) W2.  Returns (Y, H)."""
+    H = X @ w1
+    return activation(act, H) @ w2, H
+
+
+def expert_mlp2_fwd(Xd, expert_offsets, w1, w2, act: str):
+    """Listing 1 mlp(): two sequential GeMMs over the ragged segments.  Returns (Y [B,d], H [B,f])."""
+    Xd = np.asarray(Xd, np.float64)
+    B = Xd.shape[0]
+    E, d, f = w1.shape
+    Y = np.zeros((B, d))
+    H = np.zeros((B, f))
+    for e in range(E):
+        lo, hi = int(expert_offsets[e]), int(expert_offsets[e + 1])
+        if hi == lo:
+            continue
+        Y[lo:hi], H[lo:hi] = mlp2_ffn(Xd[lo:hi], np.asarray(w1[e], np.float64), np.asarray(w2[e], np.float64), act)
+    return Y, H
+
+
+def mlp2_ffn_bwd(X, H, dY, w1, w2, act: str):
+    """Backward of one two-matrix expert.  Returns dX, dW1, dW2."""
+    A = activation(act, H)
+    dA = dY @ w2.T
+    dW2 = A.T @ dY
+    dH = dA * activation_grad(act, H)
+    dX = dH @ w1.T
+    dW1 = X.T @ dH
+    return dX, dW1, dW2
+
+
+def expert_mlp2_bwd(Xd, H, dY, expert_offsets, w1, w2, act: str):
+    """Backward of the two sequential GeMMs; an empty expert gets zero weight gradients."""
+    E, d, f = w1.shape
+    dXd = np.zeros_like(np.asarray(Xd, np.float64))
+    dW1 = np.zeros((E, d, f))
+    dW2 = np.zeros((E, f, d))
+    for e in range(E):
+        lo, hi = int(expert_offsets[e]), int(expert_offsets[e + 1])
+        if hi == lo:
+            continue
+        dXd[lo:hi], dW1[e], dW2[e] = mlp2_ffn_bwd(np.asarray(Xd[lo:hi], np.float64), H[lo:hi], dY[lo:hi],
+                                                  np.asarray(w1[e], np.float64), np.asarray(w2[e], np.float64), act)
+    return dXd, dW1, dW2
+
+
+def moe2_layer_fwd(inp: dict, k: int, act: str, logits_mode: str = "contract",
+                   max_token_count: Optional[int] = None) -> dict:
+    """Listing 1's call(tokens, k, max_token_count, w1, w2) with the paper's two-matrix expert.
+
+    inp: x [T,d], w_router [d,E], bias [E]|None, w1 [E,d,f], w2 [E,f,d]."""
+    x = np.asarray(inp["x"], np.float64)
+    T = x.shape[0]
+    E = inp["w1"].shape[0]
+    if logits_mode == "contract":
+        logits = gate_logits_contract(inp["x"], inp["w_router"], inp.get("bias"))
+    else:
+        logits = gate_logits_f64(inp["x"], inp["w_router"], inp.get("bias"))
+    topk_idx, topk_w, p = route(logits, k)
+    eri = build_eri(topk_idx, topk_w, E) if max_token_count is None else \
+        build_eri_capped(topk_idx, topk_w, E, max_token_count)
+    Xd = dispatch(x, eri["token_ids"])
+    Y, H = expert_mlp2_fwd(Xd, eri["expert_offsets"], inp["w1"], inp["w2"], act)
+    out = combine(Y, eri["token_ids"], eri["combine_weights"], T)
+    return {"logits": logits, "p": p, "topk_idx": topk_idx, "topk_w": topk_w, "eri": eri,
+            "Xd": Xd, "Y": Y, "H": H, "out": out}
+
+
+def moe2_dense_definition(inp: dict, k: int, act: str, logits: np.ndarray) -> np.ndarray:
+    """out[t] = sum_e [e in TopK(t)] p[t,e] act(x[t] W1_e) W2_e, looping over every (t, e); no ERI-arrays."""
+    x = np.asarray(inp["x"], np.float64)
+    T, d = x.shape
+    E = inp["w1"].shape[0]
+    p = softmax(logits)
+    out = np.zeros((T, d))
+    for t in range(T):
+        chosen = sorted(range(E), key=lambda e: (-float(logits[t, e]), e))[:k]
+        for e in chosen:
+            y, _ = mlp2_ffn(x[t:t + 1], np.asarray(inp["w1"][e], np.float64), np.asarray(inp["w2"][e], np.float64),
+                            act)
+            out[t] += p[t, e] * y[0]
+    return out
+
+
+def moe2_layer_bwd(inp: dict, fwd: dict, k: int, act: str) -> dict:
+    """Gradients of L = <dout, out> with respect to x, w_router, w1, w2."""
+    x = np.asarray(inp["x"], np.float64)
+    dout = np.asarray(inp["dout"], np.float64)
+    T = x.shape[0]
+    eri = fwd["eri"]
+    dY, dw = combine_bwd(dout, fwd["Y"], eri["token_ids"], eri["combine_weights"], eri["row_of_slot"], k)
+    dXd, dW1, dW2 = expert_mlp2_bwd(fwd["Xd"], fwd["H"], dY, eri["expert_offsets"], inp["w1"], inp["w2"], act)
+    dx = dispatch_bwd(dXd, eri["row_of_slot"], T, k)
+    dlogits = route_bwd(fwd["p"], fwd["topk_idx"], dw)
+    dWr = x.T @ dlogits
+    dx_gate = dlogits @ np.asarray(inp["w_router"], np.float64).T
+    return {"dY": dY, "dw": dw, "dXd": dXd, "dw1": dW1, "dw2": dW2, "dx_routed": dx, "dlogits": dlogits,
+            "dw_router": dWr, "dx_gate": dx_gate, "dx": dx + dx_gate}
+
+
+def expert_param_count(E: int, d: int, f: int, matrices: int = 2) -> int:
+    """Parameters of one MoE layer's experts: `matrices` matrices of d*f per expert (Table 1: 2 h' h per expert)."""
+    return E * matrices * d * f
 
 
 # ----------------------------------------------------------------------------------------------------------

@@ -23,7 +23,7 @@ import numpy as np
 # tensor ids: fixed, part of the recipe
 _TENSOR_IDS = {
     "x": 1, "w_router": 2, "wg": 3, "wu": 4, "wd": 5, "dout": 6,
-    "shared_wg": 7, "shared_wu": 8, "shared_wd": 9, "rank_perm": 10, "logits": 11,
+    "shared_wg": 7, "shared_wu": 8, "shared_wd": 9, "rank_perm": 10, "logits": 11, "w1": 12, "w2": 13,
 }
 
 
@@ -43,6 +43,8 @@ class MoEConfig:
     w_std: float = 0.02
     skew_alpha: float = 0.0      # 0 -> no per-expert bias; else bias[e] = -alpha*1.2*ln(rank_e)
     seed: int = 0
+    expert: str = "swiglu"       # "swiglu": three matrices wg, wu, wd; "mlp2": the paper's two matrices w1, w2
+    act: str = "gelu"            # activation of the two-matrix expert: identity | gelu | silu
 
     @property
     def B(self) -> int:
@@ -71,6 +73,23 @@ CONFIGS = {
     "odd_f32": MoEConfig("odd_f32", T=77, d=50, E=7, k=3, f=22, dtype="f32", router_std=0.1),
     "odd_bf16": MoEConfig("odd_bf16", T=131, d=72, E=6, k=2, f=24, router_std=0.2),
     "mid_bf16": MoEConfig("mid_bf16", T=1024, d=512, E=16, k=4, f=384, E_s=2),
+    # the paper's own two-matrix expert at the shapes of its Table 3, one GPU's share of tokens, near-uniform load
+    "small_mlp2": MoEConfig("small_mlp2", T=8192, d=2048, E=64, k=6, f=1408, expert="mlp2"),
+    "medium_mlp2": MoEConfig("medium_mlp2", T=8192, d=5120, E=128, k=6, f=1536, expert="mlp2"),
+    "large_mlp2": MoEConfig("large_mlp2", T=4096, d=7168, E=256, k=8, f=2048, expert="mlp2"),
+    "super_mlp2": MoEConfig("super_mlp2", T=4096, d=7168, E=256, k=8, f=2560, expert="mlp2"),
+    # the share of one rank under expert parallelism of degree 8 (the paper's breakdown runs the Small model with
+    # EP = 8): 8 local experts, the same number of rows, segments 8 times as long
+    "small_ep8_mlp2": MoEConfig("small_ep8_mlp2", T=8192, d=2048, E=8, k=6, f=1408, expert="mlp2"),
+    # reduced two-matrix shapes
+    "mini_mlp2_bf16": MoEConfig("mini_mlp2_bf16", T=600, d=256, E=8, k=3, f=192, expert="mlp2"),
+    "mini_mlp2_skew": MoEConfig("mini_mlp2_skew", T=600, d=256, E=8, k=3, f=192, expert="mlp2", skew_alpha=3.0,
+                                act="silu"),
+    "mini_mlp2_f32": MoEConfig("mini_mlp2_f32", T=200, d=96, E=5, k=2, f=40, dtype="f32", router_std=0.05,
+                               expert="mlp2"),
+    "odd_mlp2_bf16": MoEConfig("odd_mlp2_bf16", T=131, d=72, E=6, k=2, f=24, router_std=0.2, expert="mlp2",
+                               act="identity"),
+    "mid_mlp2_bf16": MoEConfig("mid_mlp2_bf16", T=1024, d=512, E=16, k=4, f=384, expert="mlp2"),
 }
 
 
@@ -142,8 +161,8 @@ def make_gate_bias(cfg: MoEConfig) -> Optional[np.ndarray]:
 
 
 def make_expert_weight(cfg: MoEConfig, which: str, e: int) -> np.ndarray:
-    """One routed expert's matrix.  which in {"wg","wu"} -> [d, f]; "wd" -> [f, d]  (in x out, so Y = X W)."""
-    shape = (cfg.d, cfg.f) if which in ("wg", "wu") else (cfg.f, cfg.d)
+    """One routed expert's matrix.  which in {"wg","wu","w1"} -> [d, f]; "wd","w2" -> [f, d]  (in x out, Y = X W)."""
+    shape = (cfg.d, cfg.f) if which in ("wg", "wu", "w1") else (cfg.f, cfg.d)
     return _normal(cfg.seed, which, e, shape, cfg.w_std, cfg.dtype)
 
 
@@ -160,7 +179,7 @@ def iter_expert_weights(cfg: MoEConfig, which: str, batch: int = 16):
 
 def make_expert_weights(cfg: MoEConfig, which: str) -> np.ndarray:
     """All routed experts' matrices stacked: [E, d, f] or [E, f, d]."""
-    shape = (cfg.d, cfg.f) if which in ("wg", "wu") else (cfg.f, cfg.d)
+    shape = (cfg.d, cfg.f) if which in ("wg", "wu", "w1") else (cfg.f, cfg.d)
     out = np.empty((cfg.E,) + shape, dtype=np.float32)
     for e, a in iter_expert_weights(cfg, which):
         out[e] = a
@@ -189,6 +208,15 @@ def make_logits(T: int, E: int, seed: int = 0, std: float = 1.0) -> np.ndarray:
 
 def make_layer_inputs(cfg: MoEConfig) -> dict:
     """Every input of one forward+backward pass, as float32 arrays holding storage-exact values."""
+    if cfg.expert == "mlp2":
+        return {
+            "x": make_x(cfg),
+            "w_router": make_w_router(cfg),
+            "bias": make_gate_bias(cfg),
+            "w1": make_expert_weights(cfg, "w1"),
+            "w2": make_expert_weights(cfg, "w2"),
+            "dout": make_dout(cfg),
+        }
     return {
         "x": make_x(cfg),
         "w_router": make_w_router(cfg),
