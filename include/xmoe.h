@@ -53,8 +53,17 @@ typedef enum {
     XMOE_WS_FFN_FWD = 1,        /* rows = B (FFN rows) */
     XMOE_WS_FFN_BWD = 2,        /* rows = B            */
     XMOE_WS_GATE_BWD = 3,       /* rows = T            */
-    XMOE_WS_BUILD_ERI_CAPPED = 4 /* rows = T           */
+    XMOE_WS_BUILD_ERI_CAPPED = 4, /* rows = T          */
+    XMOE_WS_MLP2_FWD = 5,       /* rows = B            */
+    XMOE_WS_MLP2_BWD = 6        /* rows = B            */
 } xmoe_ws_op;
+
+/* activation of the two-matrix expert (xmoe_expert_mlp2_fwd / _bwd) */
+typedef enum {
+    XMOE_ACT_IDENTITY = 0,      /* act(h) = h: Listing 1's mlp() exactly as printed */
+    XMOE_ACT_GELU = 1,          /* act(h) = h * Phi(h), the exact (erf) form        */
+    XMOE_ACT_SILU = 2           /* act(h) = h * sigmoid(h)                          */
+} xmoe_act;
 
 /* Largest expert count the routing / ERI kernels accept. */
 #define XMOE_MAX_EXPERTS 512
@@ -158,6 +167,27 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
                         const void* wg, const void* wu, const void* wd,
                         void* dxd, void* dwg, void* dwu, void* dwd, int dt,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* The paper's own expert (Listing 1 mlp(pft, w1, w2): two sequential GeMMs over the ragged segments; Table 1 counts
+ * 2 h' h parameters per expert and Table 3's totals need exactly two matrices).  For each expert e and its rows:
+ *   H = Xd_e W1_e  (the listing's inter_activ),   A = act(H),   Y_e = A W2_e          (no biases)
+ * The listing prints no activation between the two GeMMs while Section 3.1 counts two intermediate activations
+ * between the FFN sub-layers, so `act` (an xmoe_act) is a parameter.
+ * xd, row_index, expert_offsets, B, E, d, f: as in xmoe_expert_ffn_fwd.  w1 [E,d,f]; w2 [E,f,d] ("in x out").
+ * Outputs: y [B,d]; h_save [B,f] (kept for backward).  ws: XMOE_WS_MLP2_FWD bytes.
+ */
+int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t* expert_offsets, int B, int E,
+                         int d, int f, const void* w1, const void* w2, int act, void* h_save, void* y, int dt,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of the two-matrix expert (derived; A is recomputed from the saved H):
+ *   dA = dY W2^T;  dW2_e = A_e^T dY_e;  dH = dA * act'(H);  dXd = dH W1^T;  dW1_e = Xd_e^T dH_e.
+ * Outputs: dxd [B,d]; dw1 [E,d,f]; dw2 [E,f,d] - overwritten, all zero for an expert with no rows.
+ * ws: XMOE_WS_MLP2_BWD bytes.
+ */
+int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
+                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
+                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream);
 
 /* Combine (Section 4.1.2 / Appendix B.4 scatter kernel, which must accumulate since k rows share a token),
  * written as a gather-reduce so that no atomics are needed and the sum order is fixed:

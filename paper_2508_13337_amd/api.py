@@ -14,7 +14,8 @@ import torch
 from ._lib import lib
 
 XMOE_F32, XMOE_BF16 = 0, 1
-WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD, WS_BUILD_ERI_CAPPED = 0, 1, 2, 3, 4
+WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD, WS_BUILD_ERI_CAPPED, WS_MLP2_FWD, WS_MLP2_BWD = 0, 1, 2, 3, 4, 5, 6
+ACT_CODES = {"identity": 0, "gelu": 1, "silu": 2}   # xmoe_act
 
 __all__ = [
     "XMoEError", "xmoe_version", "xmoe_workspace_bytes", "xmoe_gate_logits", "xmoe_route", "xmoe_build_eri",
@@ -22,6 +23,7 @@ __all__ = [
     "xmoe_dispatch_bwd", "xmoe_route_bwd", "xmoe_gate_logits_bwd", "xmoe_prof_enable", "xmoe_prof_reset",
     "xmoe_prof_read", "xmoe_prof_copy", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
+    "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
 ]
 
 
@@ -158,6 +160,36 @@ def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd,
         _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(wg, dt), _ptr(wu, dt), _ptr(wd, dt),
         _ptr(dxd, dt, "dxd"), _ptr(dwg, dt, "dwg"), _ptr(dwu, dt, "dwu"), _ptr(dwd, dt, "dwd"), dtype_code(dt),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")
+
+
+def xmoe_expert_mlp2_fwd(xd, expert_offsets, w1, w2, act: str, h_save, y, ws, row_index=None) -> None:
+    """The paper's two-matrix expert.  act: "identity" | "gelu" | "silu".  row_index: as in xmoe_expert_ffn_fwd."""
+    B = xd.shape[0] if row_index is None else row_index.numel()
+    d = xd.shape[1]
+    E, d2, f = w1.shape
+    dt = xd.dtype
+    assert d2 == d and tuple(w2.shape) == (E, f, d) and expert_offsets.numel() == E + 1
+    assert tuple(h_save.shape) == (B, f) and tuple(y.shape) == (B, d)
+    _check(lib().xmoe_expert_mlp2_fwd(
+        _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(w1, dt, "w1"), _ptr(w2, dt, "w2"),
+        ACT_CODES[act], _ptr(h_save, dt, "h_save"), _ptr(y, dt, "y"), dtype_code(dt), _ptr(ws, torch.uint8, "ws"),
+        ws.numel(), _stream()), "xmoe_expert_mlp2_fwd")
+
+
+def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, dw1, dw2, ws, row_index=None) -> None:
+    B = xd.shape[0] if row_index is None else row_index.numel()
+    d = xd.shape[1]
+    E, d2, f = w1.shape
+    dt = xd.dtype
+    assert d2 == d and tuple(w2.shape) == (E, f, d)
+    assert tuple(dw1.shape) == (E, d, f) and tuple(dw2.shape) == (E, f, d)
+    assert tuple(h_save.shape) == (B, f) and tuple(dy.shape) == (B, d) and tuple(dxd.shape) == (B, d)
+    _check(lib().xmoe_expert_mlp2_bwd(
+        _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(h_save, dt, "h_save"),
+        _ptr(dy, dt, "dy"), _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(w1, dt, "w1"),
+        _ptr(w2, dt, "w2"), ACT_CODES[act], _ptr(dxd, dt, "dxd"), _ptr(dw1, dt, "dw1"), _ptr(dw2, dt, "dw2"),
+        dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_mlp2_bwd")
 
 
 def xmoe_combine(y, row_of_slot, topk_w, shared_rows, addend, k: int, out) -> None:

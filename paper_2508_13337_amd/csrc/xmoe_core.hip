@@ -50,6 +50,10 @@ const char* const kKernelNames[K_COUNT] = {
     "ffn_dx_dma_kernel",
     "ffn_wgrad_dma_kernel<false>",
     "ffn_wgrad_dma_kernel<true>",
+    "mlp2_up_simt_kernel",
+    "mlp2_dact_simt_kernel",
+    "mlp2_up_dma_kernel",
+    "mlp2_dact_dma_kernel",
     "prof_copy_kernel",
 };
 
@@ -117,6 +121,8 @@ size_t xmoe_workspace_bytes(int op, int rows, int d, int E, int k, int f, int dt
         case XMOE_WS_FFN_BWD: return ffn_bwd_ws_bytes(rows, E, d, f, dt);
         case XMOE_WS_GATE_BWD: return gate_bwd_ws_bytes(rows, d, E);
         case XMOE_WS_BUILD_ERI_CAPPED: return eri_capped_ws_bytes(rows, E, k);
+        case XMOE_WS_MLP2_FWD: return mlp2_fwd_ws_bytes(rows, E, d, f, dt);
+        case XMOE_WS_MLP2_BWD: return mlp2_bwd_ws_bytes(rows, E, d, f, dt);
         default: return 0;
     }
 }

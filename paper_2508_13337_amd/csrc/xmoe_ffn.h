@@ -21,6 +21,20 @@ struct FfnArgs {
     void *act, *dg, *du;         // A = silu(G)*U, dG, dU   [B,f]
 };
 
+// the two-matrix expert (xmoe_expert_mlp2_fwd / _bwd)
+struct Mlp2Args {
+    int B, E, d, f, dt, act;
+    const int32_t* off;          // expert_offsets [E+1], device
+    const void *xd, *w1, *w2;
+    const int32_t* row_index;    // as in FfnArgs
+    void *h, *y;                 // forward: outputs; backward: h is an input
+    const void* dy;
+    void *dxd, *dw1, *dw2;
+    int32_t* map;
+    int32_t* sched;
+    void *a_buf, *dh;            // A = act(H), dH   [B,f]
+};
+
 int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, int32_t* sched,
                     hipStream_t s);
 
@@ -36,5 +50,11 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s);
 bool ffn_mfma_supported(const FfnArgs& a);
 int ffn_fwd_mfma(const FfnArgs& a, hipStream_t s);
 int ffn_bwd_mfma(const FfnArgs& a, hipStream_t s);
+
+int mlp2_fwd_simt(const Mlp2Args& a, hipStream_t s);
+int mlp2_bwd_simt(const Mlp2Args& a, hipStream_t s);
+bool mlp2_dma_supported(const Mlp2Args& a);
+int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s);
+int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s);
 
 }  // namespace xmoe

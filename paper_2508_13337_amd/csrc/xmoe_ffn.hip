@@ -96,4 +96,61 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     return ffn_bwd_simt(a, s);
 }
 
+int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t* expert_offsets, int B, int E,
+                         int d, int f, const void* w1, const void* w2, int act, void* h_save, void* y, int dt,
+                         void* ws, size_t ws_bytes, void* stream) {
+    int st = check_common(B, E, d, f, dt);
+    if (st != XMOE_OK) return st;
+    if (!act_ok(act)) return XMOE_ERR_UNSUPPORTED;
+    if (!expert_offsets || !w1 || !w2) return XMOE_ERR_INVALID_ARG;
+    if (B == 0) return XMOE_OK;
+    if (!xd || !h_save || !y) return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < mlp2_fwd_ws_bytes(B, E, d, f, dt))
+        return XMOE_ERR_WORKSPACE;
+    Mlp2Args a{};
+    a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt; a.act = act;
+    a.off = expert_offsets;
+    a.xd = xd; a.w1 = w1; a.w2 = w2;
+    a.row_index = row_index;
+    a.h = h_save; a.y = y;
+    char* p = (char*)ws;
+    a.map = (int32_t*)p;
+    a.sched = a.map + ffn_sched_offset(B, E);
+    p += ffn_tilemap_bytes(B, E);
+    a.a_buf = p;
+    hipStream_t s = (hipStream_t)stream;
+    if (family_cap() <= FAM_DMA && mlp2_dma_supported(a)) return mlp2_fwd_dma(a, s);
+    return mlp2_fwd_simt(a, s);
+}
+
+int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
+                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
+                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream) {
+    int st = check_common(B, E, d, f, dt);
+    if (st != XMOE_OK) return st;
+    if (!act_ok(act)) return XMOE_ERR_UNSUPPORTED;
+    if (!expert_offsets || !w1 || !w2 || !dw1 || !dw2) return XMOE_ERR_INVALID_ARG;
+    if (B > 0 && (!xd || !h_save || !dy || !dxd)) return XMOE_ERR_INVALID_ARG;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < mlp2_bwd_ws_bytes(B, E, d, f, dt))
+        return XMOE_ERR_WORKSPACE;
+    Mlp2Args a{};
+    a.B = B; a.E = E; a.d = d; a.f = f; a.dt = dt; a.act = act;
+    a.off = expert_offsets;
+    a.xd = xd; a.w1 = w1; a.w2 = w2;
+    a.row_index = row_index;
+    a.h = const_cast<void*>(h_save);
+    a.dy = dy;
+    a.dxd = dxd; a.dw1 = dw1; a.dw2 = dw2;
+    char* p = (char*)ws;
+    a.map = (int32_t*)p;
+    a.sched = a.map + ffn_sched_offset(B, E);
+    p += ffn_tilemap_bytes(B, E);
+    a.dh = p;
+    p += ffn_act_bytes(B, f, dt);
+    a.a_buf = p;
+    hipStream_t s = (hipStream_t)stream;
+    if (family_cap() <= FAM_DMA && mlp2_dma_supported(a)) return mlp2_bwd_dma(a, s);
+    return mlp2_bwd_simt(a, s);
+}
+
 }  // extern "C"

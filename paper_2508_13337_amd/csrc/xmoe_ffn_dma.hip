@@ -796,6 +796,8 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
 // =========================================================================================================
 // backward 2: dXd = dG Wg^T + dU Wu^T     (K = f twice, N = d; Wg, Wu [d, f]: rows are output columns)
 // =========================================================================================================
+// TWO = false: a single pair (the two-matrix expert: dXd = dH W1^T), dU and wu are not read
+template <bool TWO>
 __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restrict__ dG, const bf16_t* __restrict__ dU,
                                                          const int32_t* __restrict__ off,
                                                          const int32_t* __restrict__ map, int d, int f,
@@ -816,9 +818,9 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
     {
         Operand a1 = row_op(dG + (long)rt.row0 * f, f, rt.rows);
         Operand b1 = row_op(wg + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols);
-        Operand a2 = row_op(dU + (long)rt.row0 * f, f, rt.rows);
-        Operand b2 = row_op(wu + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols);
-        mainloop2<false, false, false, true>(acc, a1, b1, f, a2, b2, f, mi_count, smem, PROBE_IDX);
+        Operand a2 = TWO ? row_op(dU + (long)rt.row0 * f, f, rt.rows) : a1;
+        Operand b2 = TWO ? row_op(wu + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols) : b1;
+        mainloop2<false, false, false, TWO>(acc, a1, b1, f, a2, b2, TWO ? f : 0, mi_count, smem, PROBE_IDX);
     }
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dXd)
@@ -842,6 +844,175 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         // every wave has left its staging strip before the next tile's loads land in the ring
         lds_done_and_barrier();
         PROBE_MARK(PROBE_IDX, 3)
+    }
+}
+
+// =========================================================================================================
+// two-matrix expert, forward 1: H = Xd W1, A = act(H)      (K = d, N = f, weights "in x out" -> col tile)
+// =========================================================================================================
+// activation of the matrix-core epilogues: silu takes the hardware exp2 / reciprocal like the SwiGLU epilogues
+template <int ACT>
+__device__ __forceinline__ float act_fast(float h) {
+    if (ACT == XMOE_ACT_SILU) return h * fast_sigmoid(h);
+    return act_fwd<ACT>(h);
+}
+template <int ACT>
+__device__ __forceinline__ void act_fast_grad(float h, float& a, float& g) {
+    if (ACT == XMOE_ACT_SILU) {
+        const float sg = fast_sigmoid(h);
+        a = h * sg;
+        g = sg * (1.0f + h * (1.0f - sg));
+    } else {
+        act_fwd_grad<ACT>(h, a, g);
+    }
+}
+
+template <bool GATHER, int ACT>
+__global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restrict__ xd,
+                                                          const int32_t* __restrict__ row_index,
+                                                          const int32_t* __restrict__ off,
+                                                          const int32_t* __restrict__ map, int d, int f,
+                                                          const bf16_t* __restrict__ w1, bf16_t* __restrict__ H,
+                                                          bf16_t* __restrict__ A) {
+    extern __shared__ __align__(16) char smem[];
+    const int nt = (f + TN - 1) / TN;
+    const TileRange tr = tile_range(map[0] * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
+        const RowTile rt = get_row_tile(map, off, t / nt);
+        const int n0 = (t % nt) * TN;
+        const int ncols = f - n0 < TN ? f - n0 : TN;
+        Operand a = row_op(GATHER ? xd : xd + (long)rt.row0 * d, d, rt.rows);
+        if (GATHER) a.gather = row_index + rt.row0;
+        Operand b = col_op(w1 + (long)rt.e * d * f + n0, f, ncols, d);
+        f32x16_t acc[4][2];
+        zero_acc(acc);
+        const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+        const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
+        mainloop<false, true, false, GATHER>(acc, a, b, d, mi_count, smem);
+        char* strip = smem + wave * kStripBytes;
+        const int cols_valid = ncols - wn * 64;
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) {
+            const int r0 = wm * 128 + mi * 32;
+            const int rows_valid = rt.rows - r0;
+            const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64;
+            float x0[16], x1[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                x0[v] = acc[mi][0][v];
+                x1[v] = acc[mi][1][v];
+            }
+            strip_put(strip, 0, x0);
+            strip_put(strip, 32, x1);
+            strip_sync();
+            strip_flush<64>(strip, 0, H + base, f, rows_valid, cols_valid);
+            strip_sync();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                x0[v] = act_fast<ACT>(x0[v]);
+                x1[v] = act_fast<ACT>(x1[v]);
+            }
+            strip_put(strip, 0, x0);
+            strip_put(strip, 32, x1);
+            strip_sync();
+            strip_flush<64>(strip, 0, A + base, f, rows_valid, cols_valid);
+            strip_sync();
+        }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
+    }
+}
+
+// =========================================================================================================
+// two-matrix expert, backward 1: dA = dY W2^T (K = d, N = f; W2 [f, d]: its rows are the output columns), then
+// dH = dA * act'(H) and A = act(H) in the epilogue
+// =========================================================================================================
+template <int ACT>
+__global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __restrict__ dY,
+                                                            const int32_t* __restrict__ off,
+                                                            const int32_t* __restrict__ map, int d, int f,
+                                                            const bf16_t* __restrict__ w2,
+                                                            const bf16_t* __restrict__ H, bf16_t* __restrict__ dH,
+                                                            bf16_t* __restrict__ A) {
+    extern __shared__ __align__(16) char smem[];
+    const int nt = (f + TN - 1) / TN;
+    const TileRange tr = tile_range(map[0] * nt);
+    for (int t = tr.first; t < tr.end; t += tr.stride) {
+        const RowTile rt = get_row_tile(map, off, t / nt);
+        const int n0 = (t % nt) * TN;
+        const int ncols = f - n0 < TN ? f - n0 : TN;
+        Operand a = row_op(dY + (long)rt.row0 * d, d, rt.rows);
+        Operand b = row_op(w2 + (long)rt.e * f * d + (long)n0 * d, d, ncols);
+        f32x16_t acc[4][2];
+        zero_acc(acc);
+        const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
+        const int lane = threadIdx.x & 63;
+        const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
+        mainloop<false, false, false>(acc, a, b, d, mi_count, smem);
+        char* strip = smem + wave * kStripBytes;
+        const int cols_valid = ncols - wn * 64;
+        // 8 rounds (mi, ni) of 32 x 32 outputs.  H of a round is fetched as full 64-byte row pieces (4 lanes per
+        // row, 16 rows per instruction) while the previous round is computed and stored, then turned into the
+        // accumulator layout through a wave-private LDS buffer (rows of 64 bytes, 16-byte chunks XOR-swizzled).
+        const int m = lane & 31;
+        char* inbuf = smem + 8 * kStripBytes + wave * kInBytes;
+        uint4 hq[2][2];
+        const int frow = lane >> 2, fchunk = lane & 3;
+        auto fetch = [&](int r, uint4 (&h2)[2]) {
+            const int mi = r >> 1, ni = r & 1;
+            const int r0 = wm * 128 + mi * 32;
+            const int rows_valid = rt.rows - r0;
+            const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64 + ni * 32;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = 16 * i + frow;
+                h2[i] = make_uint4(0, 0, 0, 0);
+                if (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid)
+                    h2[i] = *reinterpret_cast<const uint4*>(H + base + (long)row * f + fchunk * 8);
+            }
+        };
+        fetch(0, hq[0]);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int mi = r >> 1, ni = r & 1;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = 16 * i + frow;
+                const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
+                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = hq[r & 1][i];
+            }
+            if (r + 1 < 8) fetch(r + 1, hq[(r + 1) & 1]);
+            strip_sync();
+            const int r0 = wm * 128 + mi * 32;
+            const int rows_valid = rt.rows - r0;
+            const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64;
+            uint2 hv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
+                hv[q] = *reinterpret_cast<const uint2*>(inbuf + m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5));
+            float dh[16], av[16];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t hw[2] = {hv[q].x, hv[q].y};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t hb = (j & 1) ? (hw[j >> 1] & 0xffff0000u) : (hw[j >> 1] << 16);
+                    float a_, g_;
+                    act_fast_grad<ACT>(__uint_as_float(hb), a_, g_);
+                    dh[4 * q + j] = acc[mi][ni][4 * q + j] * g_;
+                    av[4 * q + j] = a_;
+                }
+            }
+            strip_put(strip, 0, dh);
+            strip_put(strip, 32, av);
+            strip_sync();
+            const long o = base + ni * 32;
+            strip_flush<32>(strip, 0, dH + o, f, rows_valid, cols_valid - ni * 32);
+            strip_flush<32>(strip, 32, A + o, f, rows_valid, cols_valid - ni * 32);
+            strip_sync();
+        }
+        // every wave has left its staging strip before the next tile's loads land in the ring
+        lds_done_and_barrier();
     }
 }
 
@@ -978,7 +1149,18 @@ static int init_once() {
         if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, true>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_IDENTITY>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_GELU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_SILU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_IDENTITY>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_GELU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_SILU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
@@ -1028,7 +1210,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                                    kLdsBytes, s, dy, a.off, a.map, a.d, a.f, wd, nullptr, (const bf16_t*)a.g,
                                    (const bf16_t*)a.u, dg, du, act));
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
-                hipLaunchKernelGGL(ffn_dx_dma_kernel, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
+                hipLaunchKernelGGL(ffn_dx_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
                                    du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd));
     // dWd [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
@@ -1048,6 +1230,86 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
                                        dim3(512), kLdsBytes, s, xd, nullptr, dg, du, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+    return XMOE_OK;
+}
+
+bool mlp2_dma_supported(const Mlp2Args& a) {
+    if (a.dt != XMOE_BF16) return false;
+    if (a.d % 64 != 0 || a.f % 64 != 0) return false;
+    const void* ptrs[] = {a.xd, a.w1, a.w2, a.h, a.y, a.dy, a.dxd, a.dw1, a.dw2, a.a_buf, a.dh};
+    for (const void* p : ptrs)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+
+int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
+    int st = init_once();
+    if (st != XMOE_OK) return st;
+    const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
+    if (st != XMOE_OK) return st;
+    const bf16_t *xd = (const bf16_t*)a.xd, *w1 = (const bf16_t*)a.w1, *w2 = (const bf16_t*)a.w2;
+    const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
+    const dim3 grid(round_up8((long)max_tiles * ntf));
+    if (a.row_index) {
+#define XMOE_CALL(ACT)                                                                                               \
+    XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
+                hipLaunchKernelGGL((mlp2_up_dma_kernel<true, ACT>), grid, dim3(512), kLdsBytes, s, xd, a.row_index,  \
+                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf))
+        XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    } else {
+#define XMOE_CALL(ACT)                                                                                               \
+    XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
+                hipLaunchKernelGGL((mlp2_up_dma_kernel<false, ACT>), grid, dim3(512), kLdsBytes, s, xd, nullptr,     \
+                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf))
+        XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    }
+    XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
+                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
+                                   kLdsBytes, s, (const bf16_t*)a.a_buf, a.off, a.map, a.f, a.d, w2, (bf16_t*)a.y,
+                                   nullptr, nullptr, nullptr, nullptr, nullptr));
+    return XMOE_OK;
+}
+
+int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
+    int st = init_once();
+    if (st != XMOE_OK) return st;
+    const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
+    st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
+    if (st != XMOE_OK) return st;
+    const bf16_t *xd = (const bf16_t*)a.xd, *w1 = (const bf16_t*)a.w1, *w2 = (const bf16_t*)a.w2,
+                 *dy = (const bf16_t*)a.dy;
+    bf16_t *dh = (bf16_t*)a.dh, *act = (bf16_t*)a.a_buf;
+    const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
+    const dim3 grid(round_up8((long)max_tiles * ntf));
+#define XMOE_CALL(ACT)                                                                                            \
+    XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                               \
+                hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT>), grid, dim3(512), kLdsBytes, s, dy, a.off, a.map,  \
+                                   a.d, a.f, w2, (const bf16_t*)a.h, dh, act))
+    XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    XMOE_LAUNCH(K_FFN_DX_DMA, s,
+                hipLaunchKernelGGL(ffn_dx_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
+                                   kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd));
+    // dW2 [f, d] = A^T dY
+    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
+    XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
+                                   dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, a.off, a.sched, a.sched + a.E,
+                                   a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr));
+    // dW1 [d, f] = Xd^T dH
+    if (a.row_index)
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, true>), dim3(round_up8((long)a.E * mtd * ntf)),
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, a.off, a.sched,
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
+    else
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtd * ntf)),
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, a.off, a.sched,
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
     return XMOE_OK;
 }
 

@@ -203,9 +203,10 @@ __global__ __launch_bounds__(256) void ffn_dx_simt_kernel(const T* __restrict__ 
     simt_mainloop<true, false>(
         acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dG[(size_t)r * f + kk]) : 0.f; },
         [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wge[(size_t)n * f + kk]) : 0.f; });
-    simt_mainloop<true, false>(
-        acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dU[(size_t)r * f + kk]) : 0.f; },
-        [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wue[(size_t)n * f + kk]) : 0.f; });
+    if (dU)   // the two-matrix expert has a single pair (dH, W1)
+        simt_mainloop<true, false>(
+            acc, f, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dU[(size_t)r * f + kk]) : 0.f; },
+            [&](int kk, int nn) { int n = n0 + nn; return n < d ? to_float(wue[(size_t)n * f + kk]) : 0.f; });
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -252,6 +253,81 @@ __global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// two-matrix expert, forward 1: H = Xd W1, A = act(H)         rows: ragged, K = d, N = f
+// ---------------------------------------------------------------------------------------------------------
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void mlp2_up_simt_kernel(const T* __restrict__ xd,
+                                                           const int32_t* __restrict__ row_index,   // or NULL
+                                                           const int32_t* __restrict__ off,
+                                                           const int32_t* __restrict__ map, int d, int f,
+                                                           const T* __restrict__ w1, T* __restrict__ H,
+                                                           T* __restrict__ A) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* w1e = w1 + (size_t)e * d * f;
+    float acc[4][4] = {};
+    simt_mainloop<true, true>(
+        acc, d, sm,
+        [&](int mm, int kk) {
+            int r = row0 + mm;
+            if (r >= row_end) return 0.f;
+            if (row_index) r = row_index[r];
+            return to_float(xd[(size_t)r * d + kk]);
+        },
+        [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(w1e[(size_t)kk * f + n]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < f) {
+                H[(size_t)r * f + n] = from_float<T>(acc[i][j]);
+                A[(size_t)r * f + n] = from_float<T>(act_fwd<ACT>(acc[i][j]));
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// two-matrix expert, backward 1: dA = dY W2^T, then dH = dA * act'(H), A = act(H)     K = d, N = f
+// ---------------------------------------------------------------------------------------------------------
+template <typename T, int ACT>
+__global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict__ dY, const int32_t* __restrict__ off,
+                                                             const int32_t* __restrict__ map, int d, int f,
+                                                             const T* __restrict__ w2, const T* __restrict__ H,
+                                                             T* __restrict__ dH, T* __restrict__ A) {
+    __shared__ SimtSmem sm;
+    const int e = map[4 + 2 * blockIdx.x];
+    if (e < 0) return;
+    const int row0 = map[4 + 2 * blockIdx.x + 1];
+    const int row_end = off[e + 1];
+    const int n0 = blockIdx.y * kSimtTile;
+    const T* w2e = w2 + (size_t)e * f * d;
+    float acc[4][4] = {};
+    simt_mainloop<true, false>(
+        acc, d, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dY[(size_t)r * d + kk]) : 0.f; },
+        [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(w2e[(size_t)n * d + kk]) : 0.f; });
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
+            if (r < row_end && n < f) {
+                const size_t ix = (size_t)r * f + n;
+                float a, g;
+                act_fwd_grad<ACT>(to_float(H[ix]), a, g);
+                dH[ix] = from_float<T>(acc[i][j] * g);
+                A[ix] = from_float<T>(a);
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // host-side drivers
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
@@ -293,6 +369,57 @@ static int bwd_simt(const FfnArgs& a, hipStream_t s) {
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
                                    a.row_index, (const T*)a.du, a.off, a.d, a.f, (T*)a.dwu));
     return XMOE_OK;
+}
+
+template <typename T>
+static int mlp2_fwd_simt_t(const Mlp2Args& a, hipStream_t s) {
+    const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, a.sched, s);
+    if (st != XMOE_OK) return st;
+    dim3 g1(max_tiles, (a.f + kSimtTile - 1) / kSimtTile), g2(max_tiles, (a.d + kSimtTile - 1) / kSimtTile);
+#define XMOE_CALL(ACT)                                                                                              \
+    XMOE_LAUNCH(K_MLP2_UP_SIMT, s,                                                                                  \
+                hipLaunchKernelGGL((mlp2_up_simt_kernel<T, ACT>), g1, dim3(256), 0, s, (const T*)a.xd, a.row_index, \
+                                   a.off, a.map, a.d, a.f, (const T*)a.w1, (T*)a.h, (T*)a.a_buf))
+    XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    XMOE_LAUNCH(K_FFN_DOWN_SIMT, s,
+                hipLaunchKernelGGL(ffn_down_simt_kernel<T>, g2, dim3(256), 0, s, (const T*)a.a_buf, a.off, a.map, a.d,
+                                   a.f, (const T*)a.w2, (T*)a.y));
+    return XMOE_OK;
+}
+
+template <typename T>
+static int mlp2_bwd_simt_t(const Mlp2Args& a, hipStream_t s) {
+    const int max_tiles = ffn_max_tiles(a.B, a.E, kSimtTile);
+    int st = launch_tile_map(a.off, a.E, kSimtTile, max_tiles, a.map, a.sched, s);
+    if (st != XMOE_OK) return st;
+    const int tf = (a.f + kSimtTile - 1) / kSimtTile, td = (a.d + kSimtTile - 1) / kSimtTile;
+#define XMOE_CALL(ACT)                                                                                          \
+    XMOE_LAUNCH(K_MLP2_DACT_SIMT, s,                                                                            \
+                hipLaunchKernelGGL((mlp2_dact_simt_kernel<T, ACT>), dim3(max_tiles, tf), dim3(256), 0, s,       \
+                                   (const T*)a.dy, a.off, a.map, a.d, a.f, (const T*)a.w2, (const T*)a.h,       \
+                                   (T*)a.dh, (T*)a.a_buf))
+    XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    XMOE_LAUNCH(K_FFN_DX_SIMT, s,
+                hipLaunchKernelGGL(ffn_dx_simt_kernel<T>, dim3(max_tiles, td), dim3(256), 0, s, (const T*)a.dh,
+                                   (const T*)nullptr, a.off, a.map, a.d, a.f, (const T*)a.w1, (const T*)nullptr,
+                                   (T*)a.dxd));
+    XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
+                hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(tf, td, a.E), dim3(256), 0, s, (const T*)a.a_buf,
+                                   nullptr, (const T*)a.dy, a.off, a.f, a.d, (T*)a.dw2));
+    XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
+                hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
+                                   a.row_index, (const T*)a.dh, a.off, a.d, a.f, (T*)a.dw1));
+    return XMOE_OK;
+}
+
+int mlp2_fwd_simt(const Mlp2Args& a, hipStream_t s) {
+    return a.dt == XMOE_F32 ? mlp2_fwd_simt_t<float>(a, s) : mlp2_fwd_simt_t<bf16_t>(a, s);
+}
+int mlp2_bwd_simt(const Mlp2Args& a, hipStream_t s) {
+    return a.dt == XMOE_F32 ? mlp2_bwd_simt_t<float>(a, s) : mlp2_bwd_simt_t<bf16_t>(a, s);
 }
 
 int ffn_fwd_simt(const FfnArgs& a, hipStream_t s) {

@@ -42,6 +42,10 @@ enum KernelId : int {
     K_FFN_DX_DMA,
     K_FFN_WGRAD_DMA,
     K_FFN_WGRAD_DUAL_DMA,
+    K_MLP2_UP_SIMT,
+    K_MLP2_DACT_SIMT,
+    K_MLP2_UP_DMA,
+    K_MLP2_DACT_DMA,
     K_PROF_COPY,
     K_COUNT
 };
@@ -95,5 +99,38 @@ constexpr int kWave = 64;
 // silu(g) = g * sigmoid(g) and its derivative, in float32
 __device__ __forceinline__ float sigmoidf_(float g) { return 1.0f / (1.0f + expf(-g)); }
 __device__ __forceinline__ float siluf_(float g) { return g * sigmoidf_(g); }
+
+// activation of the two-matrix expert and its derivative, in float32 (ACT is an xmoe_act)
+template <int ACT>
+__device__ __forceinline__ float act_fwd(float h) {
+    if (ACT == XMOE_ACT_GELU) return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f));
+    if (ACT == XMOE_ACT_SILU) return siluf_(h);
+    return h;
+}
+// a = act(h), g = act'(h)
+template <int ACT>
+__device__ __forceinline__ void act_fwd_grad(float h, float& a, float& g) {
+    if (ACT == XMOE_ACT_GELU) {
+        const float Phi = 0.5f * (1.0f + erff(h * 0.70710678118654752f));
+        a = h * Phi;
+        g = Phi + h * (0.39894228040143268f * expf(-0.5f * h * h));
+    } else if (ACT == XMOE_ACT_SILU) {
+        const float sg = sigmoidf_(h);
+        a = h * sg;
+        g = sg * (1.0f + h * (1.0f - sg));
+    } else {
+        a = h;
+        g = 1.0f;
+    }
+}
+static inline bool act_ok(int act) { return act == XMOE_ACT_IDENTITY || act == XMOE_ACT_GELU || act == XMOE_ACT_SILU; }
+
+// runs CALL(ACT) with the run-time activation code as a compile-time constant
+#define XMOE_DISPATCH_ACT(act, CALL)                              \
+    do {                                                           \
+        if ((act) == XMOE_ACT_GELU) { CALL(XMOE_ACT_GELU); }       \
+        else if ((act) == XMOE_ACT_SILU) { CALL(XMOE_ACT_SILU); }  \
+        else { CALL(XMOE_ACT_IDENTITY); }                          \
+    } while (0)
 
 }  // namespace xmoe

@@ -47,6 +47,16 @@ static inline size_t ffn_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
     return ffn_tilemap_bytes(B, E) + 3 * ffn_act_bytes(B, f, dt);             // tile map | dG | dU | A
 }
 
+// two-matrix expert: tile map | A = act(H)   and   tile map | dH | A
+static inline size_t mlp2_fwd_ws_bytes(int B, int E, int d, int f, int dt) {
+    (void)d;
+    return ffn_tilemap_bytes(B, E) + ffn_act_bytes(B, f, dt);
+}
+static inline size_t mlp2_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
+    (void)d;
+    return ffn_tilemap_bytes(B, E) + 2 * ffn_act_bytes(B, f, dt);
+}
+
 // ----- gate projection backward: split-K partial sums of dWr -----
 static inline int gate_bwd_splits(int T) {
     int s = (T + 255) / 256;

@@ -128,3 +128,61 @@ class XMoELayer:
         api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
         api.xmoe_dispatch_bwd(self.dxd[:B], self.row_of_slot, self._shared(self.dxd), self.dx_gate, self.k, self.dx)
         return self.dx
+
+
+class XMoE2Layer:
+    """The same layer with the paper's own expert, Y = act(X W1) W2 (Listing 1's call(tokens, k, max_token_count,
+    w1, w2)).  Buffers and call order only; dropless; the gather of dispatch is fused into the expert MLP's loads."""
+
+    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, act: str = "gelu", device="cuda"):
+        self.T, self.d, self.E, self.k, self.f, self.act = T, d, E, k, f, act
+        B = T * k
+        self.B = B
+        dt = api.dtype_code(dtype)
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        tt = dict(dtype=dtype, device=device)
+        self.logits = torch.empty((T, E), **f32)
+        self.topk_idx = torch.empty((T, k), **i32)
+        self.topk_w = torch.empty((T, k), **f32)
+        self.tokens_per_expert = torch.empty(E, **i32)
+        self.expert_offsets = torch.empty(E + 1, **i32)
+        self.token_ids = torch.empty(B, **i32)
+        self.expert_ids = torch.empty(B, **i32)
+        self.combine_weights = torch.empty(B, **f32)
+        self.row_of_slot = torch.empty(B, **i32)
+        self.h = torch.empty((B, f), **tt)
+        self.y = torch.empty((B, d), **tt)
+        self.out = torch.empty((T, d), **tt)
+        self.dy = torch.empty((B, d), **tt)
+        self.dw = torch.empty((T, k), **f32)
+        self.dxd = torch.empty((B, d), **tt)
+        self.dlogits = torch.empty((T, E), **f32)
+        self.dx_gate = torch.empty((T, d), **tt)
+        self.dx = torch.empty((T, d), **tt)
+        ws = max(api.xmoe_workspace_bytes(api.WS_BUILD_ERI, T, d, E, k, f, dt),
+                 api.xmoe_workspace_bytes(api.WS_MLP2_FWD, B, d, E, k, f, dt),
+                 api.xmoe_workspace_bytes(api.WS_MLP2_BWD, B, d, E, k, f, dt),
+                 api.xmoe_workspace_bytes(api.WS_GATE_BWD, T, d, E, k, f, dt))
+        self.ws = api.alloc_workspace(ws, device)
+
+    # weights: dict with w_router [d,E], bias [E]|None, w1 [E,d,f], w2 [E,f,d]
+    def forward(self, x: torch.Tensor, w: dict) -> torch.Tensor:
+        api.xmoe_gate_logits(x, w["w_router"], w.get("bias"), self.logits)
+        api.xmoe_route(self.logits, self.k, self.topk_idx, self.topk_w)
+        api.xmoe_build_eri(self.topk_idx, self.topk_w, self.E, self.tokens_per_expert, self.expert_offsets,
+                           self.token_ids, self.expert_ids, self.combine_weights, self.row_of_slot, self.ws)
+        api.xmoe_expert_mlp2_fwd(x, self.expert_offsets, w["w1"], w["w2"], self.act, self.h, self.y, self.ws,
+                                 row_index=self.token_ids)
+        api.xmoe_combine(self.y, self.row_of_slot, self.topk_w, None, None, self.k, self.out)
+        return self.out
+
+    def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
+        """grads: preallocated dw_router, dw1, dw2 in the layouts of the weights."""
+        api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, self.dy, self.dw)
+        api.xmoe_expert_mlp2_bwd(x, self.h, self.dy, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,
+                                 grads["dw1"], grads["dw2"], self.ws, row_index=self.token_ids)
+        api.xmoe_route_bwd(self.logits, self.topk_idx, self.dw, self.dlogits)
+        api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
+        api.xmoe_dispatch_bwd(self.dxd, self.row_of_slot, None, self.dx_gate, self.k, self.dx)
+        return self.dx

@@ -1,0 +1,157 @@
+"""GPU parity of the paper's two-matrix expert (xmoe_expert_mlp2_fwd / _bwd and the layer built on them) against
+the CPU oracle on the same seeded inputs, through the C ABI.  Integer outputs bit for bit; floating point within
+the benchmark definition's tolerance (1e-5 float32, 2e-2 bf16), as in test_gpu_parity.py."""
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import xmoe_inputs as xi
+from gpu_util import assert_close, assert_close_chain, rel_err, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+SMALL2 = ["mini_mlp2_f32", "odd_mlp2_bf16", "mini_mlp2_bf16", "mini_mlp2_skew", "mid_mlp2_bf16"]
+
+
+def xm():
+    import paper_2508_13337_amd as m
+    return m
+
+
+@functools.lru_cache(maxsize=8)
+def oracle_run(name: str):
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe2_layer_fwd(inp, cfg.k, cfg.act)
+    bwd = oracle.moe2_layer_bwd(inp, fwd, cfg.k, cfg.act)
+    return cfg, inp, fwd, bwd
+
+
+def i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("act", ["identity", "gelu", "silu"])
+@pytest.mark.parametrize("name", ["mini_mlp2_f32", "mini_mlp2_bf16", "odd_mlp2_bf16"])
+def test_expert_mlp2_fwd_bwd(name, act):
+    """The two entry points alone, every activation, with and without the fused gather."""
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe2_layer_fwd(inp, cfg.k, act)
+    bwd = oracle.moe2_layer_bwd(inp, fwd, cfg.k, act)
+    m = xm()
+    dt = cfg.dtype
+    tdt = torch_dtype(dt)
+    code = m.dtype_code(tdt)
+    eri = fwd["eri"]
+    B, d, f, E = cfg.B, cfg.d, cfg.f, cfg.E
+    xd = to_dev(fwd["Xd"], dt)
+    off = i32(eri["expert_offsets"])
+    w1, w2 = to_dev(inp["w1"], dt), to_dev(inp["w2"], dt)
+    h = torch.empty((B, f), dtype=tdt, device="cuda")
+    y = torch.empty((B, d), dtype=tdt, device="cuda")
+    ws = m.alloc_workspace(max(m.xmoe_workspace_bytes(m.WS_MLP2_FWD, B, d, E, cfg.k, f, code),
+                               m.xmoe_workspace_bytes(m.WS_MLP2_BWD, B, d, E, cfg.k, f, code)))
+    m.xmoe_expert_mlp2_fwd(xd, off, w1, w2, act, h, y, ws)
+    assert_close(to_host(h), fwd["H"], dt, "H", floor="row")
+    assert_close(to_host(y), fwd["Y"], dt, "Y", floor="row")
+
+    # backward from the oracle's saved H and dY (rounded to storage)
+    H = xi.round_to_storage(fwd["H"].astype(np.float32), dt)
+    dY = xi.round_to_storage(bwd["dY"].astype(np.float32), dt)
+    ref = oracle.expert_mlp2_bwd(fwd["Xd"], H.astype(np.float64), dY.astype(np.float64), eri["expert_offsets"],
+                                 inp["w1"], inp["w2"], act)
+    dxd = torch.empty((B, d), dtype=tdt, device="cuda")
+    dw1 = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
+    dw2 = torch.full((E, f, d), 3.0, dtype=tdt, device="cuda")
+    m.xmoe_expert_mlp2_bwd(xd, to_dev(H, dt), to_dev(dY, dt), off, w1, w2, act, dxd, dw1, dw2, ws)
+    for got, want, what in zip((dxd, dw1, dw2), ref, ("dXd", "dW1", "dW2")):
+        assert_close(to_host(got), want, dt, what, floor="row" if what == "dXd" else "expert")
+    tpe = eri["tokens_per_expert"]
+    for e in range(E):
+        if tpe[e] == 0:
+            assert not dw1[e].any() and not dw2[e].any()
+
+    # gather fused into the operand loads: the same calls on x itself through token_ids, bit-identical results
+    x, tok = to_dev(inp["x"], dt), i32(eri["token_ids"])
+    h2, y2 = torch.empty_like(h), torch.empty_like(y)
+    m.xmoe_expert_mlp2_fwd(x, off, w1, w2, act, h2, y2, ws, row_index=tok)
+    assert torch.equal(h2, h) and torch.equal(y2, y)
+    dxd2, dw12, dw22 = torch.empty_like(dxd), torch.full_like(dw1, 5.0), torch.full_like(dw2, 5.0)
+    m.xmoe_expert_mlp2_bwd(x, to_dev(H, dt), to_dev(dY, dt), off, w1, w2, act, dxd2, dw12, dw22, ws, row_index=tok)
+    assert torch.equal(dxd2, dxd) and torch.equal(dw12, dw1) and torch.equal(dw22, dw2)
+
+
+def run_layer2(cfg, inp):
+    m = xm()
+    dt = cfg.dtype
+    layer = m.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), act=cfg.act)
+    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"]),
+         "w1": to_dev(inp["w1"], dt), "w2": to_dev(inp["w2"], dt)}
+    grads = {"dw_router": torch.empty_like(w["w_router"]), "dw1": torch.empty_like(w["w1"]),
+             "dw2": torch.empty_like(w["w2"])}
+    x, dout = to_dev(inp["x"], dt), to_dev(inp["dout"], dt)
+    out = layer.forward(x, w)
+    dx = layer.backward(x, w, dout, grads)
+    torch.cuda.synchronize()
+    return layer, out, dx, grads
+
+
+def check_layer2(cfg, fwd, bwd, layer, out, dx, grads):
+    dt = cfg.dtype
+    eri = fwd["eri"]
+    assert np.array_equal(layer.logits.cpu().numpy().view(np.uint32), fwd["logits"].view(np.uint32))
+    assert np.array_equal(layer.topk_idx.cpu().numpy(), fwd["topk_idx"])
+    for key in ("tokens_per_expert", "expert_offsets", "token_ids", "expert_ids", "row_of_slot"):
+        assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
+    assert rel_err(to_host(layer.topk_w), fwd["topk_w"]) <= 1e-5
+    errs = {"out": assert_close_chain(to_host(out), fwd["out"], dt, "out"),
+            "Y": assert_close_chain(to_host(layer.y), fwd["Y"], dt, "Y"),
+            "dx": assert_close_chain(to_host(dx), bwd["dx"], dt, "dx"),
+            "dw_router": assert_close_chain(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router",
+                                            floor="tensor", norm="tensor")}
+    for k_ in ("dw1", "dw2"):
+        errs[k_] = assert_close_chain(to_host(grads[k_]), bwd[k_], dt, k_, floor="row")
+    return errs
+
+
+@pytest.mark.parametrize("name", SMALL2)
+def test_layer2_fwd_bwd(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    layer, out, dx, grads = run_layer2(cfg, inp)
+    errs = check_layer2(cfg, fwd, bwd, layer, out, dx, grads)
+    print(name, {k_: f"{v[0]:.2e}/{v[1]:.2e}" for k_, v in errs.items()})
+
+
+def test_layer2_is_reproducible_run_to_run():
+    cfg, inp, _, _ = oracle_run("mini_mlp2_skew")
+    _, out1, dx1, g1 = run_layer2(cfg, inp)
+    out1, dx1 = out1.clone(), dx1.clone()
+    g1 = {k_: v.clone() for k_, v in g1.items()}
+    _, out2, dx2, g2 = run_layer2(cfg, inp)
+    assert torch.equal(out1, out2) and torch.equal(dx1, dx2)
+    for k_ in g1:
+        assert torch.equal(g1[k_], g2[k_]), k_
+
+
+def test_mlp2_rejects_bad_arguments():
+    m = xm()
+    t = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    off = i32(np.array([0, 4]))
+    w1 = torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda")
+    ws = m.alloc_workspace(1 << 16)
+    from paper_2508_13337_amd import _lib
+    rc = _lib.lib().xmoe_expert_mlp2_fwd(t.data_ptr(), None, off.data_ptr(), 4, 1, 64, 64, w1.data_ptr(), w1.data_ptr(),
+                                         7, t.data_ptr(), t.data_ptr(), 1, ws.data_ptr(), ws.numel(), None)
+    assert rc == 2      # unknown activation: XMOE_ERR_UNSUPPORTED, nothing enqueued
+    rc = _lib.lib().xmoe_expert_mlp2_fwd(t.data_ptr(), None, off.data_ptr(), 4, 1, 64, 64, w1.data_ptr(), w1.data_ptr(),
+                                         1, t.data_ptr(), t.data_ptr(), 1, ws.data_ptr(), 16, None)
+    assert rc == 3      # workspace too small
+    torch.cuda.synchronize()
