@@ -55,6 +55,21 @@ def kernel_work(cfg):
     T, d, E, k, f, B = cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.B
     Ts = cfg.E_s * T
     rf = (B + Ts) * f
+    if cfg.expert == "mlp2":
+        # the paper's two-matrix expert: four row GEMMs of 2*R*d*f flops and two weight gradients
+        R, W = B, E * d * f * s
+        flops = {"up": 2 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 2 * d * rf, "wgrad": 4 * d * rf}
+        bytes_ = {
+            "combine_kernel": (B + T) * d * s + (B + 2 * T) * d * s,
+            "combine_bwd_kernel": (T + 2 * B) * d * s,
+            "route_kernel": T * E * 4 + T * k * 8,
+            "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
+        }
+        gemm_bytes = {"up": R * d * s + W + 2 * R * f * s, "down": R * f * s + W + R * d * s,
+                      "dact": R * d * s + W + 3 * R * f * s, "dx": R * f * s + W + R * d * s,
+                      "wgrad": 2 * (R * f * s + R * d * s + W)}
+        bytes_.update({"gemm:" + k_: v for k_, v in gemm_bytes.items()})
+        return flops, bytes_
     flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf,
              "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf}
     bytes_ = {
@@ -85,6 +100,13 @@ GEMM_WORK = {
 for _fam in ("mfma", "simt"):
     for _k in ("gateup", "down", "dact", "dx", "wgrad"):
         GEMM_WORK[f"ffn_{_k}_{_fam}_kernel"] = _k
+# the two-matrix expert shares the down, dX and weight-gradient kernels (two launches of the latter per step)
+GEMM_WORK_MLP2 = {
+    "mlp2_up_dma_kernel": "up", "ffn_rowgemm_dma_kernel<false>": "down", "mlp2_dact_dma_kernel": "dact",
+    "ffn_dx_dma_kernel": "dx", "ffn_wgrad_dma_kernel<false>": "wgrad",
+    "mlp2_up_simt_kernel": "up", "ffn_down_simt_kernel": "down", "mlp2_dact_simt_kernel": "dact",
+    "ffn_dx_simt_kernel": "dx", "ffn_wgrad_simt_kernel": "wgrad",
+}
 
 # HBM bytes per launch of the dominant kernel read from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
@@ -126,20 +148,27 @@ def main():
     x_np, dout_np = xi.make_x(cfg), xi.make_dout(cfg)
     wr_np, bias_np = xi.make_w_router(cfg), xi.make_gate_bias(cfg)
     w = {"w_router": dev(wr_np), "bias": None if bias_np is None else torch.from_numpy(bias_np).cuda()}
-    for key in ("wg", "wu", "wd"):
+    mlp2 = cfg.expert == "mlp2"
+    wkeys = ("w1", "w2") if mlp2 else ("wg", "wu", "wd")
+    for key in wkeys:
         # expert by expert, so that the large workloads never hold a second host copy of a whole tensor
         Ea = cfg.E + cfg.E_s   # the shared experts' weights follow the routed ones
-        shape = (Ea, cfg.d, cfg.f) if key != "wd" else (Ea, cfg.f, cfg.d)
+        shape = (Ea, cfg.d, cfg.f) if key not in ("wd", "w2") else (Ea, cfg.f, cfg.d)
         w[key] = torch.empty(shape, dtype=tdt, device="cuda")
         for e, a in xi.iter_expert_weights(cfg, key):
             w[key][e].copy_(dev(a))
         if cfg.E_s:
             w[key][cfg.E:].copy_(dev(xi.make_shared_weights(cfg, key)))
     grads = {"dw_router": torch.empty_like(w["w_router"])}
-    for key in ("wg", "wu", "wd"):
+    for key in wkeys:
         grads["d" + key] = torch.empty_like(w[key])
     x, dout = dev(x_np), dev(dout_np)
-    layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s, max_token_count=args.max_token_count)
+    if mlp2:
+        assert cfg.E_s == 0 and args.max_token_count is None
+        layer = xm.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, act=cfg.act)
+    else:
+        layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s,
+                             max_token_count=args.max_token_count)
     t_gen = time.time() - t_gen
 
     def step():
@@ -184,24 +213,24 @@ def main():
     xm.xmoe_prof_reset()
 
     flops, bytes_ = kernel_work(cfg)
+    gemm_work = GEMM_WORK_MLP2 if mlp2 else GEMM_WORK
     kernels = {}
     for name, (launches, total_ms) in prof.items():
         per_step_ms = total_ms / args.steps
         ent = {"launches_per_step": launches / args.steps, "ms_per_step": round(per_step_ms, 5),
                "avg_launch_us": round(total_ms * 1e3 / launches, 3)}
-        if name in GEMM_WORK:
-            ent["tflops"] = round(flops[GEMM_WORK[name]] / (per_step_ms * 1e-3) / 1e12, 3)
+        if name in gemm_work:
+            ent["tflops"] = round(flops[gemm_work[name]] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
-        if name in GEMM_WORK:
-            ent["algorithmic_gbs"] = round(bytes_["gemm:" + GEMM_WORK[name]] / (per_step_ms * 1e-3) / 1e9, 1)
+            ent["algorithmic_gbs"] = round(bytes_["gemm:" + gemm_work[name]] / (per_step_ms * 1e-3) / 1e9, 1)
         if name in bytes_:
             ent["gbs"] = round(bytes_[name] / (per_step_ms * 1e-3) / 1e9, 2)
             ent["frac_hbm_peak"] = round(ent["gbs"] / PEAK_HBM_GBS, 5)
         kernels[name] = ent
-    gemm_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith("ffn_"))
-    total_flops = sum(flops[k_] for k_ in ("gateup", "down", "dact", "dx", "wgrad"))
-    dom = max((n for n in kernels if n.startswith("ffn_")), key=lambda n: kernels[n]["ms_per_step"])
-    dom_key = GEMM_WORK[dom]
+    gemm_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n in gemm_work)
+    total_flops = sum(flops[k_] for k_ in (("up",) if mlp2 else ("gateup",)) + ("down", "dact", "dx", "wgrad"))
+    dom = max((n for n in kernels if n in gemm_work), key=lambda n: kernels[n]["avg_launch_us"])
+    dom_key = gemm_work[dom]
     # which roof binds the dominant kernel: the one that needs longer at its peak for the kernel's algorithmic work
     dom_flops = flops[dom_key] / kernels[dom]["launches_per_step"]
     dom_bytes = bytes_["gemm:" + dom_key] / kernels[dom]["launches_per_step"]
@@ -228,14 +257,14 @@ def main():
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "T": cfg.T, "d": cfg.d, "E": cfg.E, "E_s": cfg.E_s, "k": cfg.k, "f": cfg.f,
+        "config": {"workload": cfg.name, "expert": cfg.expert if not mlp2 else f"mlp2/{cfg.act}", "T": cfg.T, "d": cfg.d, "E": cfg.E, "E_s": cfg.E_s, "k": cfg.k, "f": cfg.f,
                    "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "max_token_count": args.max_token_count, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
         "fwd_only_ms": round(fwd_ms, 4),
         "fwd_only_tokens_per_s": round(cfg.T / (fwd_ms * 1e-3), 1),
         # what stays allocated between forward and backward for the routed rows: Y, G, U (no dispatched copy Xd:
         # the gather is fused into the expert MLP's operand loads)
         "activation_bytes_held": sum(t_[:layer.B].numel() * t_.element_size()
-                                     for t_ in (layer.y, layer.g, layer.u)),
+                                     for t_ in ((layer.y, layer.h) if mlp2 else (layer.y, layer.g, layer.u))),
         "layer_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "grouped_gemm_pct_mfma_peak": round(100 * roofline["all_gemm_frac"], 3),
         "roofline": roofline,
@@ -256,6 +285,16 @@ def cpu_baseline(cfg, sample_tokens, x_np, dout_np, wr_np, bias_np):
     import oracle
     import xmoe_inputs as xi
     Ts = min(sample_tokens, cfg.T)
+    if cfg.expert == "mlp2":
+        inp = {"x": x_np[:Ts], "dout": dout_np[:Ts], "w_router": wr_np, "bias": bias_np,
+               "w1": xi.make_expert_weights(cfg, "w1"), "w2": xi.make_expert_weights(cfg, "w2")}
+        t0 = time.perf_counter()
+        fwd = oracle.moe2_layer_fwd(inp, cfg.k, cfg.act)
+        oracle.moe2_layer_bwd(inp, fwd, cfg.k, cfg.act)
+        dt = time.perf_counter() - t0
+        return {"value": round(Ts / dt, 2), "unit": "tokens/s", "cores": int(os.cpu_count()), "kind": "oracle",
+                "sample": f"first {Ts} of {cfg.T} tokens of workload {cfg.name}, all expert weights, fwd+bwd, "
+                          f"float64 numpy, {dt:.1f} s"}
     inp = {"x": x_np[:Ts], "dout": dout_np[:Ts], "w_router": wr_np, "bias": bias_np,
            "wg": xi.make_expert_weights(cfg, "wg"), "wu": xi.make_expert_weights(cfg, "wu"),
            "wd": xi.make_expert_weights(cfg, "wd"),

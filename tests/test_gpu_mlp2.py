@@ -155,3 +155,21 @@ def test_mlp2_rejects_bad_arguments():
                                          1, t.data_ptr(), t.data_ptr(), 1, ws.data_ptr(), 16, None)
     assert rc == 3      # workspace too small
     torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["small_mlp2", "small_ep8_mlp2"])
+def test_full_size_whole_oracle_mlp2(name):
+    """Table 3's Small model at one GPU's share of tokens, and the share of one rank under expert parallelism of
+    degree 8 (8 local experts, segments 8 times as long), in the launch configuration bench.py times, against the
+    whole oracle."""
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe2_layer_fwd(inp, cfg.k, cfg.act)
+    bwd = oracle.moe2_layer_bwd(inp, fwd, cfg.k, cfg.act)
+    layer, out, dx, grads = run_layer2(cfg, inp)
+    errs = check_layer2(cfg, fwd, bwd, layer, out, dx, grads)
+    print(name, {k_: f"{v[0]:.2e}/{v[1]:.2e}" for k_, v in errs.items()})
+    # held for backward: Y and H (the dispatched copy does not exist, the gather is fused into the loads)
+    held = sum(t_.numel() * t_.element_size() for t_ in (layer.y, layer.h))
+    assert held == 2 * cfg.T * cfg.k * (cfg.d + cfg.f)
