@@ -30,6 +30,13 @@ Readings of the paper that this oracle fixes (the paper is silent or garbled on 
     prints no activation between the two GeMMs while Section 3.1 speaks of two intermediate activations between
     the FFN sub-layers; act is therefore a parameter: "identity" (the listing as printed), "gelu" (x Phi(x), the
     exact erf form: the default of the Megatron-style MLP that the paper's framework trains) or "silu".
+  * Redundancy-Bypassing Dispatch, stage 0 (Section 4.2): experts are laid out over nodes in contiguous blocks
+    (node of expert e = e // experts_per_node); all tokens of this PFT share one source, so a group is the set of a
+    token's flat entries whose experts live on one destination node; the random choice of the group's pilot is
+    the entry with the smallest (rand_key[n], n), the keys being an input; pilot and replica ERI-arrays keep the
+    PFT's order (sorted by expert, stable); a replica's s1_mapping_indices entry is its pilot's position inside
+    the pilot segment of the pilot's expert ("relative index starting from 0 for each target expert"), and the
+    pilot's expert is recorded beside it so that the index can be made absolute against any offsets table.
 """
 from __future__ import annotations
 
@@ -370,6 +377,79 @@ def moe2_layer_bwd(inp: dict, fwd: dict, k: int, act: str) -> dict:
 def expert_param_count(E: int, d: int, f: int, matrices: int = 2) -> int:
     """Parameters of one MoE layer's experts: `matrices` matrices of d*f per expert (Table 1: 2 h' h per expert)."""
     return E * matrices * d * f
+
+
+# ----------------------------------------------------------------------------------------------------------
+# Redundancy-Bypassing Dispatch, stage 0: pilot selection and the two sets of ERI-arrays (Section 4.2)
+# ----------------------------------------------------------------------------------------------------------
+def rbd_stage0(topk_idx: np.ndarray, rand_key: np.ndarray, eri: dict, E: int, experts_per_node: int) -> dict:
+    """Splits the rows of a PFT into pilot tokens (one per token and destination node, chosen at random) and local
+    replicas (the token's other rows bound for the same node), with ERI-arrays for both and the mapping from every
+    replica to its pilot.
+
+    topk_idx [T,k]; rand_key [T*k] unsigned (one draw per flat entry n = t*k + j); eri: the dropless ERI-arrays."""
+    T, k = topk_idx.shape
+    B = T * k
+    tok, exp_ids, ros = eri["token_ids"], eri["expert_ids"], eri["row_of_slot"]
+    node_of = lambda e: int(e) // experts_per_node
+    is_pilot = np.zeros(B, dtype=bool)            # per PFT row
+    pilot_row_of = np.full(B, -1, dtype=np.int64)  # per PFT row: the PFT row of its group's pilot
+    for t in range(T):
+        groups = {}
+        for j in range(k):
+            groups.setdefault(node_of(topk_idx[t, j]), []).append(t * k + j)
+        for members in groups.values():
+            pilot = min(members, key=lambda n: (int(rand_key[n]), n))
+            for n in members:
+                pilot_row_of[ros[n]] = ros[pilot]
+            is_pilot[ros[pilot]] = True
+    pilot_rows = np.flatnonzero(is_pilot)          # PFT order: sorted by expert, ascending token inside an expert
+    replica_rows = np.flatnonzero(~is_pilot)
+    rank_in_class = np.empty(B, dtype=np.int64)
+    rank_in_class[pilot_rows] = np.arange(pilot_rows.size)
+    rank_in_class[replica_rows] = np.arange(replica_rows.size)
+
+    def sub_eri(rows):
+        tpe = np.bincount(exp_ids[rows], minlength=E).astype(np.int32)
+        off = np.zeros(E + 1, dtype=np.int32)
+        off[1:] = np.cumsum(tpe)
+        return {"token_ids": tok[rows].astype(np.int32), "expert_ids": exp_ids[rows].astype(np.int32),
+                "tokens_per_expert": tpe, "expert_offsets": off}
+
+    pilot, replica = sub_eri(pilot_rows), sub_eri(replica_rows)
+    # a replica records where its pilot sits inside the pilot segment of the pilot's expert
+    s1_experts = exp_ids[pilot_row_of[replica_rows]].astype(np.int32)
+    s1_indices = (rank_in_class[pilot_row_of[replica_rows]] - pilot["expert_offsets"][s1_experts]).astype(np.int32)
+    merge_src = np.where(is_pilot, rank_in_class, pilot_rows.size + rank_in_class).astype(np.int32)
+    return {"is_pilot": is_pilot, "pilot": pilot, "replica": replica, "s1_mapping_indices": s1_indices,
+            "s1_mapping_experts": s1_experts, "merge_src": merge_src}
+
+
+def rbd_absolute_index(s1_mapping_indices, s1_mapping_experts, pilot_offsets_at_destination):
+    """Re-encodes the relative pilot indices to absolute rows of a pilot buffer whose expert segments start at the
+    given offsets (after the uneven exchange these are the receiver's offsets; on one device, the sender's)."""
+    return (np.asarray(pilot_offsets_at_destination)[s1_mapping_experts] + s1_mapping_indices).astype(np.int32)
+
+
+def rbd_reconstruct(x, stage0: dict):
+    """Stages 0-2 on one device (both exchanges are the identity): instantiate the pilot buffer with the gather
+    kernel, rebuild the replicas from their pilots, merge the two groups into the experts' input order."""
+    pilot_buf = dispatch(x, stage0["pilot"]["token_ids"])
+    absolute = rbd_absolute_index(stage0["s1_mapping_indices"], stage0["s1_mapping_experts"],
+                                  stage0["pilot"]["expert_offsets"])
+    replica_buf = pilot_buf[absolute]
+    both = np.concatenate([pilot_buf, replica_buf], axis=0)
+    return both[stage0["merge_src"]]
+
+
+def rbd_expected_redundancy(E: int, k: int, experts_per_node: int) -> float:
+    """Expected share of replicas among the k rows of a token that picks k distinct experts uniformly at random:
+    1 - E[number of distinct destination nodes] / k, with P(node untouched) = C(E - m, k) / C(E, k)."""
+    from math import comb
+    m = experts_per_node
+    n_nodes = E // m
+    distinct = n_nodes * (1.0 - comb(E - m, k) / comb(E, k))
+    return 1.0 - distinct / k
 
 
 # ----------------------------------------------------------------------------------------------------------

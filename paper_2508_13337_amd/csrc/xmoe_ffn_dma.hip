@@ -29,7 +29,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 constexpr int TM = 256, TN = 256, TK = 32;
-constexpr int kStages = 4;
+#ifndef XMOE_DMA_STAGES
+#define XMOE_DMA_STAGES 4
+#endif
+constexpr int kStages = XMOE_DMA_STAGES;
 constexpr int kOpBytes = 256 * TK * 2;          // one operand tile of one stage: 16 KiB
 constexpr int kStageBytes = 2 * kOpBytes;       // A + B
 constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
@@ -1055,7 +1058,10 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             int32_t* __restrict__ counters, int E, int M, int N,
                                                             bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     extern __shared__ __align__(16) char smem[];
-    __shared__ int s_next[2];
+    // hand-over slot for the next tile's number, inside the ring's last stage: a tile's prologue fills stages
+    // 0 .. kStages-2 only, and the last stage is first refilled behind the main loop's first barrier, which no wave
+    // passes before it has read the slot; it is written after the main loop's final wait, when no load is in flight
+    int* s_next = reinterpret_cast<int*>(smem + (kStages - 1) * kStageBytes);
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
     TileQueue q;

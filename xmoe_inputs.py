@@ -23,7 +23,7 @@ import numpy as np
 # tensor ids: fixed, part of the recipe
 _TENSOR_IDS = {
     "x": 1, "w_router": 2, "wg": 3, "wu": 4, "wd": 5, "dout": 6,
-    "shared_wg": 7, "shared_wu": 8, "shared_wd": 9, "rank_perm": 10, "logits": 11, "w1": 12, "w2": 13,
+    "shared_wg": 7, "shared_wu": 8, "shared_wd": 9, "rank_perm": 10, "logits": 11, "w1": 12, "w2": 13, "rbd_key": 14,
 }
 
 
@@ -204,6 +204,12 @@ def make_logits(T: int, E: int, seed: int = 0, std: float = 1.0) -> np.ndarray:
     """Free-standing gate logits [T, E] float32 ~ N(0, std) for tests of routing in isolation."""
     g = _rng(seed, "logits")
     return g.standard_normal(size=(T, E), dtype=np.float32) * np.float32(std)
+
+
+def make_rbd_keys(n: int, seed: int = 0) -> np.ndarray:
+    """The random draws of the redundancy-bypassing dispatch's pilot selection: one uint32 per flat (token, slot)
+    entry."""
+    return _rng(seed, "rbd_key").integers(0, 2 ** 32, size=n, dtype=np.uint32)
 
 
 def make_layer_inputs(cfg: MoEConfig) -> dict:
