@@ -55,7 +55,8 @@ typedef enum {
     XMOE_WS_GATE_BWD = 3,       /* rows = T            */
     XMOE_WS_BUILD_ERI_CAPPED = 4, /* rows = T          */
     XMOE_WS_MLP2_FWD = 5,       /* rows = B            */
-    XMOE_WS_MLP2_BWD = 6        /* rows = B            */
+    XMOE_WS_MLP2_BWD = 6,       /* rows = B            */
+    XMOE_WS_RBD_STAGE0 = 7      /* rows = T            */
 } xmoe_ws_op;
 
 /* activation of the two-matrix expert (xmoe_expert_mlp2_fwd / _bwd) */
@@ -127,6 +128,39 @@ int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, i
                           int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
                           int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
                           void* ws, size_t ws_bytes, void* stream);
+
+/* Redundancy-Bypassing Dispatch, stage 0 (Section 4.2 "Pilot Selection and Instantiation"), the metadata part.
+ * Experts live on nodes in contiguous blocks: node(e) = e / experts_per_node.  A group is the set of one token's
+ * flat entries n = t*k + j whose experts share a destination node (all tokens of a PFT share the source).  The
+ * group's pilot is the entry with the smallest (rand_key[n], n) - rand_key [T*k] uint32 carries the random draws
+ * the section asks for, made by the caller; every other entry of the group is a local replica.  Both groups get
+ * ERI-arrays of their own that keep the PFT's order (sorted by expert, ascending token inside an expert):
+ *   pilot_token_ids, pilot_expert_ids [T*k]     first n_pilot entries valid, then token -1 / expert E
+ *   pilot_tokens_per_expert [E], pilot_offsets [E+1]       (pilot_offsets[E] = n_pilot, on the device only)
+ *   replica_token_ids, replica_expert_ids [T*k], replica_tokens_per_expert [E], replica_offsets [E+1]   likewise
+ *   s1_mapping_indices [T*k]   for replica r: position of its pilot inside the pilot segment of the pilot's expert
+ *                              (the section's relative index, valid before and after the uneven exchange)
+ *   s1_mapping_experts [T*k]   for replica r: the pilot's expert (E behind the last replica)
+ *   merge_src [T*k]            for PFT row i: its row in the concatenation [pilot buffer ; replica buffer]
+ * Inputs: topk_idx [T,k]; token_ids, expert_ids [T*k], expert_offsets [E+1], row_of_slot [T*k] of the dropless PFT
+ * (xmoe_build_eri).  The pilot token buffer itself is xmoe_dispatch(x, pilot_token_ids); the replicas are rebuilt at
+ * the destination as xmoe_dispatch(pilot buffer, absolute index), and the experts' input order as
+ * xmoe_dispatch([pilot buffer ; replica buffer], merge_src).  ws: XMOE_WS_RBD_STAGE0 bytes.
+ */
+int xmoe_rbd_stage0(const int32_t* topk_idx, const uint32_t* rand_key, const int32_t* token_ids,
+                    const int32_t* expert_ids, const int32_t* expert_offsets, const int32_t* row_of_slot, int T, int E,
+                    int k, int experts_per_node, int32_t* pilot_token_ids, int32_t* pilot_expert_ids,
+                    int32_t* pilot_tokens_per_expert, int32_t* pilot_offsets, int32_t* replica_token_ids,
+                    int32_t* replica_expert_ids, int32_t* replica_tokens_per_expert, int32_t* replica_offsets,
+                    int32_t* s1_mapping_indices, int32_t* s1_mapping_experts, int32_t* merge_src, void* ws,
+                    size_t ws_bytes, void* stream);
+
+/* Section 4.2: the relative pilot indices are re-encoded to absolute rows after the exchange:
+ *   absolute[r] = pilot_offsets_at_destination[s1_mapping_experts[r]] + s1_mapping_indices[r]   (-1 for a sentinel)
+ * n entries; pilot_offsets_at_destination [E+1] (on one device: pilot_offsets itself). */
+int xmoe_rbd_absolute_index(const int32_t* s1_mapping_indices, const int32_t* s1_mapping_experts,
+                            const int32_t* pilot_offsets_at_destination, int n, int E, int32_t* absolute,
+                            void* stream);
 
 /* Dispatch (Section 4.1.2 / Appendix B.4 gather kernel): xd[i,:] = x[token_ids[i],:], a bit copy.
  * x [T,d] dt; token_ids [B] int32 with values in [0,T); xd [B,d] dt (out).

@@ -30,6 +30,8 @@ SIGNATURES = {
                              [_c_int, _c_void_p, _c_size_t, _c_void_p]),
     "xmoe_expert_mlp2_bwd": (_c_int, [_c_void_p] * 5 + [_c_int] * 4 + [_c_void_p] * 2 + [_c_int] + [_c_void_p] * 3 +
                              [_c_int, _c_void_p, _c_size_t, _c_void_p]),
+    "xmoe_rbd_stage0": (_c_int, [_c_void_p] * 6 + [_c_int] * 4 + [_c_void_p] * 12 + [_c_size_t, _c_void_p]),
+    "xmoe_rbd_absolute_index": (_c_int, [_c_void_p] * 3 + [_c_int] * 2 + [_c_void_p] * 2),
     "xmoe_combine": (_c_int, [_c_void_p] * 4 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_combine_bwd": (_c_int, [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p] * 3),
     "xmoe_dispatch_bwd": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),

@@ -15,6 +15,7 @@ from ._lib import lib
 
 XMOE_F32, XMOE_BF16 = 0, 1
 WS_BUILD_ERI, WS_FFN_FWD, WS_FFN_BWD, WS_GATE_BWD, WS_BUILD_ERI_CAPPED, WS_MLP2_FWD, WS_MLP2_BWD = 0, 1, 2, 3, 4, 5, 6
+WS_RBD_STAGE0 = 7
 ACT_CODES = {"identity": 0, "gelu": 1, "silu": 2}   # xmoe_act
 
 __all__ = [
@@ -24,6 +25,7 @@ __all__ = [
     "xmoe_prof_read", "xmoe_prof_copy", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
     "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
+    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0",
 ]
 
 
@@ -117,6 +119,46 @@ def xmoe_build_eri_capped(topk_idx, topk_w, E: int, max_token_count: int, tokens
         _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
         _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_build_eri_capped")
+
+
+def xmoe_rbd_stage0(topk_idx, rand_key, token_ids, expert_ids, expert_offsets, row_of_slot, experts_per_node: int,
+                    out: dict, ws) -> None:
+    """Stage 0 of the redundancy-bypassing dispatch.  rand_key: int32 tensor holding the uint32 draws' bit patterns.
+    out: preallocated int32 tensors pilot_token_ids, pilot_expert_ids, replica_token_ids, replica_expert_ids,
+    s1_mapping_indices, s1_mapping_experts, merge_src [T*k]; pilot_tokens_per_expert, replica_tokens_per_expert [E];
+    pilot_offsets, replica_offsets [E+1]."""
+    T, k = topk_idx.shape
+    B = T * k
+    E = expert_offsets.numel() - 1
+    for name in ("pilot_token_ids", "pilot_expert_ids", "replica_token_ids", "replica_expert_ids",
+                 "s1_mapping_indices", "s1_mapping_experts", "merge_src"):
+        assert out[name].numel() == B, name
+    for name in ("pilot_tokens_per_expert", "replica_tokens_per_expert"):
+        assert out[name].numel() == E, name
+    for name in ("pilot_offsets", "replica_offsets"):
+        assert out[name].numel() == E + 1, name
+    assert rand_key.numel() == B and token_ids.numel() == B and expert_ids.numel() == B and row_of_slot.numel() == B
+    i32 = torch.int32
+    _check(lib().xmoe_rbd_stage0(
+        _ptr(topk_idx, i32, "topk_idx"), _ptr(rand_key, i32, "rand_key"), _ptr(token_ids, i32, "token_ids"),
+        _ptr(expert_ids, i32, "expert_ids"), _ptr(expert_offsets, i32, "expert_offsets"),
+        _ptr(row_of_slot, i32, "row_of_slot"), T, E, k, int(experts_per_node),
+        _ptr(out["pilot_token_ids"], i32), _ptr(out["pilot_expert_ids"], i32),
+        _ptr(out["pilot_tokens_per_expert"], i32), _ptr(out["pilot_offsets"], i32),
+        _ptr(out["replica_token_ids"], i32), _ptr(out["replica_expert_ids"], i32),
+        _ptr(out["replica_tokens_per_expert"], i32), _ptr(out["replica_offsets"], i32),
+        _ptr(out["s1_mapping_indices"], i32), _ptr(out["s1_mapping_experts"], i32), _ptr(out["merge_src"], i32),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_rbd_stage0")
+
+
+def xmoe_rbd_absolute_index(s1_mapping_indices, s1_mapping_experts, pilot_offsets_at_destination, absolute) -> None:
+    n = s1_mapping_indices.numel()
+    E = pilot_offsets_at_destination.numel() - 1
+    assert s1_mapping_experts.numel() == n and absolute.numel() == n
+    i32 = torch.int32
+    _check(lib().xmoe_rbd_absolute_index(_ptr(s1_mapping_indices, i32), _ptr(s1_mapping_experts, i32),
+                                         _ptr(pilot_offsets_at_destination, i32), n, E, _ptr(absolute, i32),
+                                         _stream()), "xmoe_rbd_absolute_index")
 
 
 def xmoe_dispatch(x, token_ids, xd) -> None:

@@ -54,6 +54,12 @@ const char* const kKernelNames[K_COUNT] = {
     "mlp2_dact_simt_kernel",
     "mlp2_up_dma_kernel",
     "mlp2_dact_dma_kernel",
+    "rbd_mark_kernel",
+    "rbd_count_kernel",
+    "rbd_scan_kernel",
+    "rbd_scatter_kernel",
+    "rbd_map_kernel",
+    "rbd_absolute_kernel",
     "prof_copy_kernel",
 };
 
@@ -123,6 +129,7 @@ size_t xmoe_workspace_bytes(int op, int rows, int d, int E, int k, int f, int dt
         case XMOE_WS_BUILD_ERI_CAPPED: return eri_capped_ws_bytes(rows, E, k);
         case XMOE_WS_MLP2_FWD: return mlp2_fwd_ws_bytes(rows, E, d, f, dt);
         case XMOE_WS_MLP2_BWD: return mlp2_bwd_ws_bytes(rows, E, d, f, dt);
+        case XMOE_WS_RBD_STAGE0: return rbd_ws_bytes(rows, k);
         default: return 0;
     }
 }

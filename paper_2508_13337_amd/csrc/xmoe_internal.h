@@ -46,6 +46,12 @@ enum KernelId : int {
     K_MLP2_DACT_SIMT,
     K_MLP2_UP_DMA,
     K_MLP2_DACT_DMA,
+    K_RBD_MARK,
+    K_RBD_COUNT,
+    K_RBD_SCAN,
+    K_RBD_SCATTER,
+    K_RBD_MAP,
+    K_RBD_ABS,
     K_PROF_COPY,
     K_COUNT
 };

@@ -57,6 +57,14 @@ static inline size_t mlp2_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
     return ffn_tilemap_bytes(B, E) + 2 * ffn_act_bytes(B, f, dt);
 }
 
+// ----- stage 0 of the redundancy-bypassing dispatch: pilot flags, pilot row of every row, pilot prefix, chunk counts
+static inline int rbd_num_chunks(long long B) { return (int)((B + 1023) / 1024); }
+static inline size_t rbd_ws_bytes(int T, int k) {
+    const long long B = (long long)T * k;
+    return 2 * align_up((size_t)(B > 0 ? B : 1) * sizeof(int32_t), 256) + align_up((size_t)(B + 1) * sizeof(int32_t), 256) +
+           align_up((size_t)(rbd_num_chunks(B) + 1) * sizeof(int32_t), 256);
+}
+
 // ----- gate projection backward: split-K partial sums of dWr -----
 static inline int gate_bwd_splits(int T) {
     int s = (T + 255) / 256;
