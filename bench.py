@@ -112,12 +112,12 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3437606157,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1426612227,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2454799955,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2815407890,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1563306155,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3336312843,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3336651270,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1403548670,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2495059123,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2846550964,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1520962817,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3330454354,
 }
 
 
