@@ -118,6 +118,12 @@ MEASURED_TRAFFIC_BYTES = {
     ("dsmoe16b", "ffn_dx_dma_kernel"): 2846550964,
     ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1520962817,
     ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3330454354,
+    ("large", "ffn_gateup_dma_kernel"): 17603657002,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 9217436376,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9201767176,
+    ("large", "ffn_dx_dma_kernel"): 17052672014,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 11995620092,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 21020452025,
 }
 
 
