@@ -188,6 +188,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # what a plain copy kernel reaches on this GPU (read + written bytes per second): the practical ceiling that the
+    # HBM-bound kernels are to be read against, next to the published 8 TB/s that the roofline fractions use
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        xm.xmoe_prof_copy(src, dst)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        xm.xmoe_prof_copy(src, dst)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -274,6 +289,7 @@ def main():
         "layer_tflops": round(total_flops / (ms_per_step * 1e-3) / 1e12, 3),
         "grouped_gemm_pct_mfma_peak": round(100 * roofline["all_gemm_frac"], 3),
         "roofline": roofline,
+        "hbm_copy_kernel_gbs": round(copy_gbs, 1),
         "kernels": kernels,
         "input_gen_s": round(t_gen, 1),
     }
