@@ -494,26 +494,10 @@ __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t*
     }
 }
 
-// Workgroups are persistent: the launch has at most one workgroup per CU and each walks a list of tiles.  Each XCD
-// (workgroups are dealt to XCDs round-robin) owns a contiguous run [first, end) of the `total` logical tiles; its
-// nloc workgroups take first + local, first + local + nloc, ...  So at any moment an XCD's workgroups sit on
-// consecutive tiles that share operand panels through that XCD's L2, and a tile's result stores drain while the
-// workgroup already fills the ring for its next tile.
-struct TileRange {
-    int first, end, stride;
-};
-__device__ __forceinline__ TileRange tile_range(int total) {
-    const int chunk = (total + kNumXcd - 1) / kNumXcd;
-    const int xcd = blockIdx.x % kNumXcd, local = blockIdx.x / kNumXcd;
-    TileRange r;
-    r.stride = gridDim.x / kNumXcd;
-    r.first = xcd * chunk + local;
-    const int e = (xcd + 1) * chunk;
-    r.end = e < total ? e : total;
-    return r;
-}
-
-// Tiles of unequal length (the weight gradients: K = an expert's row count) are handed out at run time instead.
+// Tiles are handed out at run time.  Their cost is not uniform: the weight gradients' K is an expert's row count,
+// and a row tile at the ragged end of a segment costs about three quarters of a full one, so a fixed share of
+// tiles per workgroup leaves CUs idle at the end of a launch (and a tile count just above a multiple of the CU count
+// costs a whole extra round).
 // The tile list, longest experts first, is cut into groups of kQueueGroup consecutive tiles (neighbours share
 // operand panels); group g belongs to the list of XCD g % 8, and each list has a counter.  A workgroup draws from
 // its own XCD's list and, once that is empty, from the next XCD's, and so on round the ring; it stops after it
@@ -544,6 +528,47 @@ struct TileQueue {
             victim = (victim + 1) % kNumXcd;
             v = -1;
         }
+    }
+};
+
+// A workgroup's walk over the tiles of a launch.  Workgroups are persistent (at most one per CU); thread 0 draws the
+// next tile at the start of the current one (the atomic's latency passes during the main loop), resolves it after
+// the main loop and hands the number over through LDS; everybody reads it behind the barrier that ends the tile.
+// The two-slot hand-over buffer sits in the ring's last stage: a tile's prologue fills stages 0 .. kStages-2 only,
+// and the last stage is first refilled behind the main loop's first barrier, which no wave passes before it has read
+// the slot; it is written after the main loop's final wait, when no load is in flight.
+struct TileWalker {
+    TileQueue q;
+    int* slot;
+    int it, drawn;
+    // returns the first tile (or -1); counters: this launch's kNumXcd counters, zero at launch
+    __device__ __forceinline__ int start(int32_t* counters, int total, char* smem) {
+        q.cnt = counters;
+        q.total = total;
+        q.victim = blockIdx.x % kNumXcd;
+        q.hops = 0;
+        slot = reinterpret_cast<int*>(smem + (kStages - 1) * kStageBytes);
+        it = 0;
+        drawn = -1;
+        if (threadIdx.x == 0) slot[0] = q.pop(-1);
+        __syncthreads();
+        return __builtin_amdgcn_readfirstlane(slot[0]);
+    }
+    // at the start of a tile
+    __device__ __forceinline__ void draw() {
+        drawn = -1;
+        if (threadIdx.x == 0) drawn = atomicAdd(&q.cnt[q.victim], 1);
+    }
+    // after the tile's main loop (the slot written here was last read before the barrier that ended the previous tile)
+    __device__ __forceinline__ void hand_over() {
+        if (threadIdx.x == 0) slot[(it + 1) & 1] = q.pop(drawn);
+    }
+    // ends the tile (every wave has left its staging strip before the next tile's loads land in the ring) and
+    // returns the next one; the number is wave-uniform, so table look-ups that depend on it stay scalar loads
+    __device__ __forceinline__ int next() {
+        lds_done_and_barrier();
+        ++it;
+        return __builtin_amdgcn_readfirstlane(slot[it & 1]);
     }
 };
 
@@ -603,11 +628,13 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
                                                              const int32_t* __restrict__ map, int d, int f,
                                                              const bf16_t* __restrict__ wg,
                                                              const bf16_t* __restrict__ wu, bf16_t* __restrict__ G,
-                                                             bf16_t* __restrict__ U, bf16_t* __restrict__ A) {
+                                                             bf16_t* __restrict__ U, bf16_t* __restrict__ A,
+                                                             int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (f + 127) / 128;
-    const TileRange tr = tile_range(map[0] * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+    tw.draw();
     const RowTile rt = get_row_tile(map, off, t / nt);
     PROBE_BEGIN(0, t, rt.rows)
     const int n0 = (t % nt) * 128;
@@ -624,6 +651,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     zero_acc(acc);
     const int mi_count = wave_mi_count(rt.rows);
     mainloop<false, true, true, GATHER>(acc, a, b, d, mi_count, smem, PROBE_IDX);
+    tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, G)
 
@@ -653,8 +681,6 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
         strip_flush<32>(strip, 0, A + base, f, rows_valid, cols_valid);
         strip_sync();
     }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
         PROBE_MARK(PROBE_IDX, 3)
     }
 }
@@ -670,11 +696,13 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                                                               const bf16_t* __restrict__ W, bf16_t* __restrict__ Y,
                                                               const bf16_t* __restrict__ G,
                                                               const bf16_t* __restrict__ U, bf16_t* __restrict__ dG,
-                                                              bf16_t* __restrict__ dU, bf16_t* __restrict__ A) {
+                                                              bf16_t* __restrict__ dU, bf16_t* __restrict__ A,
+                                                              int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (N + TN - 1) / TN;
-    const TileRange tr = tile_range(map[0] * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+    tw.draw();
     const RowTile rt = get_row_tile(map, off, t / nt);
     PROBE_BEGIN(DACT ? 2 : 1, t, rt.rows)
     const int n0 = (t % nt) * TN;
@@ -693,6 +721,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
         Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
         mainloop<false, true, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
+    tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dG ? dG : Y)
     char* strip = smem + wave * kStripBytes;
@@ -794,8 +823,6 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             strip_sync();
         }
     }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
         PROBE_MARK(PROBE_IDX, 3)
     }
 }
@@ -809,11 +836,12 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
                                                          const int32_t* __restrict__ off,
                                                          const int32_t* __restrict__ map, int d, int f,
                                                          const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
-                                                         bf16_t* __restrict__ dXd) {
+                                                         bf16_t* __restrict__ dXd, int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (d + TN - 1) / TN;
-    const TileRange tr = tile_range(map[0] * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+    tw.draw();
     const RowTile rt = get_row_tile(map, off, t / nt);
     PROBE_BEGIN(3, t, rt.rows)
     const int n0 = (t % nt) * TN;
@@ -829,6 +857,7 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         Operand b2 = TWO ? row_op(wu + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols) : b1;
         mainloop2<false, false, false, TWO>(acc, a1, b1, f, a2, b2, TWO ? f : 0, mi_count, smem, PROBE_IDX);
     }
+    tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dXd)
     char* strip = smem + wave * kStripBytes;
@@ -848,8 +877,6 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         strip_flush<64>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
         strip_sync();
     }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
         PROBE_MARK(PROBE_IDX, 3)
     }
 }
@@ -904,11 +931,12 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
                                                           const int32_t* __restrict__ off,
                                                           const int32_t* __restrict__ map, int d, int f,
                                                           const bf16_t* __restrict__ w1, bf16_t* __restrict__ H,
-                                                          bf16_t* __restrict__ A) {
+                                                          bf16_t* __restrict__ A, int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (f + TN - 1) / TN;
-    const TileRange tr = tile_range(map[0] * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+        tw.draw();
         const RowTile rt = get_row_tile(map, off, t / nt);
         const int n0 = (t % nt) * TN;
         const int ncols = f - n0 < TN ? f - n0 : TN;
@@ -920,6 +948,7 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
         const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
         const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
         mainloop<false, true, false, GATHER>(acc, a, b, d, mi_count, smem);
+        tw.hand_over();
         char* strip = smem + wave * kStripBytes;
         const int cols_valid = ncols - wn * 64;
 #pragma unroll
@@ -949,8 +978,6 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
             strip_flush<64>(strip, 0, A + base, f, rows_valid, cols_valid);
             strip_sync();
         }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
     }
 }
 
@@ -964,11 +991,13 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                                                             const int32_t* __restrict__ map, int d, int f,
                                                             const bf16_t* __restrict__ w2,
                                                             const bf16_t* __restrict__ H, bf16_t* __restrict__ dH,
-                                                            bf16_t* __restrict__ A) {
+                                                            bf16_t* __restrict__ A,
+                                                            int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
     const int nt = (f + TN - 1) / TN;
-    const TileRange tr = tile_range(map[0] * nt);
-    for (int t = tr.first; t < tr.end; t += tr.stride) {
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+        tw.draw();
         const RowTile rt = get_row_tile(map, off, t / nt);
         const int n0 = (t % nt) * TN;
         const int ncols = f - n0 < TN ? f - n0 : TN;
@@ -980,6 +1009,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
         const int lane = threadIdx.x & 63;
         const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
         mainloop<false, false, false>(acc, a, b, d, mi_count, smem);
+        tw.hand_over();
         char* strip = smem + wave * kStripBytes;
         const int cols_valid = ncols - wn * 64;
         // 8 rounds (mi, ni) of 32 x 32 outputs.  H of a round is fetched as full 64-byte row pieces (4 lanes per
@@ -1042,8 +1072,6 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
             strip_flush<32>(strip, 32, A + o, f, rows_valid, cols_valid - ni * 32);
             strip_sync();
         }
-        // every wave has left its staging strip before the next tile's loads land in the ring
-        lds_done_and_barrier();
     }
 }
 
@@ -1062,26 +1090,11 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             int32_t* __restrict__ counters, int E, int M, int N,
                                                             bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     extern __shared__ __align__(16) char smem[];
-    // hand-over slot for the next tile's number, inside the ring's last stage: a tile's prologue fills stages
-    // 0 .. kStages-2 only, and the last stage is first refilled behind the main loop's first barrier, which no wave
-    // passes before it has read the slot; it is written after the main loop's final wait, when no load is in flight
-    int* s_next = reinterpret_cast<int*>(smem + (kStages - 1) * kStageBytes);
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
-    TileQueue q;
-    q.cnt = counters;
-    q.total = E * mt * nt;
-    q.victim = blockIdx.x % kNumXcd;
-    q.hops = 0;
-    if (threadIdx.x == 0) s_next[0] = q.pop(-1);
-    __syncthreads();
-    int t = s_next[0];
-    // between tiles: every wave has left its staging strip before the next tile's loads land in the ring, and
-    // thread 0's hand-over is visible
-    for (int it = 0; t >= 0; lds_done_and_barrier(), ++it, t = s_next[it & 1]) {
-    // thread 0 draws the next tile now and looks at the answer only after the main loop
-    int drawn = -1;
-    if (threadIdx.x == 0) drawn = atomicAdd(&q.cnt[q.victim], 1);
+    TileWalker tw;
+    for (int t = tw.start(counters, E * mt * nt, smem); t >= 0; t = tw.next()) {
+    tw.draw();
     const int e = order[t / (mt * nt)];
     // Inside an expert the tiles are numbered band by band (kWgradBand tile rows), down the columns of a band, so
     // that the kQueueGroup consecutive tiles a group of workgroups takes form a 2 x 8 block of tiles rather than a
@@ -1117,9 +1130,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
         mainloop<true, true, DUAL, GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
-    // double-buffered hand-over: the slot written here was last read before the barrier that ended the
-    // previous tile
-    if (threadIdx.x == 0) s_next[(it + 1) & 1] = q.pop(drawn);
+    tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
     XMOE_PROBE_SKIP_EPILOGUE(acc, dW1)
     char* strip = smem + wave * kStripBytes;
@@ -1162,6 +1173,10 @@ bool ffn_dma_supported(const FfnArgs& a) {
 }
 
 static int g_num_cu = 0;
+
+// the work counters of a call's i-th row-GEMM launch (the schedule block holds, behind the sorted experts, kNumXcd
+// counters for each of the two weight-gradient launches and then for each of the two row-GEMM launches)
+static inline int32_t* row_counters(int32_t* sched, int E, int i) { return sched + E + (2 + i) * kNumXcd; }
 
 // persistent launch: one workgroup per CU, but never more than there are tiles (host-side upper bound); a
 // multiple of the XCD count
@@ -1224,16 +1239,16 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
                     hipLaunchKernelGGL(ffn_gateup_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
                                        kLdsBytes, s, xd, a.row_index, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
-                                       (bf16_t*)a.u, (bf16_t*)a.act));
+                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0)));
     else
         XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
                     hipLaunchKernelGGL(ffn_gateup_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
                                        kLdsBytes, s, xd, nullptr, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
-                                       (bf16_t*)a.u, (bf16_t*)a.act));
+                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0)));
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.act, a.off, a.map, a.f, a.d, wd, (bf16_t*)a.y, nullptr,
-                                   nullptr, nullptr, nullptr, nullptr));
+                                   nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
     return XMOE_OK;
 }
 
@@ -1250,10 +1265,10 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
     XMOE_LAUNCH(K_FFN_DACT_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntf)), dim3(512),
                                    kLdsBytes, s, dy, a.off, a.map, a.d, a.f, wd, nullptr, (const bf16_t*)a.g,
-                                   (const bf16_t*)a.u, dg, du, act));
+                                   (const bf16_t*)a.u, dg, du, act, row_counters(a.sched, a.E, 0)));
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
-                                   du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd));
+                                   du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd, row_counters(a.sched, a.E, 1)));
     // dWd [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
@@ -1297,21 +1312,23 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
 #define XMOE_CALL(ACT)                                                                                               \
     XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
                 hipLaunchKernelGGL((mlp2_up_dma_kernel<true, ACT>), grid, dim3(512), kLdsBytes, s, xd, a.row_index,  \
-                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf))
+                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf,              \
+                                   row_counters(a.sched, a.E, 0)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     } else {
 #define XMOE_CALL(ACT)                                                                                               \
     XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
                 hipLaunchKernelGGL((mlp2_up_dma_kernel<false, ACT>), grid, dim3(512), kLdsBytes, s, xd, nullptr,     \
-                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf))
+                                   a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf,              \
+                                   row_counters(a.sched, a.E, 0)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     }
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
                 hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.a_buf, a.off, a.map, a.f, a.d, w2, (bf16_t*)a.y,
-                                   nullptr, nullptr, nullptr, nullptr, nullptr));
+                                   nullptr, nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
     return XMOE_OK;
 }
 
@@ -1329,12 +1346,13 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
 #define XMOE_CALL(ACT)                                                                                            \
     XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                               \
                 hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT>), grid, dim3(512), kLdsBytes, s, dy, a.off, a.map,  \
-                                   a.d, a.f, w2, (const bf16_t*)a.h, dh, act))
+                                   a.d, a.f, w2, (const bf16_t*)a.h, dh, act, row_counters(a.sched, a.E, 0)))
     XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
-                                   kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd));
+                                   kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,
+                                   row_counters(a.sched, a.E, 1)));
     // dW2 [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,

@@ -29,8 +29,9 @@ static inline size_t eri_capped_ws_bytes(int T, int E, int k) {
 constexpr int kMinRowTile = 64;
 static inline int ffn_max_tiles(int B, int E, int tile_rows) { return (B + tile_rows - 1) / tile_rows + E; }
 // After the pairs comes the schedule block of the weight-gradient kernels: the experts in order of descending row
-// count (E ints), then kSchedCounters work counters.
-constexpr int kSchedCounters = 16;
+// count (E ints), then kSchedCounters work counters zeroed by the tile-map kernel: 8 (one per XCD) for each of the two
+// weight-gradient launches of a call, then 8 for each of its two row-GEMM launches.
+constexpr int kSchedCounters = 32;
 static inline size_t ffn_sched_offset(int B, int E) { return 4 + 2 * (size_t)ffn_max_tiles(B, E, kMinRowTile); }
 static inline size_t ffn_tilemap_bytes(int B, int E) {
     // header of 4 ints (total tiles, ...) followed by (expert, row0) pairs, then the schedule block
