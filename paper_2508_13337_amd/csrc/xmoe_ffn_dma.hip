@@ -457,8 +457,7 @@ constexpr int kStripBytes = 32 * kStripStride;    // per wave
 constexpr int kInBytes = 2 * 32 * 64;             // per wave: 32 x 32 bf16 of G and of U (dAct epilogue)
 
 __device__ __forceinline__ uint2 pack4(float a, float b, float c, float d) {
-    return make_uint2((uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16),
-                      (uint32_t)float_to_bf16_bits(c) | ((uint32_t)float_to_bf16_bits(d) << 16));
+    return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
 }
 
 // A strip belongs to one wave, and a wave's LDS operations execute in order, so a strip needs no workgroup
@@ -502,7 +501,10 @@ __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t*
 // operand panels); group g belongs to the list of XCD g % 8, and each list has a counter.  A workgroup draws from
 // its own XCD's list and, once that is empty, from the next XCD's, and so on round the ring; it stops after it
 // has found all eight lists empty.  Only thread 0 touches the counters.
-constexpr int kQueueGroup = 16;
+#ifndef XMOE_QUEUE_GROUP
+#define XMOE_QUEUE_GROUP 16
+#endif
+constexpr int kQueueGroup = XMOE_QUEUE_GROUP;
 #ifndef XMOE_WGRAD_BAND
 #define XMOE_WGRAD_BAND 2
 #endif

@@ -77,12 +77,16 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round-to-nearest-even float32 -> bfloat16 (finite inputs; NaN is kept a NaN)
+// round-to-nearest-even float32 -> bfloat16 (NaN stays a NaN): the conversion instruction of gfx950
+// (v_cvt_pk_bf16_f32), one instruction per two values
+typedef __attribute__((ext_vector_type(2))) float xmoe_f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 xmoe_bf16x2_t;
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const xmoe_f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, xmoe_bf16x2_t));
+}
 __device__ __forceinline__ uint16_t float_to_bf16_bits(float v) {
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
 }
 
 __device__ __forceinline__ float to_float(float v) { return v; }

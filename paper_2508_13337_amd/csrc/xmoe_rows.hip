@@ -35,7 +35,7 @@ struct Vec16<bf16_t> {
         uint32_t u[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            u[j] = (uint32_t)float_to_bf16_bits(v[2 * j]) | ((uint32_t)float_to_bf16_bits(v[2 * j + 1]) << 16);
+            u[j] = pack_bf16x2(v[2 * j], v[2 * j + 1]);
         return make_uint4(u[0], u[1], u[2], u[3]);
     }
 };
