@@ -213,6 +213,8 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+    # the shader clock the matrix-core kernels ran at in the last timed step (the chip lowers it under this load)
+    clocks = xm.xmoe_prof_shader_clocks()
 
     # forward-only timing (reported, not the metric)
     torch.cuda.synchronize()
@@ -244,6 +246,8 @@ def main():
             ent["tflops"] = round(flops[gemm_work[name]] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
             ent["algorithmic_gbs"] = round(bytes_["gemm:" + gemm_work[name]] / (per_step_ms * 1e-3) / 1e9, 1)
+        if name in clocks:
+            ent["shader_clock_ghz"] = round(clocks[name], 3)
         if name in bytes_:
             ent["gbs"] = round(bytes_[name] / (per_step_ms * 1e-3) / 1e9, 2)
             ent["frac_hbm_peak"] = round(ent["gbs"] / PEAK_HBM_GBS, 5)

@@ -270,6 +270,10 @@ int xmoe_prof_num_kernels(void);                  /* number of kernel ids */
 const char* xmoe_prof_kernel_name(int kernel_id); /* name of the __global__ function behind a kernel id */
 /* Waits for all recorded events, then returns launches and total milliseconds of one kernel id. */
 int xmoe_prof_get(int kernel_id, int* launches, double* total_ms);
+/* Shader clock (GHz) that the last launch of a matrix-core kernel of the expert MLP ran at, measured by the kernel
+ * itself (shader-clock counter against the constant 100 MHz counter over the lifetime of its first workgroup).
+ * Synchronises with the device.  0 for a kernel id that keeps no such record or has not run. */
+int xmoe_prof_shader_clock(int kernel_id, double* ghz);
 /* A plain copy kernel, dst[0..bytes) = src[0..bytes): exactly `bytes` read and `bytes` written, the yardstick
  * that hardware byte counters are scaled by.  Device pointers, 16-byte aligned; bytes a multiple of 16; the
  * ranges must not overlap. */

@@ -42,6 +42,7 @@ SIGNATURES = {
     "xmoe_prof_num_kernels": (_c_int, []),
     "xmoe_prof_kernel_name": (ctypes.c_char_p, [_c_int]),
     "xmoe_prof_get": (_c_int, [_c_int, ctypes.POINTER(_c_int), ctypes.POINTER(ctypes.c_double)]),
+    "xmoe_prof_shader_clock": (_c_int, [_c_int, ctypes.POINTER(ctypes.c_double)]),
     "xmoe_prof_copy": (_c_int, [_c_void_p, _c_void_p, ctypes.c_size_t, _c_void_p]),
 }
 

@@ -22,7 +22,7 @@ __all__ = [
     "XMoEError", "xmoe_version", "xmoe_workspace_bytes", "xmoe_gate_logits", "xmoe_route", "xmoe_build_eri",
     "xmoe_dispatch", "xmoe_expert_ffn_fwd", "xmoe_expert_ffn_bwd", "xmoe_combine", "xmoe_combine_bwd",
     "xmoe_dispatch_bwd", "xmoe_route_bwd", "xmoe_gate_logits_bwd", "xmoe_prof_enable", "xmoe_prof_reset",
-    "xmoe_prof_read", "xmoe_prof_copy", "dtype_code", "alloc_workspace",
+    "xmoe_prof_read", "xmoe_prof_copy", "xmoe_prof_shader_clocks", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
     "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
     "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0",
@@ -306,6 +306,17 @@ def xmoe_prof_copy(src, dst) -> None:
     assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
     _check(lib().xmoe_prof_copy(_ptr(src, None, "src"), _ptr(dst, None, "dst"), src.numel() * src.element_size(),
                                 _stream()), "xmoe_prof_copy")
+
+
+def xmoe_prof_shader_clocks() -> dict:
+    """{kernel name: GHz} for the matrix-core kernels of the expert MLP that have run (their last launch)."""
+    out = {}
+    ghz = ctypes.c_double()
+    for kid in range(lib().xmoe_prof_num_kernels()):
+        _check(lib().xmoe_prof_shader_clock(kid, ctypes.byref(ghz)), "xmoe_prof_shader_clock")
+        if ghz.value > 0.0:
+            out[lib().xmoe_prof_kernel_name(kid).decode()] = ghz.value
+    return out
 
 
 def xmoe_prof_read() -> dict:

@@ -41,6 +41,18 @@ constexpr int kNumXcd = 8;
 
 __device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
 
+// Shader clock under load: workgroup 0 of every launch of this family notes the shader-clock counter and the
+// constant 100 MHz counter when it starts and when it leaves (it is persistent, so that spans the launch); the
+// ratio is the clock the kernel really ran at (xmoe_prof_shader_clock).  One slot per kernel of the family.
+enum ClockSlot { CS_GATEUP = 0, CS_DOWN, CS_DACT, CS_DX, CS_WGRAD, CS_WGRAD_DUAL, CS_MLP2_UP, CS_MLP2_DACT, CS_COUNT };
+__device__ unsigned long long g_clock_probe[CS_COUNT][4];
+__device__ __forceinline__ void clock_note(int slot, int at_end) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        g_clock_probe[slot][2 * at_end] = clock64();
+        g_clock_probe[slot][2 * at_end + 1] = wall_clock64();
+    }
+}
+
 #ifdef XMOE_PROBE_TIMING
 // probe build only: per-tile phase timestamps (100 MHz clock) written by thread 0 of each workgroup
 struct ProbeRec {
@@ -633,6 +645,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
                                                              bf16_t* __restrict__ U, bf16_t* __restrict__ A,
                                                              int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(CS_GATEUP, 0);
     const int nt = (f + 127) / 128;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -685,6 +698,7 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     }
         PROBE_MARK(PROBE_IDX, 3)
     }
+    clock_note(CS_GATEUP, 1);
 }
 
 // =========================================================================================================
@@ -701,6 +715,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                                                               bf16_t* __restrict__ dU, bf16_t* __restrict__ A,
                                                               int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(DACT ? CS_DACT : CS_DOWN, 0);
     const int nt = (N + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -827,6 +842,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     }
         PROBE_MARK(PROBE_IDX, 3)
     }
+    clock_note(DACT ? CS_DACT : CS_DOWN, 1);
 }
 
 // =========================================================================================================
@@ -840,6 +856,7 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
                                                          const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
                                                          bf16_t* __restrict__ dXd, int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(CS_DX, 0);
     const int nt = (d + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -881,6 +898,7 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
     }
         PROBE_MARK(PROBE_IDX, 3)
     }
+    clock_note(CS_DX, 1);
 }
 
 // =========================================================================================================
@@ -935,6 +953,7 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
                                                           const bf16_t* __restrict__ w1, bf16_t* __restrict__ H,
                                                           bf16_t* __restrict__ A, int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(CS_MLP2_UP, 0);
     const int nt = (f + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -981,6 +1000,7 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
             strip_sync();
         }
     }
+    clock_note(CS_MLP2_UP, 1);
 }
 
 // =========================================================================================================
@@ -996,6 +1016,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                                                             bf16_t* __restrict__ A,
                                                             int32_t* __restrict__ counters) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(CS_MLP2_DACT, 0);
     const int nt = (f + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -1075,6 +1096,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
             strip_sync();
         }
     }
+    clock_note(CS_MLP2_DACT, 1);
 }
 
 // =========================================================================================================
@@ -1092,6 +1114,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             int32_t* __restrict__ counters, int E, int M, int N,
                                                             bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     extern __shared__ __align__(16) char smem[];
+    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 0);
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
     TileWalker tw;
@@ -1160,6 +1183,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
     }
 PROBE_MARK(PROBE_IDX, 3)
     }
+    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 1);
 }
 
 // =========================================================================================================
@@ -1376,6 +1400,29 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
 }
 
 }  // namespace xmoe
+
+extern "C" int xmoe_prof_shader_clock(int kernel_id, double* ghz) {
+    int slot = -1;
+    switch (kernel_id) {
+        case xmoe::K_FFN_GATEUP_DMA: slot = xmoe::CS_GATEUP; break;
+        case xmoe::K_FFN_DOWN_DMA: slot = xmoe::CS_DOWN; break;
+        case xmoe::K_FFN_DACT_DMA: slot = xmoe::CS_DACT; break;
+        case xmoe::K_FFN_DX_DMA: slot = xmoe::CS_DX; break;
+        case xmoe::K_FFN_WGRAD_DMA: slot = xmoe::CS_WGRAD; break;
+        case xmoe::K_FFN_WGRAD_DUAL_DMA: slot = xmoe::CS_WGRAD_DUAL; break;
+        case xmoe::K_MLP2_UP_DMA: slot = xmoe::CS_MLP2_UP; break;
+        case xmoe::K_MLP2_DACT_DMA: slot = xmoe::CS_MLP2_DACT; break;
+        default: break;
+    }
+    if (!ghz) return XMOE_ERR_INVALID_ARG;
+    *ghz = 0.0;
+    if (slot < 0) return XMOE_OK;
+    unsigned long long v[4];
+    if (hipMemcpyFromSymbol(v, HIP_SYMBOL(xmoe::g_clock_probe), sizeof(v), (size_t)slot * sizeof(v)) != hipSuccess)
+        return XMOE_ERR_HIP;
+    if (v[3] > v[1] && v[2] > v[0]) *ghz = (double)(v[2] - v[0]) / ((double)(v[3] - v[1]) * 10.0);   // 100 MHz ticks
+    return XMOE_OK;
+}
 
 #ifdef XMOE_PROBE_TIMING
 extern "C" int xmoe_probe_dump(void* host_recs, int max_recs, int reset) {
