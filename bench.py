@@ -112,18 +112,18 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3336651270,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1403548670,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2495059123,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2846550964,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1520962817,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 3330454354,
-    ("large", "ffn_gateup_dma_kernel"): 17603657002,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 9217436376,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9201767176,
-    ("large", "ffn_dx_dma_kernel"): 17052672014,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 11995620092,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 21020452025,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3867846571,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1661105022,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2879397680,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 3248960903,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1509710180,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2859835721,
+    ("large", "ffn_gateup_dma_kernel"): 18142535655,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 9067156667,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9400103642,
+    ("large", "ffn_dx_dma_kernel"): 17788713206,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10355465338,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 18884383091,
 }
 
 

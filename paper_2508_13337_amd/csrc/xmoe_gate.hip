@@ -247,62 +247,96 @@ __global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict_
 // D[row 8*(v/4) + 4*(l/32) + v%4][column l%32], v = 0..15.
 typedef __attribute__((ext_vector_type(16))) float gate_f32x16_t;
 
+// two consecutive elements of a row as float32; vec: one 4-byte (bf16) / 8-byte (float) load
+__device__ __forceinline__ void load_pair(const bf16_t* p, bool ok0, bool ok1, bool vec, float& a, float& b) {
+    if (vec) {
+        const uint32_t u = ok0 ? *reinterpret_cast<const uint32_t*>(p) : 0u;
+        a = __uint_as_float(u << 16);
+        b = __uint_as_float(u & 0xffff0000u);
+    } else {
+        a = ok0 ? to_float(p[0]) : 0.f;
+        b = ok1 ? to_float(p[1]) : 0.f;
+    }
+}
+__device__ __forceinline__ void load_pair(const float* p, bool ok0, bool ok1, bool vec, float& a, float& b) {
+    if (vec) {
+        const float2 v = ok0 ? *reinterpret_cast<const float2*>(p) : make_float2(0.f, 0.f);
+        a = v.x;
+        b = v.y;
+    } else {
+        a = ok0 ? p[0] : 0.f;
+        b = ok1 ? p[1] : 0.f;
+    }
+}
+
 // partial[s][i][e] = sum over the s-th slice of tokens of x[t,i] * dlogits[t,e]
-// The summation index is the token, and both operands are stored token-major, so a half-wave reads 32 consecutive
-// elements of one token's row: no transposition.  A block owns 32 rows i x 64 columns e of one slice; its four
-// waves take interleaved runs of 16 tokens each (enough waves in flight to hide the loads' latency), and their
-// four partial tiles are added through LDS in wave order.  grid = (ceil(d/32), ceil(E/64), splits).
+// The summation index is the token, and both operands are stored token-major, so a half-wave reads consecutive
+// elements of one token's row: no transposition.  A block owns 64 rows i x 64 columns e of one slice.  The rows and
+// columns of an instruction's 32 x 32 block are interleaved with those of its neighbour (row r of block a is
+// i0 + 2r + a, column c of block b is e0 + 2c + b), so that one 4-byte load of x and one 8-byte load of dlogits
+// per lane feed four instructions.  The block's four waves take interleaved runs of 16 tokens each (enough waves in
+// flight to hide the loads' latency), and their partial tiles are added through LDS in wave order.
+// grid = (ceil(d/64), ceil(E/64), splits).  vec_x / vec_e: the pairs may be fetched with one load.
 template <typename T>
 __global__ __launch_bounds__(256) void gate_bwd_dw_kernel(const T* __restrict__ x, const float* __restrict__ dl,
                                                           float* __restrict__ partial, int Tn, int d, int E,
-                                                          int t_per_split) {
-    __shared__ float red[4][32][64];   // [wave][accumulator register][lane]
+                                                          int t_per_split, int vec_x, int vec_e) {
+    __shared__ float red[4][32][64];   // [wave][accumulator register][lane], used once per row block a
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i0 = blockIdx.x * 32, e0 = blockIdx.y * 64;
+    const int i0 = blockIdx.x * 64, e0 = blockIdx.y * 64;
     const int tb = blockIdx.z * t_per_split;
     int te = tb + t_per_split;
     te = te < Tn ? te : Tn;
     const int h = lane >> 5, c = lane & 31;
-    const bool ok_i = i0 + c < d, ok_e0 = e0 + c < E, ok_e1 = e0 + 32 + c < E;
-    const T* xa = x + (ok_i ? i0 + c : 0);
-    const float* b0 = dl + (ok_e0 ? e0 + c : 0);
-    const float* b1 = dl + (ok_e1 ? e0 + 32 + c : 0);
-    gate_f32x16_t acc0, acc1;
+    const int ia = i0 + 2 * c, ea = e0 + 2 * c;
+    const bool ok_i0 = ia < d, ok_i1 = ia + 1 < d, ok_e0 = ea < E, ok_e1 = ea + 1 < E;
+    const T* xa = x + (ok_i0 ? ia : 0);
+    const float* ba = dl + (ok_e0 ? ea : 0);
+    gate_f32x16_t acc[2][2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     constexpr int U = 8;   // instructions' worth of operands fetched before the first is used
     for (int t0 = tb + wave * 2 * U; t0 < te; t0 += 4 * 2 * U) {
-        float av[U], bv0[U], bv1[U];
+        float av[U][2], bv[U][2];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + 2 * u + h;
             const bool ok_t = t < te;
-            av[u] = (ok_t && ok_i) ? to_float(xa[(size_t)t * d]) : 0.f;
-            bv0[u] = (ok_t && ok_e0) ? b0[(size_t)t * E] : 0.f;
-            bv1[u] = (ok_t && ok_e1) ? b1[(size_t)t * E] : 0.f;
+            load_pair(xa + (size_t)(ok_t ? t : tb) * d, ok_t && ok_i0, ok_t && ok_i1, vec_x && ok_i1, av[u][0], av[u][1]);
+            load_pair(ba + (size_t)(ok_t ? t : tb) * E, ok_t && ok_e0, ok_t && ok_e1, vec_e && ok_e1, bv[u][0], bv[u][1]);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv0[u], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], bv1[u], acc1, 0, 0, 0);
-        }
-    }
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        red[wave][v][lane] = acc0[v];
-        red[wave][16 + v][lane] = acc1[v];
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][a], bv[u][b], acc[a][b], 0, 0, 0);
     }
-    __syncthreads();
     float* out = partial + (size_t)blockIdx.z * d * E;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int n = threadIdx.x + 256 * r;   // (accumulator register, lane) pair
-        const int reg = n >> 6, l = n & 63;
-        const float sum = ((red[0][reg][l] + red[1][reg][l]) + red[2][reg][l]) + red[3][reg][l];
-        const int v = reg & 15;
-        const int i = i0 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
-        const int e = e0 + 32 * (reg >> 4) + (l & 31);
-        if (i < d && e < E) out[(size_t)i * E + e] = sum;
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            red[wave][v][lane] = acc[a][0][v];
+            red[wave][16 + v][lane] = acc[a][1][v];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int n = threadIdx.x + 256 * r;   // (accumulator register, lane) pair
+            const int reg = n >> 6, l = n & 63;
+            const float sum = ((red[0][reg][l] + red[1][reg][l]) + red[2][reg][l]) + red[3][reg][l];
+            const int v = reg & 15;
+            const int i = i0 + 2 * (8 * (v >> 2) + 4 * (l >> 5) + (v & 3)) + a;
+            const int e = e0 + 2 * (l & 31) + (reg >> 4);
+            if (i < d && e < E) out[(size_t)i * E + e] = sum;
+        }
+        __syncthreads();
     }
 }
 
@@ -427,10 +461,12 @@ static int launch_gate_bwd(const void* x, const void* w, const float* dl, int Tn
                            void* dxg, float* partial, hipStream_t s) {
     const int splits = gate_bwd_splits(Tn);
     const int tps = (Tn + splits - 1) / splits;
-    dim3 g1((d + 31) / 32, (E + 63) / 64, splits);
+    dim3 g1((d + 63) / 64, (E + 63) / 64, splits);
+    const int vec_x = (d % 2 == 0) && ((reinterpret_cast<uintptr_t>(x) & (2 * sizeof(T) - 1)) == 0);
+    const int vec_e = (E % 2 == 0) && ((reinterpret_cast<uintptr_t>(dl) & 7u) == 0);
     XMOE_LAUNCH(K_GATE_BWD_DW, s,
                 hipLaunchKernelGGL(gate_bwd_dw_kernel<T>, g1, dim3(256), 0, s, (const T*)x, dl, partial, Tn, d, E,
-                                   tps));
+                                   tps, vec_x, vec_e));
     size_t n = (size_t)d * E;
     XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, s,
                 hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
