@@ -35,6 +35,9 @@ def parse_args():
     ap.add_argument("--max-token-count", type=int, default=None,
                     help="run the layer with the token-dropping PFT construction at this per-expert capacity "
                          "(default: dropless, the configuration the metric is quoted on)")
+    ap.add_argument("--rbd-experts-per-node", type=int, default=0,
+                    help="also time stage 0 of the redundancy-bypassing dispatch on this layer's routing with that "
+                         "many experts per destination node (reported beside the step, not part of it)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run the library's plain copy kernel once over 1 GiB (a kernel of known traffic, "
                          "for scaling hardware byte counters under rocprofv3 --pmc)")
@@ -297,6 +300,36 @@ def main():
         "kernels": kernels,
         "input_gen_s": round(t_gen, 1),
     }
+
+    if args.rbd_experts_per_node > 0 and args.max_token_count is None:
+        B, E = cfg.B, cfg.E
+        i32 = dict(dtype=torch.int32, device="cuda")
+        out = {n: torch.empty(B, **i32) for n in ("pilot_token_ids", "pilot_expert_ids", "replica_token_ids",
+                                                  "replica_expert_ids", "s1_mapping_indices", "s1_mapping_experts",
+                                                  "merge_src")}
+        out.update({n: torch.empty(E, **i32) for n in ("pilot_tokens_per_expert", "replica_tokens_per_expert")})
+        out.update({n: torch.empty(E + 1, **i32) for n in ("pilot_offsets", "replica_offsets")})
+        keys = torch.from_numpy(xi.make_rbd_keys(B, cfg.seed).view(np.int32).copy()).cuda()
+        ws_rbd = xm.alloc_workspace(xm.xmoe_workspace_bytes(xm.WS_RBD_STAGE0, cfg.T, cfg.d, E, cfg.k, cfg.f, 1))
+        tok, eid = layer.token_ids[:B].contiguous(), layer.expert_ids
+        off = layer.expert_offsets[:E + 1].contiguous()
+
+        def rbd():
+            xm.xmoe_rbd_stage0(layer.topk_idx, keys, tok, eid, off, layer.row_of_slot, args.rbd_experts_per_node, out,
+                               ws_rbd)
+        for _ in range(3):
+            rbd()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            rbd()
+        e1.record()
+        torch.cuda.synchronize()
+        n_pilot = int(out["pilot_offsets"][-1].item())
+        result["rbd_stage0"] = {"experts_per_node": args.rbd_experts_per_node,
+                                "us_per_call": round(e0.elapsed_time(e1) * 1e3 / args.steps, 2),
+                                "pilots": n_pilot, "replicas": B - n_pilot,
+                                "redundancy": round((B - n_pilot) / B, 4)}
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_tokens, x_np, dout_np, wr_np, bias_np)

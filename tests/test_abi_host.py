@@ -58,6 +58,14 @@ def test_workspace_sizes(lib):
     assert lib.xmoe_workspace_bytes(0, 8192, d, E, k, f, 1) >= (8192 * k // 1024) * E * 4
     assert lib.xmoe_workspace_bytes(3, 8192, d, E, k, f, 1) >= d * E * 4
     assert lib.xmoe_workspace_bytes(1, B, d, E, k, f, 7) == 0       # unknown dtype
+    # two-matrix expert: tile map + A, and tile map + dH + A; stage 0 of the redundancy-bypassing dispatch: three
+    # int32 arrays over the T*k rows
+    m_fwd = lib.xmoe_workspace_bytes(5, B, d, E, k, f, 1)
+    m_bwd = lib.xmoe_workspace_bytes(6, B, d, E, k, f, 1)
+    assert B * f * 2 <= m_fwd < 2 * B * f * 2 and 2 * B * f * 2 <= m_bwd < 3 * B * f * 2
+    rbd = lib.xmoe_workspace_bytes(7, 8192, d, E, k, f, 1)
+    assert 3 * 8192 * k * 4 <= rbd < 4 * 8192 * k * 4
+    assert lib.xmoe_workspace_bytes(8, B, d, E, k, f, 1) == 0       # unknown op
     assert lib.xmoe_workspace_bytes(42, B, d, E, k, f, 1) == 0      # unknown op
     for op in range(4):
         assert lib.xmoe_workspace_bytes(op, B, d, E, k, f, 1) % 256 == 0

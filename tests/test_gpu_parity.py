@@ -222,6 +222,52 @@ def test_dispatch_combine_and_backward(name):
                  "dispatch_bwd", scale=0.5, floor="row")
 
 
+@pytest.mark.parametrize("T,E,k,d,dtype,drop", [(300, 16, 1, 64, "bf16", False), (257, 16, 5, 200, "bf16", True),
+                                                (190, 32, 7, 72, "f32", False), (222, 32, 9, 136, "bf16", True),
+                                                (100, 64, 13, 96, "f32", True), (64, 40, 16, 520, "bf16", False),
+                                                (50, 70, 33, 50, "f32", False)])
+def test_combine_and_backward_any_k(T, E, k, d, dtype, drop):
+    """The row movers take the slots in unrolled groups: every group size, a partial last group, several groups,
+    odd widths, and dropped entries (row_of_slot = -1), against the oracle on seeded random tensors."""
+    m = xm()
+    logits = xi.make_logits(T, E, seed=k)
+    idx, w, _ = oracle.route(logits, k)
+    cap = None
+    if drop:
+        cap = max(1, (T * k) // (2 * E))
+        eri = oracle.build_eri_capped(idx, w, E, cap)
+    else:
+        eri = oracle.build_eri(idx, w, E)
+    B = T * k
+    nk = int(eri["expert_offsets"][-1])
+    rng = np.random.default_rng(k)
+    Y = np.zeros((B, d), np.float32)
+    Y[:nk] = xi.round_to_storage(rng.standard_normal((nk, d)).astype(np.float32), dtype)
+    Y[nk:] = np.float32("nan") if dtype == "f32" else 1e30        # rows behind the retained ones must never be read
+    dout = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), dtype)
+    ros, tw = i32(eri["row_of_slot"]), f32(w)
+    out = torch.empty((T, d), dtype=torch_dtype(dtype), device="cuda")
+    m.xmoe_combine(to_dev(Y, dtype), ros, tw, None, None, k, out)
+    want = oracle.combine(Y[:nk].astype(np.float64), eri["token_ids"], eri["combine_weights"].astype(np.float32), T)
+    assert_close(to_host(out), want, dtype, "combine", scale=0.5, floor="row")
+    dy = torch.full((B, d), 7.0, dtype=torch_dtype(dtype), device="cuda")
+    dw = torch.full((T, k), 7.0, dtype=torch.float32, device="cuda")
+    m.xmoe_combine_bwd(to_dev(dout, dtype), to_dev(Y, dtype), ros, tw, dy, dw)
+    dY_ref, dw_ref = oracle.combine_bwd(dout, Y.astype(np.float64), eri["token_ids"],
+                                        eri["combine_weights"].astype(np.float32).astype(np.float64),
+                                        eri["row_of_slot"], k)
+    assert_close(to_host(dy[:nk]), dY_ref, dtype, "combine_bwd dy", scale=0.5, floor="row")
+    assert (dy[nk:] == 7.0).all()                                   # rows of dropped entries are not written
+    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw", scale=2.0)
+    dropped = (eri["row_of_slot"] < 0).reshape(T, k)
+    assert not dw.cpu().numpy()[dropped].any()
+    dx = torch.empty((T, d), dtype=torch_dtype(dtype), device="cuda")
+    dXd = np.where(np.isfinite(Y) & (np.abs(Y) < 1e20), Y, 0).astype(np.float32)
+    m.xmoe_dispatch_bwd(to_dev(dXd, dtype), ros, None, None, k, dx)
+    assert_close(to_host(dx), oracle.dispatch_bwd(dXd.astype(np.float64), eri["row_of_slot"], T, k), dtype,
+                 "dispatch_bwd", scale=0.5, floor="row")
+
+
 # ------------------------------------------------------------------------------------------------ gating backward
 @pytest.mark.parametrize("name", SMALL)
 def test_route_bwd_and_gate_bwd(name):
