@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--max-token-count", type=int, default=None,
                     help="run the layer with the token-dropping PFT construction at this per-expert capacity "
                          "(default: dropless, the configuration the metric is quoted on)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the step as one replay of a captured HIP graph instead of two dozen launches")
     ap.add_argument("--rbd-experts-per-node", type=int, default=0,
                     help="also time stage 0 of the redundancy-bypassing dispatch on this layer's routing with that "
                          "many experts per destination node (reported beside the step, not part of it)")
@@ -180,9 +182,14 @@ def main():
                              max_token_count=args.max_token_count)
     t_gen = time.time() - t_gen
 
-    def step():
+    def eager_step():
         layer.forward(x, w)
         layer.backward(x, w, dout, grads)
+
+    step = eager_step
+    if args.graph:
+        graph = xm.capture_step(layer, x, w, dout, grads)
+        step = graph.replay
 
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -232,7 +239,7 @@ def main():
     xm.xmoe_prof_reset()
     xm.xmoe_prof_enable(True)
     for _ in range(args.steps):
-        step()
+        eager_step()
     torch.cuda.synchronize()
     prof = xm.xmoe_prof_read()
     xm.xmoe_prof_enable(False)
@@ -284,7 +291,7 @@ def main():
         "metric": "MoE-layer tokens/sec fwd+bwd at 1 GPU; grouped-GEMM % bf16 MFMA peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic", "launch": "hip graph" if args.graph else "eager",
         "config": {"workload": cfg.name, "expert": cfg.expert if not mlp2 else f"mlp2/{cfg.act}", "T": cfg.T, "d": cfg.d, "E": cfg.E, "E_s": cfg.E_s, "k": cfg.k, "f": cfg.f,
                    "rows_B": cfg.B, "skew_alpha": cfg.skew_alpha, "max_token_count": args.max_token_count, "useful_tflop_per_step": round(total_flops / 1e12, 4)},
         "fwd_only_ms": round(fwd_ms, 4),

@@ -5,4 +5,4 @@ package is the thin Python binding: the functions in `api` carry the same names 
 only marshal arguments (torch tensors provide device memory and the stream).
 """
 from .api import *  # noqa: F401,F403
-from .layer import XMoE2Layer, XMoELayer, append_shared  # noqa: F401
+from .layer import XMoE2Layer, XMoELayer, append_shared, capture_step  # noqa: F401

@@ -130,6 +130,25 @@ class XMoELayer:
         return self.dx
 
 
+def capture_step(layer, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> "torch.cuda.CUDAGraph":
+    """Records one forward + backward of `layer` (either class) into a HIP graph and returns it; `graph.replay()`
+    then runs the step with one launch instead of two dozen.  The library's calls only enqueue kernels on the current
+    stream (no allocation, no synchronisation, no memset nodes: counters are cleared by kernels), so they can be
+    captured as they are.  All tensors are captured by address: refill x, dout and the weights in place."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up outside the capture (first-use initialisation of the library)
+        layer.forward(x, w)
+        layer.backward(x, w, dout, grads)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer.forward(x, w)
+        layer.backward(x, w, dout, grads)
+    return graph
+
+
 class XMoE2Layer:
     """The same layer with the paper's own expert, Y = act(X W1) W2 (Listing 1's call(tokens, k, max_token_count,
     w1, w2)).  Buffers and call order only; dropless; the gather of dispatch is fused into the expert MLP's loads."""

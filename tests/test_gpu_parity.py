@@ -436,3 +436,44 @@ def test_layer_is_reproducible_run_to_run():
     assert torch.equal(out1, out2) and torch.equal(dx1, dx2)
     for k_ in g1:
         assert torch.equal(g1[k_], g2[k_]), k_
+
+
+def test_captured_step_replays_like_eager():
+    """One forward + backward captured into a HIP graph: every replay, with eager work and synchronisations between
+    the replays, must reproduce the eager results bit for bit."""
+    cfg, inp, _, _ = oracle_run("mid_bf16")
+    m = xm()
+    dt = cfg.dtype
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), E_s=cfg.E_s)
+    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None}
+    grads = {"dw_router": torch.empty_like(w["w_router"])}
+    for k_ in ("wg", "wu", "wd"):
+        w[k_] = m.append_shared(to_dev(inp[k_], dt), to_dev(inp["shared_" + k_], dt))
+        grads["d" + k_] = torch.empty_like(w[k_])
+    x, dout = to_dev(inp["x"], dt), to_dev(inp["dout"], dt)
+    x0, dout0 = x.clone(), dout.clone()
+
+    def eager(xv, dv):
+        x.copy_(xv)
+        dout.copy_(dv)
+        out = layer.forward(x, w).clone()
+        dx = layer.backward(x, w, dout, grads).clone()
+        torch.cuda.synchronize()
+        return out, dx, {k_: v.clone() for k_, v in grads.items()}
+
+    ref_a = eager(x0, dout0)
+    ref_b = eager(dout0, x0)                      # a second input pair: the graph must follow the buffers' contents
+    graph = m.capture_step(layer, x, w, dout, grads)
+    for rep in range(4):
+        xv, dv, ref = (x0, dout0, ref_a) if rep % 2 == 0 else (dout0, x0, ref_b)
+        x.copy_(xv)
+        dout.copy_(dv)
+        for v in grads.values():
+            v.fill_(3.0)
+        layer.out.fill_(3.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(layer.out, ref[0]) and torch.equal(layer.dx, ref[1]), rep
+        for k_ in grads:
+            assert torch.equal(grads[k_], ref[2][k_]), (rep, k_)
+        (torch.ones(1000, device="cuda") * 2).sum().item()      # eager work between the replays
