@@ -1151,9 +1151,11 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         } else {
             b = col_op(Q1 + (long)lo * N + n0, N, ncols, K);
         }
-        const int wcol = DUAL ? wn * 32 : wn * 64;
+        // DUAL: the B tile is [Q1's 128 columns | Q2's 128 columns]; a wave takes 64 contiguous columns of ONE of
+        // the two (waves 0, 1: Q1; waves 2, 3: Q2), so that it stores whole 128-byte lines of one matrix
+        const int wcol = DUAL ? (wn & 1) * 64 : wn * 64;
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
-        mainloop<true, true, DUAL, GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<true, true, false, GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
     tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
@@ -1172,9 +1174,8 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         strip_put(strip, 32, x1);
         strip_sync();
         if (DUAL) {
-            const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 32;
-            strip_flush<32>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 32);
-            strip_flush<32>(strip, 32, dW2 + o, N, mrows - r0, ncols - wn * 32);
+            const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + (wn & 1) * 64;
+            strip_flush<64>(strip, 0, (wn < 2 ? dW1 : dW2) + o, N, mrows - r0, ncols - (wn & 1) * 64);
         } else {
             const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 64;
             strip_flush<64>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 64);
