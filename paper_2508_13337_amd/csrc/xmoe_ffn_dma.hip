@@ -335,8 +335,14 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
                                       const Loader<A_COL, TWO, A_GATHER>& la,
                                       const Loader<B_COL, TWO>& lb, char* __restrict__ st_next,
                                       const char* __restrict__ st, int nt) {
+    // In the kernels whose two operands are both K-strided (the weight gradients) the wave issues its k-tile's loads
+    // at raised priority, ahead of the other wave's matrix instructions on the same SIMD: measured -2 to -4 % there,
+    // +4 to +10 % in the kernels with a K-contiguous operand, where it is therefore left alone.  (Raising the
+    // priority during the matrix instructions instead costs 5 to 10 % everywhere.)
+    if (A_COL && B_COL) __builtin_amdgcn_s_setprio(1);
     la.issue(st_next, nt, kProbeNoA);
     lb.issue(st_next + kOpBytes, nt, kProbeNoB);
+    if (A_COL && B_COL) __builtin_amdgcn_s_setprio(0);
     read_frags<A_COL, B_COL, DUAL>(f0, st, st + kOpBytes, 0);
     mma_step(acc, f1);
 #ifdef XMOE_PROBE_HALFLDS
