@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0               # MI355X HBM3E, published
+PEAK_FP32_TFLOPS = 157.3            # MI355X float32 vector / matrix, published
 
 
 def parse_args():
@@ -51,6 +52,20 @@ def get_cfg(name):
     if name.startswith("longseq-T"):
         return xi.CONFIGS["longseq"].with_T(int(name[len("longseq-T"):]))
     return xi.CONFIGS[name]
+
+
+def small_kernel_work(cfg):
+    """Algorithmic bytes of the index kernels and float32 flops of the gate projection kernels (both expert kinds)."""
+    T, d, E, k, B = cfg.T, cfg.d, cfg.E, cfg.k, cfg.B
+    chunks = (B + 1023) // 1024
+    bytes_ = {
+        "eri_hist_kernel": B * 4 + chunks * E * 4,                    # expert ids read, chunk histograms written
+        "eri_scan_kernel": 2 * chunks * E * 4 + (2 * E + 1) * 4,      # histograms -> chunk bases, counts, offsets
+        "eri_scatter_kernel": B * 8 + chunks * E * 4 + B * 16,        # (expert, weight) read; 4 arrays of B written
+    }
+    f32_flops = {"gate_logits_kernel": 2 * T * d * E, "gate_bwd_dw_kernel": 2 * T * d * E,
+                 "gate_bwd_dx_kernel": 2 * T * d * E}
+    return bytes_, f32_flops
 
 
 def kernel_work(cfg):
@@ -246,6 +261,8 @@ def main():
     xm.xmoe_prof_reset()
 
     flops, bytes_ = kernel_work(cfg)
+    small_bytes, f32_flops = small_kernel_work(cfg)
+    bytes_.update(small_bytes)
     gemm_work = GEMM_WORK_MLP2 if mlp2 else GEMM_WORK
     kernels = {}
     for name, (launches, total_ms) in prof.items():
@@ -256,6 +273,9 @@ def main():
             ent["tflops"] = round(flops[gemm_work[name]] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
             ent["algorithmic_gbs"] = round(bytes_["gemm:" + gemm_work[name]] / (per_step_ms * 1e-3) / 1e9, 1)
+        if name in f32_flops:
+            ent["f32_tflops"] = round(f32_flops[name] / (per_step_ms * 1e-3) / 1e12, 3)
+            ent["frac_f32_peak"] = round(ent["f32_tflops"] / PEAK_FP32_TFLOPS, 5)
         if name in clocks:
             ent["shader_clock_ghz"] = round(clocks[name], 3)
         if name in bytes_:
