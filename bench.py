@@ -132,18 +132,18 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3867846571,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1661105022,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2879397680,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 3248960903,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1509710180,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2859835721,
-    ("large", "ffn_gateup_dma_kernel"): 18142535655,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 9067156667,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9400103642,
-    ("large", "ffn_dx_dma_kernel"): 17788713206,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10355465338,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 18884383091,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3916849235,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1655731791,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2852209068,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 3229654353,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1565349182,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2865934382,
+    ("large", "ffn_gateup_dma_kernel"): 18129055004,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 9088332502,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9363818067,
+    ("large", "ffn_dx_dma_kernel"): 17779866049,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10359643162,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 18814300805,
 }
 
 
