@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--max-token-count", type=int, default=None,
                     help="run the layer with the token-dropping PFT construction at this per-expert capacity "
                          "(default: dropless, the configuration the metric is quoted on)")
+    ap.add_argument("--materialise-dy", action="store_true",
+                    help="unfused backward of combine: dY [B,d] is written and read back (for comparisons)")
     ap.add_argument("--graph", action="store_true",
                     help="time the step as one replay of a captured HIP graph instead of two dozen launches")
     ap.add_argument("--rbd-experts-per-node", type=int, default=0,
@@ -68,9 +70,11 @@ def small_kernel_work(cfg):
     return bytes_, f32_flops
 
 
-def kernel_work(cfg):
+def kernel_work(cfg, materialise_dy=False):
     """Algorithmic work of one step per kernel: flops for the GEMM kernels, bytes for the row movers.
-    The expert MLP runs on R = B + E_s*T rows (the shared experts' segments are copies of x)."""
+    The expert MLP runs on R = B + E_s*T rows (the shared experts' segments are copies of x).
+    materialise_dy: the unfused backward of combine (dY written by combine_bwd, dOut copied to the shared rows)."""
+    dy_rows = 1 if materialise_dy else 0
     s = 4 if cfg.dtype == "f32" else 2
     T, d, E, k, f, B = cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, cfg.B
     Ts = cfg.E_s * T
@@ -81,7 +85,7 @@ def kernel_work(cfg):
         flops = {"up": 2 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 2 * d * rf, "wgrad": 4 * d * rf}
         bytes_ = {
             "combine_kernel": (B + T) * d * s + (B + 2 * T) * d * s,
-            "combine_bwd_kernel": (T + 2 * B) * d * s,
+            "combine_bwd_kernel": (T + (1 + dy_rows) * B) * d * s,
             "route_kernel": T * E * 4 + T * k * 8,
             "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
         }
@@ -93,11 +97,11 @@ def kernel_work(cfg):
     flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf,
              "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf}
     bytes_ = {
-        # only use left in the layer: backward (E_s > 0), dout copied to the shared experts' dY rows
-        "dispatch_kernel": (T + Ts) * d * s if Ts else 0,
+        # only use left in the layer: the unfused backward (E_s > 0), dout copied to the shared experts' dY rows
+        "dispatch_kernel": (T + Ts) * d * s if (Ts and materialise_dy) else 0,
         "combine_kernel": (B + Ts + T) * d * s                                # forward combine
                           + (B + Ts + 2 * T) * d * s,                         # + dispatch backward (same kernel)
-        "combine_bwd_kernel": (T + 2 * B) * d * s,
+        "combine_bwd_kernel": (T + (1 + dy_rows) * B) * d * s,
         "route_kernel": T * E * 4 + T * k * 8,
         "route_bwd_kernel": 2 * T * E * 4 + T * k * 8,
     }
@@ -191,10 +195,11 @@ def main():
     x, dout = dev(x_np), dev(dout_np)
     if mlp2:
         assert cfg.E_s == 0 and args.max_token_count is None
-        layer = xm.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, act=cfg.act)
+        layer = xm.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, act=cfg.act,
+                              fuse_combine_bwd=not args.materialise_dy)
     else:
         layer = xm.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s,
-                             max_token_count=args.max_token_count)
+                             max_token_count=args.max_token_count, fuse_combine_bwd=not args.materialise_dy)
     t_gen = time.time() - t_gen
 
     def eager_step():
@@ -260,7 +265,7 @@ def main():
     xm.xmoe_prof_enable(False)
     xm.xmoe_prof_reset()
 
-    flops, bytes_ = kernel_work(cfg)
+    flops, bytes_ = kernel_work(cfg, args.materialise_dy)
     small_bytes, f32_flops = small_kernel_work(cfg)
     bytes_.update(small_bytes)
     gemm_work = GEMM_WORK_MLP2 if mlp2 else GEMM_WORK

@@ -193,11 +193,19 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t*
  *   dA = dY Wd^T;  dWd_e = A_e^T dY_e;  dG = dA * U * silu'(G);  dU = dA * silu(G);
  *   dXd = dG Wg^T + dU Wu^T;  dWg_e = Xd_e^T dG_e;  dWu_e = Xd_e^T dU_e.
  * xd, row_index: as in the forward call.
+ * dy_row_index: NULL (dy is [B,d]), or the backward of combine fused into the operand loads, the mirror image of
+ * row_index: dy is then the gradient of the layer's output, dout [T,d], dy_row_index [B] int32 holds token ids and
+ * dy_row_scale [B] float32 (NULL = all 1) the combine weight of each row (token_ids and combine_weights of the
+ * ERI-arrays; for a shared expert's rows 0..T-1 and 1), and row i of dY is dy_row_scale[i] * dout[dy_row_index[i]]:
+ * no [B,d] gradient of the expert outputs exists.  The scale is applied in float32 behind the matrix product
+ * (dA = s * (dout Wd^T), dWd = (s * A)^T dout), so the product s * dout is not rounded to dt first; results agree
+ * with the call on a materialised dY to rounding.  Entries of rows outside every segment are never read.
  * Outputs: dxd [B,d]; dwg, dwu [E,d,f]; dwd [E,f,d] - overwritten, all zero for an expert with no rows.
  * ws: XMOE_WS_FFN_BWD bytes.
  */
 int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
-                        const void* dy, const int32_t* expert_offsets, int B, int E, int d, int f,
+                        const void* dy, const int32_t* dy_row_index, const float* dy_row_scale,
+                        const int32_t* expert_offsets, int B, int E, int d, int f,
                         const void* wg, const void* wu, const void* wd,
                         void* dxd, void* dwg, void* dwu, void* dwd, int dt,
                         void* ws, size_t ws_bytes, void* stream);
@@ -216,12 +224,14 @@ int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t
 
 /* Backward of the two-matrix expert (derived; A is recomputed from the saved H):
  *   dA = dY W2^T;  dW2_e = A_e^T dY_e;  dH = dA * act'(H);  dXd = dH W1^T;  dW1_e = Xd_e^T dH_e.
+ * dy_row_index, dy_row_scale: as in xmoe_expert_ffn_bwd.
  * Outputs: dxd [B,d]; dw1 [E,d,f]; dw2 [E,f,d] - overwritten, all zero for an expert with no rows.
  * ws: XMOE_WS_MLP2_BWD bytes.
  */
 int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
-                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
-                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream);
+                         const int32_t* dy_row_index, const float* dy_row_scale, const int32_t* expert_offsets, int B,
+                         int E, int d, int f, const void* w1, const void* w2, int act, void* dxd, void* dw1, void* dw2,
+                         int dt, void* ws, size_t ws_bytes, void* stream);
 
 /* Combine (Section 4.1.2 / Appendix B.4 scatter kernel, which must accumulate since k rows share a token),
  * written as a gather-reduce so that no atomics are needed and the sum order is fixed:
@@ -238,6 +248,8 @@ int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
 /* Backward of combine:
  *   dy[row_of_slot[t*k+j],:] = topk_w[t,j] * dout[t,:];     dw[t,j] = <dout[t,:], y[row_of_slot[t*k+j],:]>
  * dout [T,d]; y [B,d]; dy [B,d] (out); dw [T,k] float32 (out).
+ * dy == NULL: only dw is computed (topk_w may then be NULL too) - for callers that hand dout, token ids and combine
+ * weights to the expert MLP's backward instead (its dy_row_index), so that dY is never written.
  */
 int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w,
                      int T, int k, int d, int dt, void* dy, float* dw, void* stream);

@@ -186,8 +186,18 @@ def xmoe_expert_ffn_fwd(xd, expert_offsets, wg, wu, wd, g_save, u_save, y, ws, r
         _stream()), "xmoe_expert_ffn_fwd")
 
 
+def _check_dy(dy, B, d, dy_row_index, dy_row_scale):
+    if dy_row_index is None:
+        assert dy_row_scale is None and tuple(dy.shape) == (B, d)
+    else:
+        assert dy.shape[1] == d and dy_row_index.numel() == B
+        assert dy_row_scale is None or dy_row_scale.numel() == B
+
+
 def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd, dwg, dwu, dwd, ws,
-                        row_index=None) -> None:
+                        row_index=None, dy_row_index=None, dy_row_scale=None) -> None:
+    """dy_row_index: None, or token ids [B]: dy is then dout [T,d] and row i of dY is dy_row_scale[i] * dout[dy_row_index[i]]
+    (dy_row_scale None = 1): the backward of combine fused into the operand loads."""
     B = xd.shape[0] if row_index is None else row_index.numel()
     d = xd.shape[1]
     E, d2, f = wg.shape
@@ -195,10 +205,12 @@ def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd,
     assert d2 == d and tuple(wu.shape) == (E, d, f) and tuple(wd.shape) == (E, f, d)
     assert tuple(dwg.shape) == (E, d, f) and tuple(dwu.shape) == (E, d, f) and tuple(dwd.shape) == (E, f, d)
     assert tuple(g_save.shape) == (B, f) and tuple(u_save.shape) == (B, f)
-    assert tuple(dy.shape) == (B, d) and tuple(dxd.shape) == (B, d)
+    assert tuple(dxd.shape) == (B, d)
+    _check_dy(dy, B, d, dy_row_index, dy_row_scale)
     _check(lib().xmoe_expert_ffn_bwd(
         _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(g_save, dt, "g_save"),
-        _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"),
+        _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"), _ptr(dy_row_index, torch.int32, "dy_row_index"),
+        _ptr(dy_row_scale, torch.float32, "dy_row_scale"),
         _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(wg, dt), _ptr(wu, dt), _ptr(wd, dt),
         _ptr(dxd, dt, "dxd"), _ptr(dwg, dt, "dwg"), _ptr(dwu, dt, "dwu"), _ptr(dwd, dt, "dwd"), dtype_code(dt),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")
@@ -219,17 +231,21 @@ def xmoe_expert_mlp2_fwd(xd, expert_offsets, w1, w2, act: str, h_save, y, ws, ro
         ws.numel(), _stream()), "xmoe_expert_mlp2_fwd")
 
 
-def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, dw1, dw2, ws, row_index=None) -> None:
+def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, dw1, dw2, ws, row_index=None,
+                         dy_row_index=None, dy_row_scale=None) -> None:
     B = xd.shape[0] if row_index is None else row_index.numel()
     d = xd.shape[1]
     E, d2, f = w1.shape
     dt = xd.dtype
     assert d2 == d and tuple(w2.shape) == (E, f, d)
     assert tuple(dw1.shape) == (E, d, f) and tuple(dw2.shape) == (E, f, d)
-    assert tuple(h_save.shape) == (B, f) and tuple(dy.shape) == (B, d) and tuple(dxd.shape) == (B, d)
+    assert tuple(h_save.shape) == (B, f) and tuple(dxd.shape) == (B, d)
+    _check_dy(dy, B, d, dy_row_index, dy_row_scale)
     _check(lib().xmoe_expert_mlp2_bwd(
         _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(h_save, dt, "h_save"),
-        _ptr(dy, dt, "dy"), _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(w1, dt, "w1"),
+        _ptr(dy, dt, "dy"), _ptr(dy_row_index, torch.int32, "dy_row_index"),
+        _ptr(dy_row_scale, torch.float32, "dy_row_scale"),
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(w1, dt, "w1"),
         _ptr(w2, dt, "w2"), ACT_CODES[act], _ptr(dxd, dt, "dxd"), _ptr(dw1, dt, "dw1"), _ptr(dw2, dt, "dw2"),
         dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_mlp2_bwd")
 
@@ -250,10 +266,12 @@ def xmoe_combine(y, row_of_slot, topk_w, shared_rows, addend, k: int, out) -> No
 
 
 def xmoe_combine_bwd(dout, y, row_of_slot, topk_w, dy, dw) -> None:
+    """dy None: only dw is computed (the expert MLP's backward then takes dout, token ids and combine weights)."""
     T, d = dout.shape
-    k = topk_w.shape[1]
+    k = dw.shape[1]
     dt = dout.dtype
-    assert tuple(dy.shape) == tuple(y.shape) == (T * k, d) and tuple(dw.shape) == (T, k)
+    assert tuple(y.shape) == (T * k, d) and tuple(dw.shape) == (T, k)
+    assert dy is None or tuple(dy.shape) == (T * k, d)
     _check(lib().xmoe_combine_bwd(_ptr(dout, None, "dout"), _ptr(y, dt, "y"),
                                   _ptr(row_of_slot, torch.int32, "row_of_slot"),
                                   _ptr(topk_w, torch.float32, "topk_w"), T, k, d, dtype_code(dt), _ptr(dy, dt, "dy"),

@@ -14,6 +14,9 @@ struct FfnArgs {
     // forward: outputs g, u, y; backward: inputs g, u, dy and outputs dxd, dwg, dwu, dwd
     void *g, *u, *y;
     const void* dy;
+    // backward: NULL, or dy is the [T,d] gradient of the layer's output and row i of dY is dy_scale[i] * dy[dy_index[i]]
+    const int32_t* dy_index;
+    const float* dy_scale;       // NULL = 1
     void *dxd, *dwg, *dwu, *dwd;
     // workspace carve-up
     int32_t* map;                // tile map
@@ -29,6 +32,8 @@ struct Mlp2Args {
     const int32_t* row_index;    // as in FfnArgs
     void *h, *y;                 // forward: outputs; backward: h is an input
     const void* dy;
+    const int32_t* dy_index;     // as in FfnArgs
+    const float* dy_scale;
     void *dxd, *dw1, *dw2;
     int32_t* map;
     int32_t* sched;

@@ -64,12 +64,14 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t*
 }
 
 int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
-                        const void* dy, const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
+                        const void* dy, const int32_t* dy_row_index, const float* dy_row_scale,
+                        const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
                         const void* wd, void* dxd, void* dwg, void* dwu, void* dwd, int dt, void* ws,
                         size_t ws_bytes, void* stream) {
     int st = check_common(B, E, d, f, dt);
     if (st != XMOE_OK) return st;
     if (!expert_offsets || !wg || !wu || !wd || !dwg || !dwu || !dwd) return XMOE_ERR_INVALID_ARG;
+    if (dy_row_scale && !dy_row_index) return XMOE_ERR_INVALID_ARG;
     if (B > 0 && (!xd || !g_save || !u_save || !dy || !dxd)) return XMOE_ERR_INVALID_ARG;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < ffn_bwd_ws_bytes(B, E, d, f, dt))
         return XMOE_ERR_WORKSPACE;
@@ -80,6 +82,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     a.row_index = row_index;
     a.g = const_cast<void*>(g_save); a.u = const_cast<void*>(u_save);
     a.dy = dy;
+    a.dy_index = dy_row_index; a.dy_scale = dy_row_scale;
     a.dxd = dxd; a.dwg = dwg; a.dwu = dwu; a.dwd = dwd;
     char* p = (char*)ws;
     a.map = (int32_t*)p;
@@ -92,7 +95,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
     if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
-    if (family_cap() <= FAM_REG && !row_index && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
+    if (family_cap() <= FAM_REG && !row_index && !dy_row_index && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
     return ffn_bwd_simt(a, s);
 }
 
@@ -124,11 +127,13 @@ int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t
 }
 
 int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
-                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
-                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream) {
+                         const int32_t* dy_row_index, const float* dy_row_scale, const int32_t* expert_offsets, int B,
+                         int E, int d, int f, const void* w1, const void* w2, int act, void* dxd, void* dw1, void* dw2,
+                         int dt, void* ws, size_t ws_bytes, void* stream) {
     int st = check_common(B, E, d, f, dt);
     if (st != XMOE_OK) return st;
     if (!act_ok(act)) return XMOE_ERR_UNSUPPORTED;
+    if (dy_row_scale && !dy_row_index) return XMOE_ERR_INVALID_ARG;
     if (!expert_offsets || !w1 || !w2 || !dw1 || !dw2) return XMOE_ERR_INVALID_ARG;
     if (B > 0 && (!xd || !h_save || !dy || !dxd)) return XMOE_ERR_INVALID_ARG;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < mlp2_bwd_ws_bytes(B, E, d, f, dt))
@@ -140,6 +145,7 @@ int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h
     a.row_index = row_index;
     a.h = const_cast<void*>(h_save);
     a.dy = dy;
+    a.dy_index = dy_row_index; a.dy_scale = dy_row_scale;
     a.dxd = dxd; a.dw1 = dw1; a.dw2 = dw2;
     char* p = (char*)ws;
     a.map = (int32_t*)p;

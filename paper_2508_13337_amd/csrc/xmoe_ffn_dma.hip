@@ -330,10 +330,10 @@ __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt
 // The two stages are distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS
 // read may observe a direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0))
 // before each transposing read, which serialises the ring.
-template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER>
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER, bool B_GATHER>
 __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1,
                                       const Loader<A_COL, TWO, A_GATHER>& la,
-                                      const Loader<B_COL, TWO>& lb, char* __restrict__ st_next,
+                                      const Loader<B_COL, TWO, B_GATHER>& lb, char* __restrict__ st_next,
                                       const char* __restrict__ st, int nt) {
     // In the kernels whose two operands are both K-strided (the weight gradients) the wave issues its k-tile's loads
     // at raised priority, ahead of the other wave's matrix instructions on the same SIMD: measured -2 to -4 % there,
@@ -381,7 +381,7 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
 // 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
 // accumulator registers around every iteration.)
-template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER = false>
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER = false, bool B_GATHER = false>
 __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                           const Operand& oa2, const Operand& ob2, int K2, int mi_count,
                                           char* smem, int probe_idx = -1) {
@@ -389,9 +389,9 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
     if (nk <= 0) return;
     mi_count = __builtin_amdgcn_readfirstlane(mi_count);
-    static_assert(!(A_GATHER && TWO), "a gathered operand cannot be the first of two concatenated ones");
+    static_assert(!((A_GATHER || B_GATHER) && TWO), "a gathered operand cannot be one of two concatenated ones");
     Loader<A_COL, TWO, A_GATHER> la;
-    Loader<B_COL, TWO> lb;
+    Loader<B_COL, TWO, B_GATHER> lb;
     la.init(oa, oa2, nk1, nk);
     lb.init(ob, ob2, nk1, nk);
     // prologue: k-tiles 0 .. kStages-2 (tiles past the end fetch zeros into stages nobody reads, which keeps the
@@ -412,7 +412,7 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         zero_frags(f1);   // the first call multiplies the carried fragments: zeros
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
-            kstep<A_COL, B_COL, DUAL, TWO, A_GATHER>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
+            kstep<A_COL, B_COL, DUAL, TWO, A_GATHER, B_GATHER>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
                                            smem + (kt % kStages) * kStageBytes, nt);
             wait_loads_and_barrier<kInFlight>();
         }
@@ -431,10 +431,10 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     wait_loads_and_barrier<0>();
 }
 
-template <bool A_COL, bool B_COL, bool DUAL, bool A_GATHER = false>
+template <bool A_COL, bool B_COL, bool DUAL, bool A_GATHER = false, bool B_GATHER = false>
 __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                          int mi_count, char* smem, int probe_idx = -1) {
-    mainloop2<A_COL, B_COL, DUAL, false, A_GATHER>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
+    mainloop2<A_COL, B_COL, DUAL, false, A_GATHER, B_GATHER>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
 }
 
 #ifdef XMOE_PROBE_NOEPI
@@ -494,8 +494,11 @@ __device__ __forceinline__ void strip_put(char* strip, int col0, const float (&x
 }
 
 // writes strip columns [col0, col0 + NC) of rows [0, rows_valid) to C (row stride ldc); columns >= cols_valid
-// (a multiple of 4) are skipped.  NC = 32 or 64.
-template <int NC>
+// (a multiple of 4) are skipped.  NC = 32 or 64.  NT: streaming stores for results that this launch never reads
+// again and that are written as whole 128-byte lines: they then do not displace the operand panels the workgroups of
+// an XCD share through L2 (measured -1 to -2 % in the down, dX and weight-gradient kernels; the gate/up kernel, whose
+// rows go out as 64-byte pieces, is 2.5 % slower with them and keeps ordinary stores).
+template <int NC, bool NT = false>
 __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t* C, long ldc, int rows_valid,
                                             int cols_valid) {
     const int lane = threadIdx.x & 63;
@@ -505,9 +508,16 @@ __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t*
 #pragma unroll
     for (int it = 0; it < 32 / RPI; ++it) {
         const int r = it * RPI + lane / LPR;
-        if (r < rows_valid && c4 < cols_valid)
-            *reinterpret_cast<uint2*>(C + (long)r * ldc + c4) =
-                *reinterpret_cast<const uint2*>(strip + r * kStripStride + (col0 + c4) * 2);
+        if (r < rows_valid && c4 < cols_valid) {
+            const uint2 v = *reinterpret_cast<const uint2*>(strip + r * kStripStride + (col0 + c4) * 2);
+            if (NT) {
+                typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+                const u32x2_t w = {v.x, v.y};
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t*>(C + (long)r * ldc + c4));
+            } else {
+                *reinterpret_cast<uint2*>(C + (long)r * ldc + c4) = v;
+            }
+        }
     }
 }
 
@@ -711,8 +721,13 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
 // forward 2: Y = A Wd          (K = f, N = d, weights "in x out" -> col tile)
 // backward 1: dA = dY Wd^T     (K = d, N = f, weights K-contiguous -> row tile) + dG, dU, A in the epilogue
 // =========================================================================================================
-template <bool DACT>
+// DY_GATHER (backward 1 only): X is the [T, K] gradient of the layer's output and row i of dY is
+// x_scale[i] * X[x_index[i]] (the backward of combine folded into this GEMM: dA = s * (dOut Wd^T), and the A that
+// the weight-gradient kernel multiplies with the gathered dOut rows is written as s * A); x_scale NULL = 1.
+template <bool DACT, bool DY_GATHER = false>
 __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __restrict__ X,
+                                                              const int32_t* __restrict__ x_index,
+                                                              const float* __restrict__ x_scale,
                                                               const int32_t* __restrict__ off,
                                                               const int32_t* __restrict__ map, int K, int N,
                                                               const bf16_t* __restrict__ W, bf16_t* __restrict__ Y,
@@ -730,7 +745,8 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     PROBE_BEGIN(DACT ? 2 : 1, t, rt.rows)
     const int n0 = (t % nt) * TN;
     const int ncols = N - n0 < TN ? N - n0 : TN;
-    Operand a = row_op(X + (long)rt.row0 * K, K, rt.rows);
+    Operand a = row_op(DY_GATHER ? X : X + (long)rt.row0 * K, K, rt.rows);
+    if (DY_GATHER) a.gather = x_index + rt.row0;
     const bf16_t* We = W + (long)PROBE_E(rt.e) * K * N;
     f32x16_t acc[4][2];
     zero_acc(acc);
@@ -739,7 +755,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
     if (DACT) {
         Operand b = row_op(We + (long)n0 * K, K, ncols);   // Wd is [f, d]: its rows are the output columns
-        mainloop<false, false, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<false, false, false, DY_GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     } else {
         Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
         mainloop<false, true, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
@@ -765,7 +781,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             strip_put(strip, 0, x0);
             strip_put(strip, 32, x1);
             strip_sync();
-            strip_flush<64>(strip, 0, Y + base, N, rows_valid, cols_valid);
+            strip_flush<64, true>(strip, 0, Y + base, N, rows_valid, cols_valid);
             strip_sync();
         } else {
             // nothing here: the dAct epilogue is handled after the loop (it pipelines its G/U loads over all rounds)
@@ -818,6 +834,8 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                 gv[q] = *reinterpret_cast<const uint2*>(inbuf + off);
                 uv[q] = *reinterpret_cast<const uint2*>(inbuf + 2048 + off);
             }
+            float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
+            if (DY_GATHER && x_scale && m < rows_valid) sc = x_scale[rt.row0 + r0 + m];
             float dg[16], du[16], av[16];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -827,12 +845,12 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                     const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
                     const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
                     const float g = __uint_as_float(gb), u = __uint_as_float(ub);
-                    const float da = acc[mi][ni][4 * q + j];
+                    const float da = DY_GATHER ? acc[mi][ni][4 * q + j] * sc : acc[mi][ni][4 * q + j];
                     const float sg = fast_sigmoid(g);
                     const float sl = g * sg;
                     dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
                     du[4 * q + j] = da * sl;
-                    av[4 * q + j] = sl * u;
+                    av[4 * q + j] = DY_GATHER ? sl * u * sc : sl * u;
                 }
             }
             strip_put(strip, 0, dg);
@@ -899,7 +917,7 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         strip_put(strip, 0, x0);
         strip_put(strip, 32, x1);
         strip_sync();
-        strip_flush<64>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
+        strip_flush<64, true>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
         strip_sync();
     }
         PROBE_MARK(PROBE_IDX, 3)
@@ -1013,8 +1031,11 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
 // two-matrix expert, backward 1: dA = dY W2^T (K = d, N = f; W2 [f, d]: its rows are the output columns), then
 // dH = dA * act'(H) and A = act(H) in the epilogue
 // =========================================================================================================
-template <int ACT>
+// DY_GATHER: as in ffn_rowgemm_dma_kernel (row i of dY is dy_scale[i] * dY[dy_index[i]]; A is written scaled)
+template <int ACT, bool DY_GATHER>
 __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __restrict__ dY,
+                                                            const int32_t* __restrict__ dy_index,
+                                                            const float* __restrict__ dy_scale,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ map, int d, int f,
                                                             const bf16_t* __restrict__ w2,
@@ -1030,14 +1051,15 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
         const RowTile rt = get_row_tile(map, off, t / nt);
         const int n0 = (t % nt) * TN;
         const int ncols = f - n0 < TN ? f - n0 : TN;
-        Operand a = row_op(dY + (long)rt.row0 * d, d, rt.rows);
+        Operand a = row_op(DY_GATHER ? dY : dY + (long)rt.row0 * d, d, rt.rows);
+        if (DY_GATHER) a.gather = dy_index + rt.row0;
         Operand b = row_op(w2 + (long)rt.e * f * d + (long)n0 * d, d, ncols);
         f32x16_t acc[4][2];
         zero_acc(acc);
         const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
         const int lane = threadIdx.x & 63;
         const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
-        mainloop<false, false, false>(acc, a, b, d, mi_count, smem);
+        mainloop<false, false, false, DY_GATHER>(acc, a, b, d, mi_count, smem);
         tw.hand_over();
         char* strip = smem + wave * kStripBytes;
         const int cols_valid = ncols - wn * 64;
@@ -1080,6 +1102,8 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
 #pragma unroll
             for (int q = 0; q < 4; ++q)   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
                 hv[q] = *reinterpret_cast<const uint2*>(inbuf + m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5));
+            float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
+            if (DY_GATHER && dy_scale && m < rows_valid) sc = dy_scale[rt.row0 + r0 + m];
             float dh[16], av[16];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -1089,8 +1113,8 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                     const uint32_t hb = (j & 1) ? (hw[j >> 1] & 0xffff0000u) : (hw[j >> 1] << 16);
                     float a_, g_;
                     act_fast_grad<ACT>(__uint_as_float(hb), a_, g_);
-                    dh[4 * q + j] = acc[mi][ni][4 * q + j] * g_;
-                    av[4 * q + j] = a_;
+                    dh[4 * q + j] = DY_GATHER ? acc[mi][ni][4 * q + j] * sc * g_ : acc[mi][ni][4 * q + j] * g_;
+                    av[4 * q + j] = DY_GATHER ? a_ * sc : a_;
                 }
             }
             strip_put(strip, 0, dh);
@@ -1110,11 +1134,14 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
 // operands are K-strided -> col tiles).  DUAL: two right-hand sides Q1, Q2 sharing P (dWg and dWu share Xd);
 // the block then covers 128 columns of each.  An expert with no rows gets zeros.
 // =========================================================================================================
-template <bool DUAL, bool GATHER>
+// GATHER: P is a [T, M] matrix and row r of the expert's P is P[row_index[lo + r]].  QGATHER (not with DUAL): the
+// same for Q1 through q_index (the gradient of the layer's output standing in for the rows of dY).
+template <bool DUAL, bool GATHER, bool QGATHER = false>
 __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P,
                                                             const int32_t* __restrict__ row_index,
                                                             const bf16_t* __restrict__ Q1,
                                                             const bf16_t* __restrict__ Q2,
+                                                            const int32_t* __restrict__ q_index,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ order,
                                                             int32_t* __restrict__ counters, int E, int M, int N,
@@ -1155,13 +1182,15 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
             b.n_lo = b.n_hi = ncols;
             b.k_valid = K;
         } else {
-            b = col_op(Q1 + (long)lo * N + n0, N, ncols, K);
+            b = col_op(QGATHER ? Q1 + n0 : Q1 + (long)lo * N + n0, N, ncols, K);
+            if (QGATHER) b.gather = q_index + lo;
         }
         // DUAL: the B tile is [Q1's 128 columns | Q2's 128 columns]; a wave takes 64 contiguous columns of ONE of
         // the two (waves 0, 1: Q1; waves 2, 3: Q2), so that it stores whole 128-byte lines of one matrix
         const int wcol = DUAL ? (wn & 1) * 64 : wn * 64;
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
-        mainloop<true, true, false, GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        static_assert(!(DUAL && QGATHER), "the gathered right-hand side is a single matrix");
+        mainloop<true, true, false, GATHER, QGATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
     }
     tw.hand_over();
     PROBE_MARK(PROBE_IDX, 2)
@@ -1181,10 +1210,10 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         strip_sync();
         if (DUAL) {
             const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + (wn & 1) * 64;
-            strip_flush<64>(strip, 0, (wn < 2 ? dW1 : dW2) + o, N, mrows - r0, ncols - (wn & 1) * 64);
+            strip_flush<64, true>(strip, 0, (wn < 2 ? dW1 : dW2) + o, N, mrows - r0, ncols - (wn & 1) * 64);
         } else {
             const long o = (long)e * M * N + (long)(m0 + r0) * N + n0 + wn * 64;
-            strip_flush<64>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 64);
+            strip_flush<64, true>(strip, 0, dW1 + o, N, mrows - r0, ncols - wn * 64);
         }
         strip_sync();
     }
@@ -1237,8 +1266,10 @@ static int init_once() {
             g_num_cu = prop.multiProcessorCount / kNumXcd * kNumXcd;
         int st = allow_big_lds(ffn_gateup_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false, true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, true>);
@@ -1248,9 +1279,12 @@ static int init_once() {
         if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_IDENTITY>);
         if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_GELU>);
         if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_SILU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, false>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, true>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, false>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, true>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, false>);
+        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
@@ -1279,8 +1313,9 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
                                        kLdsBytes, s, xd, nullptr, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
                                        (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0)));
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
-                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
-                                   kLdsBytes, s, (const bf16_t*)a.act, a.off, a.map, a.f, a.d, wd, (bf16_t*)a.y, nullptr,
+                hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
+                                   kLdsBytes, s, (const bf16_t*)a.act, nullptr, nullptr, a.off, a.map, a.f, a.d, wd,
+                                   (bf16_t*)a.y, nullptr,
                                    nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
     return XMOE_OK;
 }
@@ -1295,30 +1330,45 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                  *wd = (const bf16_t*)a.wd, *dy = (const bf16_t*)a.dy;
     bf16_t *dg = (bf16_t*)a.dg, *du = (bf16_t*)a.du, *act = (bf16_t*)a.act;
     const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
-    XMOE_LAUNCH(K_FFN_DACT_DMA, s,
-                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntf)), dim3(512),
-                                   kLdsBytes, s, dy, a.off, a.map, a.d, a.f, wd, nullptr, (const bf16_t*)a.g,
-                                   (const bf16_t*)a.u, dg, du, act, row_counters(a.sched, a.E, 0)));
+    if (a.dy_index)
+        XMOE_LAUNCH(K_FFN_DACT_DMA, s,
+                    hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, true>), dim3(round_up8((long)max_tiles * ntf)),
+                                       dim3(512), kLdsBytes, s, dy, a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f, wd,
+                                       nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
+                                       row_counters(a.sched, a.E, 0)));
+    else
+        XMOE_LAUNCH(K_FFN_DACT_DMA, s,
+                    hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, false>), dim3(round_up8((long)max_tiles * ntf)),
+                                       dim3(512), kLdsBytes, s, dy, nullptr, nullptr, a.off, a.map, a.d, a.f, wd,
+                                       nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
+                                       row_counters(a.sched, a.E, 0)));
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
                                    du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd, row_counters(a.sched, a.E, 1)));
     // dWd [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
-    XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
-                hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
-                                   dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
-                                   (bf16_t*)a.dwd, nullptr));
+    if (a.dy_index)
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
+                                       dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
+                                       nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                                       (bf16_t*)a.dwd, nullptr));
+    else
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
+                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, a.off, a.sched,
+                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     const int ntf2 = (a.f + 127) / 128;
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
-                                       dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, nullptr, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
-                                       dim3(512), kLdsBytes, s, xd, nullptr, dg, du, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dg, du, nullptr, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     return XMOE_OK;
 }
@@ -1359,8 +1409,9 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
 #undef XMOE_CALL
     }
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
-                hipLaunchKernelGGL(ffn_rowgemm_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
-                                   kLdsBytes, s, (const bf16_t*)a.a_buf, a.off, a.map, a.f, a.d, w2, (bf16_t*)a.y,
+                hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
+                                   kLdsBytes, s, (const bf16_t*)a.a_buf, nullptr, nullptr, a.off, a.map, a.f, a.d, w2,
+                                   (bf16_t*)a.y,
                                    nullptr, nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
     return XMOE_OK;
 }
@@ -1376,32 +1427,50 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     bf16_t *dh = (bf16_t*)a.dh, *act = (bf16_t*)a.a_buf;
     const int ntf = (a.f + TN - 1) / TN, ntd = (a.d + TN - 1) / TN;
     const dim3 grid(round_up8((long)max_tiles * ntf));
-#define XMOE_CALL(ACT)                                                                                            \
-    XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                               \
-                hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT>), grid, dim3(512), kLdsBytes, s, dy, a.off, a.map,  \
-                                   a.d, a.f, w2, (const bf16_t*)a.h, dh, act, row_counters(a.sched, a.E, 0)))
-    XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+    if (a.dy_index) {
+#define XMOE_CALL(ACT)                                                                                              \
+    XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
+                hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, true>), grid, dim3(512), kLdsBytes, s, dy, a.dy_index, \
+                                   a.dy_scale, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,            \
+                                   row_counters(a.sched, a.E, 0)))
+        XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
+    } else {
+#define XMOE_CALL(ACT)                                                                                              \
+    XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
+                hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, false>), grid, dim3(512), kLdsBytes, s, dy, nullptr,  \
+                                   nullptr, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,               \
+                                   row_counters(a.sched, a.E, 0)))
+        XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
+#undef XMOE_CALL
+    }
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,
                                    row_counters(a.sched, a.E, 1)));
     // dW2 [f, d] = A^T dY
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
-    XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
-                hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
-                                   dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, a.off, a.sched, a.sched + a.E,
-                                   a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr));
+    if (a.dy_index)
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
+                                       dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
+                                       nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                                       (bf16_t*)a.dw2, nullptr));
+    else
+        XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
+                    hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
+                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, a.off, a.sched,
+                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr));
     // dW1 [d, f] = Xd^T dH
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, true>), dim3(round_up8((long)a.E * mtd * ntf)),
-                                       dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, nullptr, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtd * ntf)),
-                                       dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, nullptr, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
     return XMOE_OK;
 }

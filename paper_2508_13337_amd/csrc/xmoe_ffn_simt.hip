@@ -148,7 +148,10 @@ __global__ __launch_bounds__(256) void ffn_down_simt_kernel(const T* __restrict_
 //                                                            rows: ragged, K = d, N = f
 // ---------------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict__ dY, const int32_t* __restrict__ off,
+__global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict__ dY,
+                                                            const int32_t* __restrict__ dy_index,   // or NULL
+                                                            const float* __restrict__ dy_scale,     // or NULL
+                                                            const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ map, int d, int f,
                                                             const T* __restrict__ wd, const T* __restrict__ G,
                                                             const T* __restrict__ U, T* __restrict__ dG,
@@ -162,7 +165,13 @@ __global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict_
     const T* wde = wd + (size_t)e * f * d;
     float acc[4][4] = {};
     simt_mainloop<true, false>(
-        acc, d, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dY[(size_t)r * d + kk]) : 0.f; },
+        acc, d, sm,
+        [&](int mm, int kk) {
+            int r = row0 + mm;
+            if (r >= row_end) return 0.f;
+            if (dy_index) r = dy_index[r];   // row r of dY is dy_scale[r] * dY[dy_index[r]]; the scale follows below
+            return to_float(dY[(size_t)r * d + kk]);
+        },
         [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wde[(size_t)n * d + kk]) : 0.f; });
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
@@ -172,12 +181,13 @@ __global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict_
             int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
             if (r < row_end && n < f) {
                 size_t ix = (size_t)r * f + n;
-                float g = to_float(G[ix]), u = to_float(U[ix]), da = acc[i][j];
+                const float sc = (dy_index && dy_scale) ? dy_scale[r] : 1.0f;
+                float g = to_float(G[ix]), u = to_float(U[ix]), da = acc[i][j] * sc;
                 float sg = sigmoidf_(g);
                 float sl = g * sg;
                 dG[ix] = from_float<T>(da * u * (sg * (1.0f + g * (1.0f - sg))));
                 dU[ix] = from_float<T>(da * sl);
-                A[ix] = from_float<T>(sl * u);
+                A[ix] = from_float<T>(sl * u * sc);   // scaled: the weight gradient multiplies it with unscaled rows
             }
         }
 }
@@ -225,6 +235,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict__ P,
                                                              const int32_t* __restrict__ row_index,   // of P, or NULL
                                                              const T* __restrict__ Q,
+                                                             const int32_t* __restrict__ q_index,     // of Q, or NULL
                                                              const int32_t* __restrict__ off, int M, int N,
                                                              T* __restrict__ dW) {
     __shared__ SimtSmem sm;
@@ -240,7 +251,12 @@ __global__ __launch_bounds__(256) void ffn_wgrad_simt_kernel(const T* __restrict
             const int r = row_index ? row_index[lo + kk] : lo + kk;
             return to_float(P[(size_t)r * M + m]);
         },
-        [&](int kk, int nn) { int n = n0 + nn; return n < N ? to_float(Q[(size_t)(lo + kk) * N + n]) : 0.f; });
+        [&](int kk, int nn) {
+            int n = n0 + nn;
+            if (n >= N) return 0.f;
+            const int r = q_index ? q_index[lo + kk] : lo + kk;
+            return to_float(Q[(size_t)r * N + n]);
+        });
     T* out = dW + (size_t)e * M * N;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
@@ -296,7 +312,10 @@ __global__ __launch_bounds__(256) void mlp2_up_simt_kernel(const T* __restrict__
 // two-matrix expert, backward 1: dA = dY W2^T, then dH = dA * act'(H), A = act(H)     K = d, N = f
 // ---------------------------------------------------------------------------------------------------------
 template <typename T, int ACT>
-__global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict__ dY, const int32_t* __restrict__ off,
+__global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict__ dY,
+                                                             const int32_t* __restrict__ dy_index,   // or NULL
+                                                             const float* __restrict__ dy_scale,     // or NULL
+                                                             const int32_t* __restrict__ off,
                                                              const int32_t* __restrict__ map, int d, int f,
                                                              const T* __restrict__ w2, const T* __restrict__ H,
                                                              T* __restrict__ dH, T* __restrict__ A) {
@@ -309,7 +328,13 @@ __global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict
     const T* w2e = w2 + (size_t)e * f * d;
     float acc[4][4] = {};
     simt_mainloop<true, false>(
-        acc, d, sm, [&](int mm, int kk) { int r = row0 + mm; return r < row_end ? to_float(dY[(size_t)r * d + kk]) : 0.f; },
+        acc, d, sm,
+        [&](int mm, int kk) {
+            int r = row0 + mm;
+            if (r >= row_end) return 0.f;
+            if (dy_index) r = dy_index[r];
+            return to_float(dY[(size_t)r * d + kk]);
+        },
         [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(w2e[(size_t)n * d + kk]) : 0.f; });
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
@@ -321,8 +346,9 @@ __global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict
                 const size_t ix = (size_t)r * f + n;
                 float a, g;
                 act_fwd_grad<ACT>(to_float(H[ix]), a, g);
-                dH[ix] = from_float<T>(acc[i][j] * g);
-                A[ix] = from_float<T>(a);
+                const float sc = (dy_index && dy_scale) ? dy_scale[r] : 1.0f;
+                dH[ix] = from_float<T>(acc[i][j] * sc * g);
+                A[ix] = from_float<T>(a * sc);
             }
         }
 }
@@ -353,21 +379,21 @@ static int bwd_simt(const FfnArgs& a, hipStream_t s) {
     if (st != XMOE_OK) return st;
     const int tf = (a.f + kSimtTile - 1) / kSimtTile, td = (a.d + kSimtTile - 1) / kSimtTile;
     XMOE_LAUNCH(K_FFN_DACT_SIMT, s,
-                hipLaunchKernelGGL(ffn_dact_simt_kernel<T>, dim3(max_tiles, tf), dim3(256), 0, s, (const T*)a.dy, a.off,
-                                   a.map, a.d, a.f, (const T*)a.wd, (const T*)a.g, (const T*)a.u, (T*)a.dg, (T*)a.du,
+                hipLaunchKernelGGL(ffn_dact_simt_kernel<T>, dim3(max_tiles, tf), dim3(256), 0, s, (const T*)a.dy,
+                                   a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f, (const T*)a.wd, (const T*)a.g, (const T*)a.u, (T*)a.dg, (T*)a.du,
                                    (T*)a.act));
     XMOE_LAUNCH(K_FFN_DX_SIMT, s,
                 hipLaunchKernelGGL(ffn_dx_simt_kernel<T>, dim3(max_tiles, td), dim3(256), 0, s, (const T*)a.dg,
                                    (const T*)a.du, a.off, a.map, a.d, a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.dxd));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(tf, td, a.E), dim3(256), 0, s, (const T*)a.act,
-                                   nullptr, (const T*)a.dy, a.off, a.f, a.d, (T*)a.dwd));
+                                   nullptr, (const T*)a.dy, a.dy_index, a.off, a.f, a.d, (T*)a.dwd));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
-                                   a.row_index, (const T*)a.dg, a.off, a.d, a.f, (T*)a.dwg));
+                                   a.row_index, (const T*)a.dg, nullptr, a.off, a.d, a.f, (T*)a.dwg));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
-                                   a.row_index, (const T*)a.du, a.off, a.d, a.f, (T*)a.dwu));
+                                   a.row_index, (const T*)a.du, nullptr, a.off, a.d, a.f, (T*)a.dwu));
     return XMOE_OK;
 }
 
@@ -398,8 +424,8 @@ static int mlp2_bwd_simt_t(const Mlp2Args& a, hipStream_t s) {
 #define XMOE_CALL(ACT)                                                                                          \
     XMOE_LAUNCH(K_MLP2_DACT_SIMT, s,                                                                            \
                 hipLaunchKernelGGL((mlp2_dact_simt_kernel<T, ACT>), dim3(max_tiles, tf), dim3(256), 0, s,       \
-                                   (const T*)a.dy, a.off, a.map, a.d, a.f, (const T*)a.w2, (const T*)a.h,       \
-                                   (T*)a.dh, (T*)a.a_buf))
+                                   (const T*)a.dy, a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f,              \
+                                   (const T*)a.w2, (const T*)a.h, (T*)a.dh, (T*)a.a_buf))
     XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     XMOE_LAUNCH(K_FFN_DX_SIMT, s,
@@ -408,10 +434,10 @@ static int mlp2_bwd_simt_t(const Mlp2Args& a, hipStream_t s) {
                                    (T*)a.dxd));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(tf, td, a.E), dim3(256), 0, s, (const T*)a.a_buf,
-                                   nullptr, (const T*)a.dy, a.off, a.f, a.d, (T*)a.dw2));
+                                   nullptr, (const T*)a.dy, a.dy_index, a.off, a.f, a.d, (T*)a.dw2));
     XMOE_LAUNCH(K_FFN_WGRAD_SIMT, s,
                 hipLaunchKernelGGL(ffn_wgrad_simt_kernel<T>, dim3(td, tf, a.E), dim3(256), 0, s, (const T*)a.xd,
-                                   a.row_index, (const T*)a.dh, a.off, a.d, a.f, (T*)a.dw1));
+                                   a.row_index, (const T*)a.dh, nullptr, a.off, a.d, a.f, (T*)a.dw1));
     return XMOE_OK;
 }
 

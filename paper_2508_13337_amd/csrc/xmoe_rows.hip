@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
             const int r = row_of_slot[(size_t)t * k + j];
             const bool ok = j0 + jj < k && (unsigned)r < (unsigned)B;
             r8[jj] = ok ? r : -1;
-            w8[jj] = topk_w[(size_t)t * k + j];
+            w8[jj] = dy ? topk_w[(size_t)t * k + j] : 0.f;
             dot[jj] = 0.f;   // stays 0 for a dropped entry: the output does not depend on its weight
         }
         if (VEC) {
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
                         dot[jj] = fmaf(g[i], v[i], dot[jj]);
                         o[i] = w8[jj] * g[i];
                     }
-                    reinterpret_cast<uint4*>(dy + (size_t)r8[jj] * d)[c] = Vec16<T>::pack(o);
+                    if (dy) reinterpret_cast<uint4*>(dy + (size_t)r8[jj] * d)[c] = Vec16<T>::pack(o);
                 }
             }
         } else {
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
                 for (int jj = 0; jj < KU; ++jj) {
                     if (r8[jj] < 0) continue;
                     dot[jj] = fmaf(g, to_float(y[(size_t)r8[jj] * d + c]), dot[jj]);
-                    dy[(size_t)r8[jj] * d + c] = from_float<T>(w8[jj] * g);
+                    if (dy) dy[(size_t)r8[jj] * d + c] = from_float<T>(w8[jj] * g);
                 }
             }
         }
@@ -330,7 +330,7 @@ int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot
     int st = check_rows_args(T, k, d, dt);
     if (st != XMOE_OK) return st;
     if (T == 0) return XMOE_OK;
-    if (!dout || !y || !row_of_slot || !topk_w || !dy || !dw) return XMOE_ERR_INVALID_ARG;
+    if (!dout || !y || !row_of_slot || !dw || (dy && !topk_w)) return XMOE_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     return dt == XMOE_F32 ? launch_combine_bwd<float>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s)
                           : launch_combine_bwd<bf16_t>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s);

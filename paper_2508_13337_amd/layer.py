@@ -22,14 +22,18 @@ class XMoELayer:
     """Buffers and call order for one layer of T tokens; weights are passed in by the caller.
 
     The gather of dispatch is fused into the expert MLP's operand loads: the MLP reads x through token_ids, and no
-    [B,d] copy of the tokens exists (xmoe_dispatch itself is only used to copy dOut into the shared experts' dY rows).
+    [B,d] copy of the tokens exists.  The backward of combine is fused the same way (fuse_combine_bwd, the default):
+    the MLP's backward reads dOut through token_ids and scales by combine_weights, xmoe_combine_bwd only computes the
+    gradient of the combine weights, and no [B,d] gradient of the expert outputs exists.  (Without it dY is written
+    by xmoe_combine_bwd, and xmoe_dispatch copies dOut into the shared experts' dY rows.)
     Shared experts (every token, weight 1) run inside the same grouped-GEMM launches as the routed ones: they are
     experts E .. E+E_s-1 whose segments are rows [B + s*T, B + (s+1)*T) and read x[0..T-1], so the tail of
     expert_offsets and of token_ids is constant and written once here."""
 
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, E_s: int = 0, device="cuda",
-                 max_token_count: Optional[int] = None):
+                 max_token_count: Optional[int] = None, fuse_combine_bwd: bool = True):
         self.T, self.d, self.E, self.k, self.f, self.E_s = T, d, E, k, f, E_s
+        self.fuse_combine_bwd = fuse_combine_bwd
         # None: dropless.  Else the per-expert capacity of the token-dropping PFT construction; the number of
         # retained rows is then known on the device only, so the shared experts (whose segments would have to start
         # right behind the retained rows) run as calls of their own on x.
@@ -55,14 +59,16 @@ class XMoELayer:
         self.expert_offsets = self.offsets_all[:E + 1]
         self.token_ids = self.token_ids_all[:B]
         self.expert_ids = torch.empty(B, **i32)
-        self.combine_weights = torch.empty(B, **f32)
+        # combine weight of every row of the expert MLP: the ERI-array for the routed rows, 1 for a shared expert's
+        self.combine_weights_all = torch.ones(R, **f32)
+        self.combine_weights = self.combine_weights_all[:B]
         self.row_of_slot = torch.empty(B, **i32)
         self.g = torch.empty((R, f), **act)
         self.u = torch.empty((R, f), **act)
         self.y = torch.empty((R, d), **act)
         self.out = torch.empty((T, d), **act)
         # backward
-        self.dy = torch.empty((R, d), **act)
+        self.dy = None if fuse_combine_bwd else torch.empty((R, d), **act)
         self.dw = torch.empty((T, k), **f32)
         self.dxd = torch.empty((R, d), **act)
         self.dlogits = torch.empty((T, E), **f32)
@@ -107,17 +113,26 @@ class XMoELayer:
     def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
         """grads: preallocated dw_router, dwg, dwu, dwd in the layouts of the weights."""
         B, E, T = self.B, self.E, self.T
-        api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, self.dy[:B], self.dw)
+        fused = self.fuse_combine_bwd
+        api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, None if fused else self.dy[:B], self.dw)
         if self.max_token_count is None:
-            if self.E_s > 0:   # dY of a shared expert's rows is dout itself
-                api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
-            api.xmoe_expert_ffn_bwd(x, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
-                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
-                                    row_index=self.token_ids_all)
+            if fused:
+                api.xmoe_expert_ffn_bwd(x, self.g, self.u, dout, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                        self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
+                                        row_index=self.token_ids_all, dy_row_index=self.token_ids_all,
+                                        dy_row_scale=self.combine_weights_all)
+            else:
+                if self.E_s > 0:   # dY of a shared expert's rows is dout itself
+                    api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
+                api.xmoe_expert_ffn_bwd(x, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                        self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
+                                        row_index=self.token_ids_all)
         else:
-            api.xmoe_expert_ffn_bwd(x, self.g[:B], self.u[:B], self.dy[:B], self.expert_offsets,
+            api.xmoe_expert_ffn_bwd(x, self.g[:B], self.u[:B], dout if fused else self.dy[:B], self.expert_offsets,
                                     w["wg"][:E], w["wu"][:E], w["wd"][:E], self.dxd[:B], grads["dwg"][:E],
-                                    grads["dwu"][:E], grads["dwd"][:E], self.ws, row_index=self.token_ids)
+                                    grads["dwu"][:E], grads["dwd"][:E], self.ws, row_index=self.token_ids,
+                                    dy_row_index=self.token_ids if fused else None,
+                                    dy_row_scale=self.combine_weights if fused else None)
             for s in range(self.E_s):
                 seg = slice(B + s * T, B + (s + 1) * T)
                 one = slice(E + s, E + s + 1)
@@ -153,8 +168,10 @@ class XMoE2Layer:
     """The same layer with the paper's own expert, Y = act(X W1) W2 (Listing 1's call(tokens, k, max_token_count,
     w1, w2)).  Buffers and call order only; dropless; the gather of dispatch is fused into the expert MLP's loads."""
 
-    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, act: str = "gelu", device="cuda"):
+    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype: torch.dtype, act: str = "gelu", device="cuda",
+                 fuse_combine_bwd: bool = True):
         self.T, self.d, self.E, self.k, self.f, self.act = T, d, E, k, f, act
+        self.fuse_combine_bwd = fuse_combine_bwd
         B = T * k
         self.B = B
         dt = api.dtype_code(dtype)
@@ -173,7 +190,7 @@ class XMoE2Layer:
         self.h = torch.empty((B, f), **tt)
         self.y = torch.empty((B, d), **tt)
         self.out = torch.empty((T, d), **tt)
-        self.dy = torch.empty((B, d), **tt)
+        self.dy = None if fuse_combine_bwd else torch.empty((B, d), **tt)
         self.dw = torch.empty((T, k), **f32)
         self.dxd = torch.empty((B, d), **tt)
         self.dlogits = torch.empty((T, E), **f32)
@@ -198,9 +215,15 @@ class XMoE2Layer:
 
     def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
         """grads: preallocated dw_router, dw1, dw2 in the layouts of the weights."""
-        api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, self.dy, self.dw)
-        api.xmoe_expert_mlp2_bwd(x, self.h, self.dy, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,
-                                 grads["dw1"], grads["dw2"], self.ws, row_index=self.token_ids)
+        if self.fuse_combine_bwd:   # dY is never written: the MLP's backward reads dOut through token_ids
+            api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, None, self.dw)
+            api.xmoe_expert_mlp2_bwd(x, self.h, dout, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,
+                                     grads["dw1"], grads["dw2"], self.ws, row_index=self.token_ids,
+                                     dy_row_index=self.token_ids, dy_row_scale=self.combine_weights)
+        else:
+            api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, self.dy, self.dw)
+            api.xmoe_expert_mlp2_bwd(x, self.h, self.dy, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,
+                                     grads["dw1"], grads["dw2"], self.ws, row_index=self.token_ids)
         api.xmoe_route_bwd(self.logits, self.topk_idx, self.dw, self.dlogits)
         api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
         api.xmoe_dispatch_bwd(self.dxd, self.row_of_slot, None, self.dx_gate, self.k, self.dx)

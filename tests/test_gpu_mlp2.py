@@ -88,11 +88,24 @@ def test_expert_mlp2_fwd_bwd(name, act):
     m.xmoe_expert_mlp2_bwd(x, to_dev(H, dt), to_dev(dY, dt), off, w1, w2, act, dxd2, dw12, dw22, ws, row_index=tok)
     assert torch.equal(dxd2, dxd) and torch.equal(dw12, dw1) and torch.equal(dw22, dw2)
 
+    # backward of combine fused into the operand loads: dY = combine_weights * dout[token_ids], never materialised
+    dout, cw = to_dev(inp["dout"], dt), f32(eri["combine_weights"])
+    dY_exact = (eri["combine_weights"].astype(np.float32).astype(np.float64)[:, None]
+                * xi.round_to_storage(inp["dout"], dt).astype(np.float64)[eri["token_ids"]])
+    ref3 = oracle.expert_mlp2_bwd(fwd["Xd"], H.astype(np.float64), dY_exact, eri["expert_offsets"], inp["w1"],
+                                  inp["w2"], act)
+    dxd3, dw13, dw23 = torch.empty_like(dxd), torch.full_like(dw1, 7.0), torch.full_like(dw2, 7.0)
+    m.xmoe_expert_mlp2_bwd(x, to_dev(H, dt), dout, off, w1, w2, act, dxd3, dw13, dw23, ws, row_index=tok,
+                           dy_row_index=tok, dy_row_scale=cw)
+    for got, want, what in zip((dxd3, dw13, dw23), ref3, ("dXd", "dW1", "dW2")):
+        assert_close(to_host(got), want, dt, what + " (fused dY)", floor="row" if what == "dXd" else "expert")
 
-def run_layer2(cfg, inp):
+
+def run_layer2(cfg, inp, fuse_combine_bwd=True):
     m = xm()
     dt = cfg.dtype
-    layer = m.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), act=cfg.act)
+    layer = m.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), act=cfg.act,
+                         fuse_combine_bwd=fuse_combine_bwd)
     w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"]),
          "w1": to_dev(inp["w1"], dt), "w2": to_dev(inp["w2"], dt)}
     grads = {"dw_router": torch.empty_like(w["w_router"]), "dw1": torch.empty_like(w["w1"]),
@@ -126,8 +139,16 @@ def check_layer2(cfg, fwd, bwd, layer, out, dx, grads):
 def test_layer2_fwd_bwd(name):
     cfg, inp, fwd, bwd = oracle_run(name)
     layer, out, dx, grads = run_layer2(cfg, inp)
+    assert layer.dy is None     # the default: the backward of combine is fused, dY does not exist
     errs = check_layer2(cfg, fwd, bwd, layer, out, dx, grads)
     print(name, {k_: f"{v[0]:.2e}/{v[1]:.2e}" for k_, v in errs.items()})
+
+
+@pytest.mark.parametrize("name", ["mini_mlp2_f32", "mini_mlp2_bf16"])
+def test_layer2_with_materialised_dy(name):
+    cfg, inp, fwd, bwd = oracle_run(name)
+    layer, out, dx, grads = run_layer2(cfg, inp, fuse_combine_bwd=False)
+    check_layer2(cfg, fwd, bwd, layer, out, dx, grads)
 
 
 def test_layer2_is_reproducible_run_to_run():

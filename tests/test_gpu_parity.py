@@ -213,6 +213,9 @@ def test_dispatch_combine_and_backward(name):
                                         eri["row_of_slot"], cfg.k)
     assert_close(to_host(dy), dY_ref, dt, "combine_bwd dy", scale=0.5, floor="row")
     assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw", scale=2.0)
+    dw_only = torch.full_like(dw, -1.0)   # without dY: the same dw, bit for bit
+    m.xmoe_combine_bwd(to_dev(inp["dout"], dt), to_dev(Y, dt), ros, None, None, dw_only)
+    assert torch.equal(dw_only, dw)
 
     # dispatch backward on the oracle's dXd
     dXd = xi.round_to_storage(bwd["dXd"].astype(np.float32), dt)
@@ -342,13 +345,35 @@ def test_expert_ffn_fwd_bwd(name):
                           row_index=tok)
     assert torch.equal(dxd2, dxd) and torch.equal(dwg2, dwg) and torch.equal(dwu2, dwu) and torch.equal(dwd2, dwd)
 
+    # backward of combine fused into the operand loads: dY is given as dout, token ids and combine weights, and is
+    # never rounded to storage - the reference is the oracle on the exact dY = combine_weights * dout[token_ids]
+    dout, cw = to_dev(inp["dout"], dt), f32(eri["combine_weights"])
+    cw64 = eri["combine_weights"].astype(np.float32).astype(np.float64)
+    dout64 = xi.round_to_storage(inp["dout"], dt).astype(np.float64)
+    for scale, dY_exact in ((cw, cw64[:, None] * dout64[eri["token_ids"]]), (None, dout64[eri["token_ids"]])):
+        ref3 = oracle.expert_ffn_bwd(fwd["Xd"], G.astype(np.float64), U.astype(np.float64), dY_exact,
+                                     eri["expert_offsets"], inp["wg"], inp["wu"], inp["wd"])
+        dxd3 = torch.empty_like(dxd)
+        dwg3, dwu3, dwd3 = torch.full_like(dwg, 7.0), torch.full_like(dwu, 7.0), torch.full_like(dwd, 7.0)
+        m.xmoe_expert_ffn_bwd(x, to_dev(G, dt), to_dev(U, dt), dout, off, wg, wu, wd, dxd3, dwg3, dwu3, dwd3, ws,
+                              row_index=tok, dy_row_index=tok, dy_row_scale=scale)
+        for got, want, what in zip((dxd3, dwg3, dwu3, dwd3), ref3, ("dXd", "dWg", "dWu", "dWd")):
+            assert_close(to_host(got), want, dt, what + " (fused dY)", floor="row" if what == "dXd" else "expert")
+        for e in range(E):
+            if tpe[e] == 0:
+                assert not dwg3[e].any() and not dwu3[e].any() and not dwd3[e].any()
+    with pytest.raises(Exception):   # a scale without an index
+        m.xmoe_expert_ffn_bwd(x, to_dev(G, dt), to_dev(U, dt), to_dev(dY, dt), off, wg, wu, wd, dxd3, dwg3, dwu3, dwd3,
+                              ws, row_index=tok, dy_row_index=None, dy_row_scale=cw)
+
 
 # ------------------------------------------------------------------------------------------------ whole layer
-def run_layer(cfg, inp, max_token_count=None):
+def run_layer(cfg, inp, max_token_count=None, fuse_combine_bwd=True):
     m = xm()
     dt = cfg.dtype
     tdt = torch_dtype(dt)
-    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s, max_token_count=max_token_count)
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s, max_token_count=max_token_count,
+                        fuse_combine_bwd=fuse_combine_bwd)
     w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"])}
     grads = {"dw_router": torch.empty_like(w["w_router"])}
     for k_ in ("wg", "wu", "wd"):
@@ -422,8 +447,28 @@ def test_layer_with_token_dropping(name, cap):
 def test_layer_fwd_bwd(name):
     cfg, inp, fwd, bwd = oracle_run(name)
     layer, out, dx, grads = run_layer(cfg, inp)
+    assert layer.dy is None     # the default: the backward of combine is fused, dY does not exist
     errs = check_layer(cfg, inp, fwd, bwd, layer, out, dx, grads)
     print(name, {k_: f"{v[0]:.2e}/{v[1]:.2e}" for k_, v in errs.items()})
+
+
+@pytest.mark.parametrize("name,cap", [("tiny_f32", None), ("mini_bf16_skew", None), ("odd_bf16", None),
+                                      ("mini_bf16", 200)])
+def test_layer_with_materialised_dy(name, cap):
+    """The unfused backward (xmoe_combine_bwd writes dY, dOut is copied into the shared experts' rows)."""
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    fwd = oracle.moe_layer_fwd(inp, cfg.k, max_token_count=cap)
+    bwd = oracle.moe_layer_bwd(inp, fwd, cfg.k)
+    layer, out, dx, grads = run_layer(cfg, inp, max_token_count=cap, fuse_combine_bwd=False)
+    dt = cfg.dtype
+    assert_close_chain(to_host(out), fwd["out"], dt, "out")
+    assert_close_chain(to_host(dx), bwd["dx"], dt, "dx")
+    assert_close_chain(to_host(grads["dw_router"]), bwd["dw_router"], dt, "dw_router", floor="tensor", norm="tensor")
+    for k_ in ("dwg", "dwu", "dwd"):
+        assert_close_chain(to_host(grads[k_][:cfg.E]), bwd[k_], dt, k_, floor="row")
+        if cfg.E_s > 0:
+            assert_close_chain(to_host(grads[k_][cfg.E:]), bwd["dshared_" + k_[1:]], dt, "dshared_" + k_[1:], floor="row")
 
 
 def test_layer_is_reproducible_run_to_run():
