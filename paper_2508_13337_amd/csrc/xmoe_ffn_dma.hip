@@ -3,7 +3,8 @@
 // 4-stage ring, so that no tile ever passes through registers and three K-steps of loads are always in flight.
 //
 //   block = 512 threads = 8 waves (2 x 4); block tile 256 x 256, K stepped by 32; wave tile 128 x 64 =
-//   4 x 2 tiles of v_mfma_f32_32x32x16_bf16 with float32 accumulators; one block per CU (128 KiB of LDS).
+//   4 x 2 tiles of v_mfma_f32_32x32x16_bf16 with float32 accumulators; one block per CU (128 KiB of LDS for the
+//   ring, 8 KiB for the index buffers of gathered operands).
 //
 // Two LDS tile layouts, chosen by which index of the operand is contiguous in memory:
 //   K-contiguous operand ("row" tile): [256 rows][32 k], 64-byte rows; fragments are read with ds_read_b128.
@@ -35,7 +36,15 @@ constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int kStages = XMOE_DMA_STAGES;
 constexpr int kOpBytes = 256 * TK * 2;          // one operand tile of one stage: 16 KiB
 constexpr int kStageBytes = 2 * kOpBytes;       // A + B
-constexpr int kLdsBytes = kStages * kStageBytes;   // 128 KiB
+// Behind the ring: the index buffers of the gathered K-strided operands (see Loader), per operand and wave two chunks
+// of kIdxChunk k-tiles x 4 k-rows x 4 bytes.
+constexpr int kIdxChunk = 16;
+constexpr int kIdxChunkBytes = kIdxChunk * 4 * 4;             // 256 bytes: one direct-to-LDS dword load of a wave
+constexpr int kIdxWaveBytes = 2 * kIdxChunkBytes;
+constexpr int kIdxBytes = 2 * 8 * kIdxWaveBytes;              // two operands x eight waves: 8 KiB
+constexpr int kIdxScalarTiles = kStages;                      // k-tiles 0 .. kStages-1 of a tile take their rows by scalar loads
+constexpr int kLdsBytes = kStages * kStageBytes + kIdxBytes;  // 136 KiB
+static_assert(kLdsBytes <= 160 * 1024, "LDS of one CU");
 constexpr int kLoadsPerTile = 4;                // per thread: 2 for A, 2 for B
 constexpr int kNumXcd = 8;
 
@@ -132,22 +141,64 @@ struct Operand {
     // gathered operand (loaders with GATHER): the tile's row r (row tile) or k-row r (col tile) is row gather[r] of
     // the matrix at p_lo - the dispatched copy of the tokens is never made
     const int32_t* gather;
+    const int32_t* gather_dma;   // K-strided gathered operand: the same array again (see Loader::gidx_dma)
 };
 
 // per-thread state of the two direct-to-LDS loads an operand needs per stage.  TWO: the K range is the
 // concatenation of two GEMMs (k-tiles [0, nk1) come from operand set 1, [nk1, nk) from set 2).
-// GATHER: rows come through an index array (Operand::gather).  The indices are read with wave-uniform addresses, i.e.
-// through the scalar unit: a per-lane vector load would join the ordered queue of direct-to-LDS loads, and waiting
-// for it would drain the ring.
+// GATHER: rows come through an index array (Operand::gather).  A per-lane vector load of the indices would join the
+// ordered queue of direct-to-LDS loads, and waiting for it would drain the ring.  A K-contiguous operand needs its 256
+// row indices once per tile and reads them with wave-uniform addresses, i.e. through the scalar unit.
+// A K-strided operand needs four new indices per wave and k-tile.  With the chain index -> row -> 64-bit address at
+// the head of a k-step, in front of the step's loads and of everything the wave issues after them, such an operand
+// costs 10 to 12 % of the loop (measured with an identity index on a contiguous copy: it is this chain, not the
+// scattered rows).  So the addresses of a step's loads are formed at the END of the previous step, behind its last
+// matrix instruction (prepare_next), from indices that were read in the middle of that step.  For that the indices
+// travel like the operands: one direct-to-LDS dword load per wave fetches the wave's rows of 16 k-tiles into a
+// wave-private buffer behind the ring (two buffers; chunk c+1 is requested while chunk c is half used, and the k-tile
+// loop's own waits cover it long before it is read), and per k-tile a lane reads its two indices from LDS.  (Scalar
+// loads do not work here: the per-lane choice between two of them in the same step is folded into the load address,
+// which makes them vector loads.)  Only the first kIdxScalarTiles k-tiles of a tile, which are needed before the
+// first chunk can have landed, take the scalar path, one call ahead.
 template <bool COL, bool TWO, bool GATHER = false>
 struct Loader {
     const bf16_t* g[TWO ? 2 : 1][2];   // global address of this lane's 16 bytes for k-tile 0 (or kZero16)
     const int32_t* gidx;  // GATHER: index array
-    int gmul[2];          // GATHER && COL: leading dimension of the gathered matrix (0 for lanes that fetch zeros)
-    // GATHER && COL: source rows of this wave's four k-rows of the k-tile that the next issue() loads; fetched one
-    // call ahead (issue() is called for k-tiles 0, 1, 2, ... in order) so their latency is off the critical path
-    mutable int gk[4];
-    __device__ __forceinline__ void fetch_rows(int kt) const {
+    // GATHER && COL: the same address for the direct-to-LDS index loads, reached through a second kernel parameter.  A
+    // direct-to-LDS load counts as a possible write through both of its pointers, so one that visibly reads the index
+    // array would turn every ordinary load from that array (the scalar loads of the first k-tiles and of the
+    // K-contiguous operand's rows) into a vector load, and waiting for a vector load drains the ring.
+    const int32_t* gidx_dma;   // (the kernels take the index array as two __restrict__ parameters for this)
+    int gld;              // GATHER && COL: leading dimension of the gathered matrix
+    // GATHER && COL: this lane's two source rows (k-rows wave*4 + lane/32 and wave*4 + 2 + lane/32) of the k-tile after
+    // the one issued last (issue() is called for k-tiles 0, 1, 2, ... in order)
+    mutable int gk2[2];
+    mutable const bf16_t* pnext[2];   // the addresses the next main-loop issue() loads from (prepare_next)
+    mutable int gk[4];    // the same k-tile's four k-rows of this wave, where they were fetched by scalar loads
+    char* ibuf;           // GATHER && COL: this wave's two index chunks in LDS
+    // requests chunk c (k-tiles [16c, 16c+16)): lane l fetches the index of k-row (wave*4 + l%4) of k-tile 16c + l/4
+    __device__ __forceinline__ void idx_issue(int c, char* __restrict__ dst) const {
+        const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int kk = (c * kIdxChunk + (lane >> 2)) * TK + wave * 4 + (lane & 3);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(gidx_dma + (kk < k_valid ? kk : k_valid - 1)), LDS_PTR(dst), 4, 0, 0);
+    }
+    // this lane's two source rows of k-tile kt: k-rows wave*4 + lane/32 and wave*4 + 2 + lane/32
+    __device__ __forceinline__ void idx_read(int kt, const char* __restrict__ src) const {
+        const int lane = threadIdx.x & 63;
+        const int* p = reinterpret_cast<const int*>(src + (kt & (kIdxChunk - 1)) * 16 + (lane >> 5) * 4);
+        gk2[0] = p[0];
+        gk2[1] = p[2];
+    }
+    __device__ __forceinline__ char* idx_buf(int chunk) const { return ibuf + (chunk & 1) * kIdxChunkBytes; }
+    // before k-tile kt is issued: half way through a chunk, request the next one (if the tile has it).  It lands in the
+    // buffer that is not read before k-tile 16*(chunk+1) - 1 is issued, seven k-tiles (and barriers) later.
+    __device__ __forceinline__ void request_ahead(int kt) const {
+        if (GATHER && COL) {
+            const int c = (kt >> 4) + 1;
+            if ((kt & (kIdxChunk - 1)) == kIdxChunk / 2 && c * kIdxChunk * TK < k_valid) idx_issue(c, idx_buf(c));
+        }
+    }
+    __device__ __forceinline__ void fetch_rows(int kt) const {   // the scalar path (first k-tiles of a tile)
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -155,19 +206,28 @@ struct Loader {
             gk[r] = gidx[kk < k_valid ? kk : k_valid - 1];   // wave-uniform address
         }
     }
+    // the scalar path's rows as this lane's two
+    __device__ __forceinline__ void rows_from_scalar() const {
+        const bool up = (threadIdx.x & 32) != 0;
+        gk2[0] = up ? gk[1] : gk[0];
+        gk2[1] = up ? gk[3] : gk[2];
+    }
     long step[2];         // elements to advance per k-tile (0 for lanes that fetch zeros)
     int krow[2];          // col tile: k index inside the tile, for the k_valid test
     int lds_off[2];       // wave-uniform byte offset of the instruction's 1 KiB destination inside the tile
     int k_valid;
     int nk1, nk;          // k-tiles of set 1, total k-tiles; tiles past the end fetch zeros
 
-    __device__ __forceinline__ void init(const Operand& o, const Operand& o2, int num_k1, int num_k) {
+    // ibuf_: this operand's index buffers (kIdxWaveBytes per wave); only touched by a gathered K-strided operand
+    __device__ __forceinline__ void init(const Operand& o, const Operand& o2, int num_k1, int num_k, char* ibuf_) {
         const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        ibuf = ibuf_ + wave * kIdxWaveBytes;
         k_valid = o.k_valid;
         nk1 = num_k1;
         nk = num_k;
         gidx = o.gather;
-        gmul[0] = gmul[1] = 0;
+        gidx_dma = o.gather_dma;
+        gld = (int)o.ld;
         int grow[2] = {0, 0};   // GATHER && !COL: source rows of this lane's two tile rows
         if (GATHER && !COL) {
 #pragma unroll
@@ -199,35 +259,69 @@ struct Loader {
                 g[0][i] = ok ? (hi ? o.p_hi : o.p_lo) + (GATHER ? 0 : (long)kr * o.ld) + col
                              : reinterpret_cast<const bf16_t*>(kZero16);
                 step[i] = ok ? (long)TK * o.ld : 0;
-                gmul[i] = ok ? (int)o.ld : 0;
                 krow[i] = ok ? kr : (1 << 30);
                 lds_off[i] = (wave * 4 + i * 2) * 512;
             }
         }
-        if (GATHER && COL) fetch_rows(0);
+        if (GATHER && COL) {
+            // chunk 0 is older than every operand load of the tile, so the wait that ends the prologue covers it
+            idx_issue(0, idx_buf(0));
+            fetch_rows(0);
+            rows_from_scalar();
+        }
     }
 
-    // issues the two loads of k-tile kt into `tile` (LDS address of this operand's tile in the target stage)
-    __device__ __forceinline__ void issue(char* tile, int kt, bool probe_zero = false) const {
+    // issues the two loads of k-tile kt into `tile` (LDS address of this operand's tile in the target stage).
+    // PROLOGUE: one of the first kStages-1 k-tiles of a tile (gathered K-strided operand: rows by scalar loads, one
+    // call ahead); otherwise a main-loop step, whose addresses prepare_next() has formed.
+    // gathered K-strided operand: forms the addresses of k-tile kt from the rows in gk2.  Called at the END of a main
+    // loop step for the next one, while the step's last matrix instructions still run: formed at the head of the
+    // step, the chain index -> row -> 64-bit address sits in front of the step's loads and all that follows them.
+    __device__ __forceinline__ void prepare_next(int kt) const {
+        if (GATHER && COL) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const bf16_t* p = g[0][i] + (long)gk2[i] * gld;
+                if (kt * TK + krow[i] >= k_valid) p = reinterpret_cast<const bf16_t*>(kZero16);
+                pnext[i] = p;
+            }
+            // an anchor in front of the barrier that ends the step (volatile asm statements keep their order): the
+            // scheduler would otherwise sink this arithmetic behind the barrier, to the head of the next step
+            asm volatile("" ::"v"(pnext[0]), "v"(pnext[1]));
+        }
+    }
+    // main loop: the rows of k-tile kt from the index chunk; called in the middle of the step that issued k-tile kt-1,
+    // among its fragment reads (right behind the loads, in front of the first matrix instruction, the wait for the
+    // step's first fragments would also wait for this read)
+    __device__ __forceinline__ void read_rows(int kt, const char* __restrict__ idx_rd) const {
+        if (GATHER && COL) idx_read(kt, idx_rd);
+    }
+    template <bool PROLOGUE>
+    __device__ __forceinline__ void issue(char* tile, int kt, bool probe_zero) const {
         int src_row[2] = {0, 0};
         if (GATHER && COL) {
-            const int lane = threadIdx.x & 63;
-            src_row[0] = (lane >> 5) ? gk[1] : gk[0];
-            src_row[1] = (lane >> 5) ? gk[3] : gk[2];
-            fetch_rows(kt + 1);
+            src_row[0] = gk2[0];
+            src_row[1] = gk2[1];
+            // the prologue issues k-tiles 0 .. kStages-2 and prepares k-tiles 1 .. kStages-1 = kIdxScalarTiles-1
+            if (PROLOGUE) {
+                fetch_rows(kt + 1);
+                rows_from_scalar();
+                if (kt == kStages - 2) prepare_next(kt + 1);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const bf16_t* p;
             if (GATHER && COL) {
-                p = g[0][i] + (long)src_row[i] * gmul[i];
+                // lanes outside the operand hold the block of zeros in g and krow beyond every k_valid
+                p = PROLOGUE ? g[0][i] + (long)src_row[i] * gld : pnext[i];
             } else if (TWO) {
                 p = kt < nk1 ? g[0][i] + (long)kt * step[i] : g[TWO ? 1 : 0][i] + (long)(kt - nk1) * step[i];
             } else {
                 p = g[0][i] + (long)kt * step[i];
             }
             if (COL) {
-                if (kt * TK + krow[i] >= k_valid) p = reinterpret_cast<const bf16_t*>(kZero16);
+                if ((PROLOGUE || !GATHER) && kt * TK + krow[i] >= k_valid) p = reinterpret_cast<const bf16_t*>(kZero16);
             } else {
                 if (kt >= nk) p = reinterpret_cast<const bf16_t*>(kZero16);
             }
@@ -321,6 +415,23 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 // workgroup barrier that waits only for the wave's LDS traffic (result stores stay in flight)
 __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// The index chunk a k-tile's loads read (gathered K-strided operands only) is handed to kstep / feed_step as a
+// __restrict__ parameter, for the same reason as the ring stages: an LDS read that may observe a direct-to-LDS load
+// in flight makes the compiler drain every outstanding load first.  (The chunk requested between two k-tiles goes to
+// the other buffer of the pair.)
+
+// a k-tile of a wave that has nothing to multiply: it only feeds the ring
+template <class LA, class LB>
+__device__ __forceinline__ void feed_step(const LA& la, const LB& lb, char* __restrict__ st_next, int nt,
+                                          const char* __restrict__ ia_rd, const char* __restrict__ ib_rd) {
+    la.template issue<false>(st_next, nt, kProbeNoA);
+    lb.template issue<false>(st_next + kOpBytes, nt, kProbeNoB);
+    la.read_rows(nt + 1, ia_rd);
+    lb.read_rows(nt + 1, ib_rd);
+    la.prepare_next(nt + 1);
+    lb.prepare_next(nt + 1);
+}
+
 // One k-tile of the main loop.  On entry k-tile kt has landed in `st`, every wave has finished reading the stage
 // `st_next` (k-tile kt-1), and f1 still holds the second 16-wide k-step of k-tile kt-1.  The body refills st_next
 // with k-tile nt = kt+3, fetches the first k-step of k-tile kt while the MFMAs of the carried f1 run, then fetches
@@ -334,17 +445,20 @@ template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER, bool B_GAT
 __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1,
                                       const Loader<A_COL, TWO, A_GATHER>& la,
                                       const Loader<B_COL, TWO, B_GATHER>& lb, char* __restrict__ st_next,
-                                      const char* __restrict__ st, int nt) {
+                                      const char* __restrict__ st, int nt, const char* __restrict__ ia_rd,
+                                      const char* __restrict__ ib_rd) {
     // In the kernels whose two operands are both K-strided (the weight gradients) the wave issues its k-tile's loads
     // at raised priority, ahead of the other wave's matrix instructions on the same SIMD: measured -2 to -4 % there,
     // +4 to +10 % in the kernels with a K-contiguous operand, where it is therefore left alone.  (Raising the
     // priority during the matrix instructions instead costs 5 to 10 % everywhere.)
     if (A_COL && B_COL) __builtin_amdgcn_s_setprio(1);
-    la.issue(st_next, nt, kProbeNoA);
-    lb.issue(st_next + kOpBytes, nt, kProbeNoB);
+    la.template issue<false>(st_next, nt, kProbeNoA);
+    lb.template issue<false>(st_next + kOpBytes, nt, kProbeNoB);
     if (A_COL && B_COL) __builtin_amdgcn_s_setprio(0);
     read_frags<A_COL, B_COL, DUAL>(f0, st, st + kOpBytes, 0);
     mma_step(acc, f1);
+    la.read_rows(nt + 1, ia_rd);
+    lb.read_rows(nt + 1, ib_rd);
 #ifdef XMOE_PROBE_HALFLDS
     f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
 #else
@@ -375,6 +489,10 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
     }
+    // gathered K-strided operands: the next step's load addresses, behind the last matrix instruction (0x002 = VALU)
+    la.prepare_next(nt + 1);
+    lb.prepare_next(nt + 1);
+    if ((A_GATHER && A_COL) || (B_GATHER && B_COL)) __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);
 }
 
 // acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
@@ -392,14 +510,15 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     static_assert(!((A_GATHER || B_GATHER) && TWO), "a gathered operand cannot be one of two concatenated ones");
     Loader<A_COL, TWO, A_GATHER> la;
     Loader<B_COL, TWO, B_GATHER> lb;
-    la.init(oa, oa2, nk1, nk);
-    lb.init(ob, ob2, nk1, nk);
+    char* idx_area = smem + kStages * kStageBytes;
+    la.init(oa, oa2, nk1, nk, idx_area);
+    lb.init(ob, ob2, nk1, nk, idx_area + 8 * kIdxWaveBytes);
     // prologue: k-tiles 0 .. kStages-2 (tiles past the end fetch zeros into stages nobody reads, which keeps the
     // number of outstanding loads uniform)
 #pragma unroll
     for (int s = 0; s < kStages - 1; ++s) {
-        la.issue(smem + s * kStageBytes, s, kProbeNoA);
-        lb.issue(smem + s * kStageBytes + kOpBytes, s, kProbeNoB);
+        la.template issue<true>(smem + s * kStageBytes, s, kProbeNoA);
+        lb.template issue<true>(smem + s * kStageBytes + kOpBytes, s, kProbeNoB);
     }
     // Invariant at the top of iteration kt (established by the barrier before it): k-tiles <= kt have landed for
     // every thread, and every wave is done reading k-tile kt-1, so that stage can be refilled with k-tile kt+3:
@@ -412,8 +531,11 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         zero_frags(f1);   // the first call multiplies the carried fragments: zeros
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
+            la.request_ahead(nt);
+            lb.request_ahead(nt);
             kstep<A_COL, B_COL, DUAL, TWO, A_GATHER, B_GATHER>(acc, f0, f1, la, lb, smem + (nt % kStages) * kStageBytes,
-                                           smem + (kt % kStages) * kStageBytes, nt);
+                                                               smem + (kt % kStages) * kStageBytes, nt,
+                                                               la.idx_buf((nt + 1) >> 4), lb.idx_buf((nt + 1) >> 4));
             wait_loads_and_barrier<kInFlight>();
         }
         mma_step(acc, f1);   // second k-step of the last k-tile
@@ -421,9 +543,10 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         // a wave whose rows (or columns) all lie past the ragged tail: it only feeds the ring and keeps the barriers
         for (int kt = 0; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
-            char* st_next = smem + (nt % kStages) * kStageBytes;
-            la.issue(st_next, nt, kProbeNoA);
-            lb.issue(st_next + kOpBytes, nt, kProbeNoB);
+            la.request_ahead(nt);
+            lb.request_ahead(nt);
+            feed_step(la, lb, smem + (nt % kStages) * kStageBytes, nt, la.idx_buf((nt + 1) >> 4),
+                      lb.idx_buf((nt + 1) >> 4));
             wait_loads_and_barrier<kInFlight>();
         }
     }
@@ -622,6 +745,7 @@ __device__ __forceinline__ Operand row_op(const bf16_t* p, long ld, int rows) {
     o.n_lo = o.n_hi = rows;
     o.k_valid = 0;
     o.gather = nullptr;
+    o.gather_dma = nullptr;
     return o;
 }
 __device__ __forceinline__ Operand col_op(const bf16_t* p, long ld, int cols, int k_valid) {
@@ -633,6 +757,7 @@ __device__ __forceinline__ Operand col_op(const bf16_t* p, long ld, int cols, in
     o.n_hi = cols > 128 ? cols - 128 : 0;
     o.k_valid = k_valid;
     o.gather = nullptr;
+    o.gather_dma = nullptr;
     return o;
 }
 
@@ -1142,6 +1267,8 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ Q1,
                                                             const bf16_t* __restrict__ Q2,
                                                             const int32_t* __restrict__ q_index,
+                                                            const int32_t* __restrict__ row_index_dma,
+                                                            const int32_t* __restrict__ q_index_dma,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ order,
                                                             int32_t* __restrict__ counters, int E, int M, int N,
@@ -1173,7 +1300,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
     if (K > 0) {
         // GATHER: P is the token matrix and k-row r of the expert's P is P[row_index[lo + r]]
         Operand a = col_op(GATHER ? P + m0 : P + (long)lo * M + m0, M, mrows, K);
-        if (GATHER) a.gather = row_index + lo;
+        if (GATHER) a.gather = row_index + lo, a.gather_dma = row_index_dma + lo;
         Operand b;
         if (DUAL) {
             b.p_lo = Q1 + (long)lo * N + n0;
@@ -1183,7 +1310,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
             b.k_valid = K;
         } else {
             b = col_op(QGATHER ? Q1 + n0 : Q1 + (long)lo * N + n0, N, ncols, K);
-            if (QGATHER) b.gather = q_index + lo;
+            if (QGATHER) b.gather = q_index + lo, b.gather_dma = q_index_dma + lo;
         }
         // DUAL: the B tile is [Q1's 128 columns | Q2's 128 columns]; a wave takes 64 contiguous columns of ONE of
         // the two (waves 0, 1: Q1; waves 2, 3: Q2), so that it stores whole 128-byte lines of one matrix
@@ -1250,7 +1377,7 @@ static inline unsigned round_up8(long v) {
 
 template <class Kern>
 static int allow_big_lds(Kern k) {
-    // kernels of this family use 128 KiB of dynamic LDS, above the 64 KiB default limit
+    // kernels of this family use 136 KiB of dynamic LDS, above the 64 KiB default limit
     return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                kLdsBytes) == hipSuccess
                ? XMOE_OK
@@ -1351,24 +1478,27 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
-                                       nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
+                                       a.d,
                                        (bf16_t*)a.dwd, nullptr));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
-                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
+                                       a.sched,
                                        a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     const int ntf2 = (a.f + 127) / 128;
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
-                                       dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, nullptr, a.row_index, nullptr, a.off,
+                                       a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
-                                       dim3(512), kLdsBytes, s, xd, nullptr, dg, du, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dg, du, nullptr, nullptr, nullptr, a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
     return XMOE_OK;
 }
@@ -1454,23 +1584,27 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
-                                       nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f, a.d,
+                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
+                                       a.d,
                                        (bf16_t*)a.dw2, nullptr));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
-                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
+                                       a.sched,
                                        a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr));
     // dW1 [d, f] = Xd^T dH
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, true>), dim3(round_up8((long)a.E * mtd * ntf)),
-                                       dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, nullptr, a.row_index, nullptr,
+                                       a.off, a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtd * ntf)),
-                                       dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, nullptr, a.off, a.sched,
+                                       dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, nullptr, nullptr, nullptr, a.off,
+                                       a.sched,
                                        a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
     return XMOE_OK;
 }
