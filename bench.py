@@ -136,18 +136,18 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3916849235,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1655731791,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2852209068,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 3229654353,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1565349182,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2865934382,
-    ("large", "ffn_gateup_dma_kernel"): 18129055004,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 9088332502,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9363818067,
-    ("large", "ffn_dx_dma_kernel"): 17779866049,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10359643162,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 18814300805,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3965870826,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1595350369,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2935644543,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 3263785013,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1511414078,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2867165295,
+    ("large", "ffn_gateup_dma_kernel"): 18151200502,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 9062810803,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9452494613,
+    ("large", "ffn_dx_dma_kernel"): 17747160311,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10220612862,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17483443110,
 }
 
 
