@@ -37,11 +37,19 @@ __global__ __launch_bounds__(512) void eri_scan_kernel(int32_t* __restrict__ chu
     __shared__ int tot[XMOE_MAX_EXPERTS];
     const int e = threadIdx.x;
     if (e < E) {
+        // 16 chunks at a time: the loads of a batch are independent, so the walk costs nchunks/16 round trips to
+        // memory instead of nchunks
+        constexpr int kBatch = 16;
         int run = 0;
-        for (int c = 0; c < nchunks; ++c) {
-            int v = chunk_counts[(size_t)c * E + e];
-            chunk_counts[(size_t)c * E + e] = run;
-            run += v;
+        for (int c0 = 0; c0 < nchunks; c0 += kBatch) {
+            int v[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) v[j] = c0 + j < nchunks ? chunk_counts[(size_t)(c0 + j) * E + e] : 0;
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (c0 + j < nchunks) chunk_counts[(size_t)(c0 + j) * E + e] = run;
+                run += v[j];
+            }
         }
         tot[e] = run;
         tokens_per_expert[e] = run;
