@@ -136,18 +136,18 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3965870826,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1595350369,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2935644543,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 3263785013,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1511414078,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2867165295,
-    ("large", "ffn_gateup_dma_kernel"): 18151200502,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 9062810803,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9452494613,
-    ("large", "ffn_dx_dma_kernel"): 17747160311,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10220612862,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 17483443110,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 4017192532,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1693180066,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2931516895,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 3154431484,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1510164826,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2871385098,
+    ("large", "ffn_gateup_dma_kernel"): 18260262241,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 9073607719,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9345146472,
+    ("large", "ffn_dx_dma_kernel"): 17539410752,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10219706657,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17481636355,
 }
 
 
