@@ -367,6 +367,43 @@ def test_expert_ffn_fwd_bwd(name):
                               ws, row_index=tok, dy_row_index=None, dy_row_scale=cw)
 
 
+@pytest.mark.parametrize("rows", [(1537, 0, 163), (2049, 31, 1), (513, 512, 511)])
+def test_expert_ffn_bwd_long_ragged_segments(rows):
+    """Segments of several index chunks (a K-strided gathered operand fetches its row indices 16 k-tiles = 512 rows at
+    a time) with ragged ends, an empty or a one-row expert: both gathers against the oracle, element by element."""
+    m = xm()
+    rng = np.random.default_rng(sum(rows))
+    T, d, f, E = 900, 128, 192, len(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    B = int(off[-1])
+    dt = "bf16"
+    x = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), dt)
+    dout = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), dt)
+    tok = rng.integers(0, T, size=B).astype(np.int32)
+    cw = rng.random(B).astype(np.float32)
+    wg, wu = (xi.round_to_storage((rng.standard_normal((E, d, f)) / np.sqrt(d)).astype(np.float32), dt) for _ in range(2))
+    wd = xi.round_to_storage((rng.standard_normal((E, f, d)) / np.sqrt(f)).astype(np.float32), dt)
+    G = xi.round_to_storage(rng.standard_normal((B, f)).astype(np.float32), dt)
+    U = xi.round_to_storage(rng.standard_normal((B, f)).astype(np.float32), dt)
+    dY = cw.astype(np.float64)[:, None] * dout.astype(np.float64)[tok]
+    ref = oracle.expert_ffn_bwd(x.astype(np.float64)[tok], G.astype(np.float64), U.astype(np.float64), dY, off,
+                                wg.astype(np.float64), wu.astype(np.float64), wd.astype(np.float64))
+    tdt = torch_dtype(dt)
+    code = m.dtype_code(tdt)
+    ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_FFN_BWD, B, d, E, 1, f, code))
+    dxd = torch.empty((B, d), dtype=tdt, device="cuda")
+    dwg = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
+    dwu, dwd = torch.full_like(dwg, 3.0), torch.full((E, f, d), 3.0, dtype=tdt, device="cuda")
+    m.xmoe_expert_ffn_bwd(to_dev(x, dt), to_dev(G, dt), to_dev(U, dt), to_dev(dout, dt), i32(off), to_dev(wg, dt),
+                          to_dev(wu, dt), to_dev(wd, dt), dxd, dwg, dwu, dwd, ws, row_index=i32(tok),
+                          dy_row_index=i32(tok), dy_row_scale=f32(cw))
+    for got, want, what in zip((dxd, dwg, dwu, dwd), ref, ("dXd", "dWg", "dWu", "dWd")):
+        assert_close(to_host(got), want, dt, what, floor="row" if what == "dXd" else "expert")
+    for e in range(E):
+        if rows[e] == 0:
+            assert not dwg[e].any() and not dwu[e].any() and not dwd[e].any()
+
+
 # ------------------------------------------------------------------------------------------------ whole layer
 def run_layer(cfg, inp, max_token_count=None, fuse_combine_bwd=True):
     m = xm()
