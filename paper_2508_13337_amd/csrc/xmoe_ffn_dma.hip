@@ -740,17 +740,40 @@ struct TileWalker {
     }
 };
 
+#ifndef XMOE_ROW_BAND
+#define XMOE_ROW_BAND 4
+#endif
+constexpr int kRowBand = XMOE_ROW_BAND;   // row tiles per band of the row-GEMM tile numbering
 struct RowTile {
     int e, row0, rows;   // expert, first row, valid rows (1..256)
+    int col;             // column tile
 };
-__device__ __forceinline__ RowTile get_row_tile(const int32_t* __restrict__ map, const int32_t* __restrict__ off,
-                                                int mt) {
-    RowTile t;
-    t.e = map[4 + 2 * mt];
-    t.row0 = map[4 + 2 * mt + 1];
-    const int r = off[t.e + 1] - t.row0;
-    t.rows = r < TM ? r : TM;
-    return t;
+// Tile t of a launch over (row tiles of all experts) x nt column tiles.  An expert's tiles occupy the range of t they
+// have in row-major numbering (row tile * nt + column tile); inside it they are numbered band by band (kRowBand row
+// tiles), and inside a band down the rows first.  The kQueueGroup consecutive tiles that the workgroups of an XCD take
+// together then form a block of about 4 x 4 tiles (8 operand panels for 16 tiles) instead of a strip of one and a half
+// rows (12 to 13 panels), whether the expert has three row tiles or thirty.
+__device__ __forceinline__ RowTile get_tile(const int32_t* __restrict__ map, const int32_t* __restrict__ off, int t,
+                                            int nt) {
+    RowTile r;
+    const int mt = t / nt;
+    r.e = map[4 + 2 * mt];
+    const int lo = off[r.e], hi = off[r.e + 1];
+    if (kRowBand <= 1) {
+        r.row0 = map[4 + 2 * mt + 1];
+        r.col = t - mt * nt;
+    } else {
+        const int mt0 = mt - (map[4 + 2 * mt + 1] - lo) / TM;   // the expert's first row tile
+        const int R = (hi - lo + TM - 1) / TM;                  // its row tiles
+        const int local = t - mt0 * nt;
+        const int band = local / (kRowBand * nt);
+        const int in_band = local - band * kRowBand * nt;
+        const int band_rows = R - band * kRowBand < kRowBand ? R - band * kRowBand : kRowBand;
+        r.col = in_band / band_rows;
+        r.row0 = lo + (band * kRowBand + in_band - r.col * band_rows) * TM;
+    }
+    r.rows = hi - r.row0 < TM ? hi - r.row0 : TM;
+    return r;
 }
 
 __device__ __forceinline__ Operand row_op(const bf16_t* p, long ld, int rows) {
@@ -806,9 +829,9 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
     tw.draw();
-    const RowTile rt = get_row_tile(map, off, t / nt);
+    const RowTile rt = get_tile(map, off, t, nt);
     PROBE_BEGIN(0, t, rt.rows)
-    const int n0 = (t % nt) * 128;
+    const int n0 = rt.col * 128;
     const int ncols = f - n0 < 128 ? f - n0 : 128;
     Operand a = row_op(GATHER ? xd : xd + (long)rt.row0 * d, d, rt.rows);
     if (GATHER) a.gather = row_index + rt.row0;
@@ -881,9 +904,9 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
     tw.draw();
-    const RowTile rt = get_row_tile(map, off, t / nt);
+    const RowTile rt = get_tile(map, off, t, nt);
     PROBE_BEGIN(DACT ? 2 : 1, t, rt.rows)
-    const int n0 = (t % nt) * TN;
+    const int n0 = rt.col * TN;
     const int ncols = N - n0 < TN ? N - n0 : TN;
     Operand a = row_op(DY_GATHER ? X : X + (long)rt.row0 * K, K, rt.rows);
     if (DY_GATHER) a.gather = x_index + rt.row0;
@@ -1025,9 +1048,9 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
     tw.draw();
-    const RowTile rt = get_row_tile(map, off, t / nt);
+    const RowTile rt = get_tile(map, off, t, nt);
     PROBE_BEGIN(3, t, rt.rows)
-    const int n0 = (t % nt) * TN;
+    const int n0 = rt.col * TN;
     const int ncols = d - n0 < TN ? d - n0 : TN;
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
     const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
@@ -1122,8 +1145,8 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
         tw.draw();
-        const RowTile rt = get_row_tile(map, off, t / nt);
-        const int n0 = (t % nt) * TN;
+        const RowTile rt = get_tile(map, off, t, nt);
+        const int n0 = rt.col * TN;
         const int ncols = f - n0 < TN ? f - n0 : TN;
         Operand a = row_op(GATHER ? xd : xd + (long)rt.row0 * d, d, rt.rows);
         if (GATHER) a.gather = row_index + rt.row0;
@@ -1188,8 +1211,8 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
         tw.draw();
-        const RowTile rt = get_row_tile(map, off, t / nt);
-        const int n0 = (t % nt) * TN;
+        const RowTile rt = get_tile(map, off, t, nt);
+        const int n0 = rt.col * TN;
         const int ncols = f - n0 < TN ? f - n0 : TN;
         Operand a = row_op(DY_GATHER ? dY : dY + (long)rt.row0 * d, d, rt.rows);
         if (DY_GATHER) a.gather = dy_index + rt.row0;
