@@ -136,18 +136,18 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 4017192532,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1693180066,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2931516895,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 3154431484,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1510164826,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2871385098,
-    ("large", "ffn_gateup_dma_kernel"): 18260262241,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 9073607719,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9345146472,
-    ("large", "ffn_dx_dma_kernel"): 17539410752,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10219706657,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 17481636355,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3463409620,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1408432662,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2934179163,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2660460069,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1518195874,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2861881569,
+    ("large", "ffn_gateup_dma_kernel"): 18316390495,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 8932319433,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9251261118,
+    ("large", "ffn_dx_dma_kernel"): 17127280665,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10218733859,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17481697790,
 }
 
 
