@@ -82,7 +82,8 @@ def kernel_work(cfg, materialise_dy=False):
     if cfg.expert == "mlp2":
         # the paper's two-matrix expert: four row GEMMs of 2*R*d*f flops and two weight gradients
         R, W = B, E * d * f * s
-        flops = {"up": 2 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 2 * d * rf, "wgrad": 4 * d * rf}
+        flops = {"up": 2 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 2 * d * rf, "wgrad": 4 * d * rf,
+                 "bwd_rest": 6 * d * rf}       # dXd, dW2 and dW1 as one launch
         bytes_ = {
             "combine_kernel": (B + T) * d * s + (B + 2 * T) * d * s,
             "combine_bwd_kernel": (T + (1 + dy_rows) * B) * d * s,
@@ -92,10 +93,12 @@ def kernel_work(cfg, materialise_dy=False):
         gemm_bytes = {"up": R * d * s + W + 2 * R * f * s, "down": R * f * s + W + R * d * s,
                       "dact": R * d * s + W + 3 * R * f * s, "dx": R * f * s + W + R * d * s,
                       "wgrad": 2 * (R * f * s + R * d * s + W)}
+        gemm_bytes["bwd_rest"] = gemm_bytes["dx"] + gemm_bytes["wgrad"]
         bytes_.update({"gemm:" + k_: v for k_, v in gemm_bytes.items()})
         return flops, bytes_
     flops = {"gateup": 4 * d * rf, "down": 2 * d * rf, "dact": 2 * d * rf, "dx": 4 * d * rf, "wgrad": 6 * d * rf,
-             "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf}
+             "wgrad_wd": 2 * d * rf, "wgrad_wg_wu": 4 * d * rf,
+             "bwd_rest": 10 * d * rf}          # dXd, dWd and dWg | dWu as one launch
     bytes_ = {
         # only use left in the layer: the unfused backward (E_s > 0), dout copied to the shared experts' dY rows
         "dispatch_kernel": (T + Ts) * d * s if (Ts and materialise_dy) else 0,
@@ -111,6 +114,7 @@ def kernel_work(cfg, materialise_dy=False):
                   "dact": R * d * s + W + 5 * R * f * s, "dx": 2 * R * f * s + 2 * W + R * d * s,
                   "wgrad_wd": R * f * s + R * d * s + W, "wgrad_wg_wu": R * d * s + 2 * R * f * s + 2 * W}
     gemm_bytes["wgrad"] = gemm_bytes["wgrad_wd"] + gemm_bytes["wgrad_wg_wu"]
+    gemm_bytes["bwd_rest"] = gemm_bytes["dx"] + gemm_bytes["wgrad"]
     bytes_.update({"gemm:" + k_: v for k_, v in gemm_bytes.items()})
     return flops, bytes_
 
@@ -120,6 +124,7 @@ GEMM_WORK = {
     "ffn_gateup_dma_kernel": "gateup", "ffn_rowgemm_dma_kernel<false>": "down",
     "ffn_rowgemm_dma_kernel<true>": "dact", "ffn_dx_dma_kernel": "dx",
     "ffn_wgrad_dma_kernel<false>": "wgrad_wd", "ffn_wgrad_dma_kernel<true>": "wgrad_wg_wu",
+    "ffn_bwd_rest_dma_kernel": "bwd_rest",
 }
 for _fam in ("mfma", "simt"):
     for _k in ("gateup", "down", "dact", "dx", "wgrad"):
@@ -127,7 +132,7 @@ for _fam in ("mfma", "simt"):
 # the two-matrix expert shares the down, dX and weight-gradient kernels (two launches of the latter per step)
 GEMM_WORK_MLP2 = {
     "mlp2_up_dma_kernel": "up", "ffn_rowgemm_dma_kernel<false>": "down", "mlp2_dact_dma_kernel": "dact",
-    "ffn_dx_dma_kernel": "dx", "ffn_wgrad_dma_kernel<false>": "wgrad",
+    "ffn_dx_dma_kernel": "dx", "ffn_wgrad_dma_kernel<false>": "wgrad", "ffn_bwd_rest_dma_kernel": "bwd_rest",
     "mlp2_up_simt_kernel": "up", "ffn_down_simt_kernel": "down", "mlp2_dact_simt_kernel": "dact",
     "ffn_dx_simt_kernel": "dx", "ffn_wgrad_simt_kernel": "wgrad",
 }

@@ -50,6 +50,7 @@ const char* const kKernelNames[K_COUNT] = {
     "ffn_dx_dma_kernel",
     "ffn_wgrad_dma_kernel<false>",
     "ffn_wgrad_dma_kernel<true>",
+    "ffn_bwd_rest_dma_kernel",
     "mlp2_up_simt_kernel",
     "mlp2_dact_simt_kernel",
     "mlp2_up_dma_kernel",

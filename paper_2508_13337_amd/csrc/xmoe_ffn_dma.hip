@@ -19,6 +19,8 @@
 //
 // The MFMA is issued with the operands swapped (B fragment first), so a lane ends up with 4 consecutive output
 // columns of one row; results are rounded to bf16, staged through LDS and written with row-contiguous stores.
+#include <stdlib.h>
+
 #include "xmoe_ffn.h"
 
 namespace xmoe {
@@ -53,7 +55,8 @@ __device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
 // Shader clock under load: workgroup 0 of every launch of this family notes the shader-clock counter and the
 // constant 100 MHz counter when it starts and when it leaves (it is persistent, so that spans the launch); the
 // ratio is the clock the kernel really ran at (xmoe_prof_shader_clock).  One slot per kernel of the family.
-enum ClockSlot { CS_GATEUP = 0, CS_DOWN, CS_DACT, CS_DX, CS_WGRAD, CS_WGRAD_DUAL, CS_MLP2_UP, CS_MLP2_DACT, CS_COUNT };
+enum ClockSlot { CS_GATEUP = 0, CS_DOWN, CS_DACT, CS_DX, CS_WGRAD, CS_WGRAD_DUAL, CS_MLP2_UP, CS_MLP2_DACT, CS_BWD_REST,
+                 CS_COUNT };
 __device__ unsigned long long g_clock_probe[CS_COUNT][4];
 __device__ __forceinline__ void clock_note(int slot, int at_end) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -1036,18 +1039,14 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
 // backward 2: dXd = dG Wg^T + dU Wu^T     (K = f twice, N = d; Wg, Wu [d, f]: rows are output columns)
 // =========================================================================================================
 // TWO = false: a single pair (the two-matrix expert: dXd = dH W1^T), dU and wu are not read
+// one tile of it; t counts (row tiles of all experts) x column tiles
 template <bool TWO>
-__global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restrict__ dG, const bf16_t* __restrict__ dU,
-                                                         const int32_t* __restrict__ off,
-                                                         const int32_t* __restrict__ map, int d, int f,
-                                                         const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
-                                                         bf16_t* __restrict__ dXd, int32_t* __restrict__ counters) {
-    extern __shared__ __align__(16) char smem[];
-    clock_note(CS_DX, 0);
+__device__ __forceinline__ void dx_tile(int t, TileWalker& tw, char* smem, const bf16_t* __restrict__ dG,
+                                        const bf16_t* __restrict__ dU, const int32_t* __restrict__ off,
+                                        const int32_t* __restrict__ map, int d, int f,
+                                        const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
+                                        bf16_t* __restrict__ dXd) {
     const int nt = (d + TN - 1) / TN;
-    TileWalker tw;
-    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
-    tw.draw();
     const RowTile rt = get_tile(map, off, t, nt);
     PROBE_BEGIN(3, t, rt.rows)
     const int n0 = rt.col * TN;
@@ -1083,7 +1082,22 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
         strip_flush<64, true>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
         strip_sync();
     }
-        PROBE_MARK(PROBE_IDX, 3)
+    PROBE_MARK(PROBE_IDX, 3)
+}
+
+template <bool TWO>
+__global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restrict__ dG, const bf16_t* __restrict__ dU,
+                                                         const int32_t* __restrict__ off,
+                                                         const int32_t* __restrict__ map, int d, int f,
+                                                         const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
+                                                         bf16_t* __restrict__ dXd, int32_t* __restrict__ counters) {
+    extern __shared__ __align__(16) char smem[];
+    clock_note(CS_DX, 0);
+    const int nt = (d + TN - 1) / TN;
+    TileWalker tw;
+    for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
+        tw.draw();
+        dx_tile<TWO>(t, tw, smem, dG, dU, off, map, d, f, wg, wu, dXd);
     }
     clock_note(CS_DX, 1);
 }
@@ -1299,25 +1313,17 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
 // =========================================================================================================
 // GATHER: P is a [T, M] matrix and row r of the expert's P is P[row_index[lo + r]].  QGATHER (not with DUAL): the
 // same for Q1 through q_index (the gradient of the layer's output standing in for the rows of dY).
-template <bool DUAL, bool GATHER, bool QGATHER = false>
-__global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P,
-                                                            const int32_t* __restrict__ row_index,
-                                                            const bf16_t* __restrict__ Q1,
-                                                            const bf16_t* __restrict__ Q2,
-                                                            const int32_t* __restrict__ q_index,
-                                                            const int32_t* __restrict__ row_index_dma,
-                                                            const int32_t* __restrict__ q_index_dma,
-                                                            const int32_t* __restrict__ off,
-                                                            const int32_t* __restrict__ order,
-                                                            int32_t* __restrict__ counters, int E, int M, int N,
-                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
-    extern __shared__ __align__(16) char smem[];
-    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 0);
+// one tile of it; t counts experts (in the order of `order`) x row tiles x column tiles
+template <bool DUAL, bool GATHER, bool QGATHER>
+__device__ __forceinline__ void wgrad_tile(int t, TileWalker& tw, char* smem, const bf16_t* __restrict__ P,
+                                           const int32_t* __restrict__ row_index, const bf16_t* __restrict__ Q1,
+                                           const bf16_t* __restrict__ Q2, const int32_t* __restrict__ q_index,
+                                           const int32_t* __restrict__ row_index_dma,
+                                           const int32_t* __restrict__ q_index_dma, const int32_t* __restrict__ off,
+                                           const int32_t* __restrict__ order, int M, int N,
+                                           bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
-    TileWalker tw;
-    for (int t = tw.start(counters, E * mt * nt, smem); t >= 0; t = tw.next()) {
-    tw.draw();
     const int e = order[t / (mt * nt)];
     // Inside an expert the tiles are numbered band by band (kWgradBand tile rows), down the columns of a band, so
     // that the kQueueGroup consecutive tiles a group of workgroups takes form a 2 x 8 block of tiles rather than a
@@ -1382,9 +1388,74 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         }
         strip_sync();
     }
-PROBE_MARK(PROBE_IDX, 3)
+    PROBE_MARK(PROBE_IDX, 3)
+}
+
+template <bool DUAL, bool GATHER, bool QGATHER = false>
+__global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __restrict__ P,
+                                                            const int32_t* __restrict__ row_index,
+                                                            const bf16_t* __restrict__ Q1,
+                                                            const bf16_t* __restrict__ Q2,
+                                                            const int32_t* __restrict__ q_index,
+                                                            const int32_t* __restrict__ row_index_dma,
+                                                            const int32_t* __restrict__ q_index_dma,
+                                                            const int32_t* __restrict__ off,
+                                                            const int32_t* __restrict__ order,
+                                                            int32_t* __restrict__ counters, int E, int M, int N,
+                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
+    extern __shared__ __align__(16) char smem[];
+    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 0);
+    constexpr int NB = DUAL ? 128 : TN;
+    const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
+    TileWalker tw;
+    for (int t = tw.start(counters, E * mt * nt, smem); t >= 0; t = tw.next()) {
+        tw.draw();
+        wgrad_tile<DUAL, GATHER, QGATHER>(t, tw, smem, P, row_index, Q1, Q2, q_index, row_index_dma, q_index_dma, off,
+                                          order, M, N, dW1, dW2);
     }
     clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 1);
+}
+
+// =========================================================================================================
+// backward of the SwiGLU expert after dG, dU and A exist: dXd, dWd and dWg | dWu in ONE launch.  The three GEMMs
+// are independent of each other, so a workgroup that finds dXd's tile queue empty goes straight on to dWd's and
+// then to dWg | dWu's (each from the largest expert down) instead of idling until the launch ends: two of three
+// launch tails and two launch gaps disappear.  The three walks are separate loops, each with the counters it has
+// as a launch of its own, so each keeps the register allocation of its own kernel.
+// =========================================================================================================
+// SWIGLU = false: the two-matrix expert (dXd = dH W1^T, dW2 = A^T dY, dW1 = Xd^T dH; dG stands for dH, wg for W1,
+// dWg for dW1; dU, wu and dWu are not used)
+template <bool SWIGLU, bool GATHER, bool DY_GATHER>
+__global__ __launch_bounds__(512) void ffn_bwd_rest_dma_kernel(
+    const bf16_t* __restrict__ dG, const bf16_t* __restrict__ dU, const bf16_t* __restrict__ act,
+    const bf16_t* __restrict__ dY, const int32_t* __restrict__ dy_index, const int32_t* __restrict__ dy_index_dma,
+    const bf16_t* __restrict__ xd, const int32_t* __restrict__ row_index, const int32_t* __restrict__ row_index_dma,
+    const int32_t* __restrict__ off, const int32_t* __restrict__ map, const int32_t* __restrict__ order,
+    int32_t* __restrict__ cnt_dx, int32_t* __restrict__ cnt_wd, int32_t* __restrict__ cnt_wgu, int E, int d, int f,
+    const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu, bf16_t* __restrict__ dXd, bf16_t* __restrict__ dWd,
+    bf16_t* __restrict__ dWg, bf16_t* __restrict__ dWu) {
+    extern __shared__ __align__(16) char smem[];
+    clock_note(CS_BWD_REST, 0);
+    TileWalker tw;
+    for (int t = tw.start(cnt_dx, map[0] * ((d + TN - 1) / TN), smem); t >= 0; t = tw.next()) {
+        tw.draw();
+        dx_tile<SWIGLU>(t, tw, smem, dG, dU, off, map, d, f, wg, wu, dXd);
+    }
+    // a walk's start writes the hand-over slot that the last next() of the walk before it has just read
+    __syncthreads();
+    for (int t = tw.start(cnt_wd, E * ((f + TM - 1) / TM) * ((d + TN - 1) / TN), smem); t >= 0; t = tw.next()) {
+        tw.draw();
+        wgrad_tile<false, false, DY_GATHER>(t, tw, smem, act, nullptr, dY, nullptr, dy_index, nullptr, dy_index_dma,
+                                            off, order, f, d, dWd, nullptr);
+    }
+    __syncthreads();
+    constexpr int NB = SWIGLU ? 128 : TN;
+    for (int t = tw.start(cnt_wgu, E * ((d + TM - 1) / TM) * ((f + NB - 1) / NB), smem); t >= 0; t = tw.next()) {
+        tw.draw();
+        wgrad_tile<SWIGLU, GATHER, false>(t, tw, smem, xd, row_index, dG, dU, nullptr, row_index_dma, nullptr, off,
+                                          order, d, f, dWg, dWu);
+    }
+    clock_note(CS_BWD_REST, 1);
 }
 
 // =========================================================================================================
@@ -1400,6 +1471,17 @@ bool ffn_dma_supported(const FfnArgs& a) {
 }
 
 static int g_num_cu = 0;
+
+// The backward's three independent GEMMs run as one launch unless the environment variable XMOE_BWD_MERGE is 0
+// (for comparisons and for the per-kernel profiles).
+static bool bwd_merged() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("XMOE_BWD_MERGE");
+        v = (e && e[0] == '0') ? 0 : 1;
+    }
+    return v == 1;
+}
 
 // the work counters of a call's i-th row-GEMM launch (the schedule block holds, behind the sorted experts, kNumXcd
 // counters for each of the two weight-gradient launches and then for each of the two row-GEMM launches)
@@ -1436,6 +1518,14 @@ static int init_once() {
         if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false, true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, true>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, false>);
+        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, true>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<false>);
         if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, true>);
         if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_IDENTITY>);
@@ -1507,11 +1597,30 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                                        dim3(512), kLdsBytes, s, dy, nullptr, nullptr, a.off, a.map, a.d, a.f, wd,
                                        nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
                                        row_counters(a.sched, a.E, 0)));
+    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
+    const int ntf2 = (a.f + 127) / 128;
+    if (bwd_merged()) {
+        // dXd, dWd, dWg | dWu: one launch
+        const long tiles = (long)max_tiles * ntd + (long)a.E * mtf * ntd + (long)a.E * mtd * ntf2;
+        const dim3 grid(round_up8(tiles));
+#define XMOE_REST(G, DYG)                                                                                             \
+    XMOE_LAUNCH(K_FFN_BWD_REST_DMA, s,                                                                                \
+                hipLaunchKernelGGL((ffn_bwd_rest_dma_kernel<true, G, DYG>), grid, dim3(512), kLdsBytes, s, dg, du,    \
+                                   act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off, a.map,       \
+                                   a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E, a.sched + a.E + kNumXcd,    \
+                                   a.E, a.d, a.f, wg, wu, (bf16_t*)a.dxd, (bf16_t*)a.dwd, (bf16_t*)a.dwg,             \
+                                   (bf16_t*)a.dwu))
+        if (a.row_index && a.dy_index) XMOE_REST(true, true);
+        else if (a.row_index) XMOE_REST(true, false);
+        else if (a.dy_index) XMOE_REST(false, true);
+        else XMOE_REST(false, false);
+#undef XMOE_REST
+        return XMOE_OK;
+    }
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
                                    du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd, row_counters(a.sched, a.E, 1)));
     // dWd [f, d] = A^T dY
-    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     if (a.dy_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
@@ -1526,7 +1635,6 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                                        a.sched,
                                        a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
-    const int ntf2 = (a.f + 127) / 128;
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
@@ -1612,12 +1720,30 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     }
+    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
+    if (bwd_merged()) {
+        // dXd, dW2, dW1: one launch
+        const long tiles = (long)max_tiles * ntd + (long)a.E * mtf * ntd + (long)a.E * mtd * ntf;
+        const dim3 grid_rest(round_up8(tiles));
+#define XMOE_REST(G, DYG)                                                                                             \
+    XMOE_LAUNCH(K_FFN_BWD_REST_DMA, s,                                                                                \
+                hipLaunchKernelGGL((ffn_bwd_rest_dma_kernel<false, G, DYG>), grid_rest, dim3(512), kLdsBytes, s, dh,  \
+                                   nullptr, act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off,     \
+                                   a.map, a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E,                      \
+                                   a.sched + a.E + kNumXcd, a.E, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,               \
+                                   (bf16_t*)a.dw2, (bf16_t*)a.dw1, nullptr))
+        if (a.row_index && a.dy_index) XMOE_REST(true, true);
+        else if (a.row_index) XMOE_REST(true, false);
+        else if (a.dy_index) XMOE_REST(false, true);
+        else XMOE_REST(false, false);
+#undef XMOE_REST
+        return XMOE_OK;
+    }
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,
                                    row_counters(a.sched, a.E, 1)));
     // dW2 [f, d] = A^T dY
-    const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     if (a.dy_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
@@ -1658,6 +1784,7 @@ extern "C" int xmoe_prof_shader_clock(int kernel_id, double* ghz) {
         case xmoe::K_FFN_DX_DMA: slot = xmoe::CS_DX; break;
         case xmoe::K_FFN_WGRAD_DMA: slot = xmoe::CS_WGRAD; break;
         case xmoe::K_FFN_WGRAD_DUAL_DMA: slot = xmoe::CS_WGRAD_DUAL; break;
+        case xmoe::K_FFN_BWD_REST_DMA: slot = xmoe::CS_BWD_REST; break;
         case xmoe::K_MLP2_UP_DMA: slot = xmoe::CS_MLP2_UP; break;
         case xmoe::K_MLP2_DACT_DMA: slot = xmoe::CS_MLP2_DACT; break;
         default: break;

@@ -42,6 +42,7 @@ enum KernelId : int {
     K_FFN_DX_DMA,
     K_FFN_WGRAD_DMA,
     K_FFN_WGRAD_DUAL_DMA,
+    K_FFN_BWD_REST_DMA,
     K_MLP2_UP_SIMT,
     K_MLP2_DACT_SIMT,
     K_MLP2_UP_DMA,

@@ -5,6 +5,9 @@ point outputs must stay within the benchmark definition's tolerance (max relativ
 workloads, 2e-2 for bf16 with float32 accumulation; relative error floored at the tensor's RMS).
 All calls go through the ctypes binding, i.e. through the C ABI."""
 import functools
+import os
+import subprocess
+import sys
 
 import numpy as np
 import pytest
@@ -394,14 +397,42 @@ def test_expert_ffn_bwd_long_ragged_segments(rows):
     dxd = torch.empty((B, d), dtype=tdt, device="cuda")
     dwg = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
     dwu, dwd = torch.full_like(dwg, 3.0), torch.full((E, f, d), 3.0, dtype=tdt, device="cuda")
+    m.xmoe_prof_reset()
+    m.xmoe_prof_enable(True)
     m.xmoe_expert_ffn_bwd(to_dev(x, dt), to_dev(G, dt), to_dev(U, dt), to_dev(dout, dt), i32(off), to_dev(wg, dt),
                           to_dev(wu, dt), to_dev(wd, dt), dxd, dwg, dwu, dwd, ws, row_index=i32(tok),
                           dy_row_index=i32(tok), dy_row_scale=f32(cw))
+    torch.cuda.synchronize()
+    launched = set(m.xmoe_prof_read())
+    m.xmoe_prof_enable(False)
+    m.xmoe_prof_reset()
+    # dXd, dWd and dWg | dWu run as one launch unless XMOE_BWD_MERGE=0 asks for three
+    if os.environ.get("XMOE_BWD_MERGE", "1")[:1] == "0":
+        assert {"ffn_dx_dma_kernel", "ffn_wgrad_dma_kernel<false>", "ffn_wgrad_dma_kernel<true>"} <= launched
+    else:
+        assert "ffn_bwd_rest_dma_kernel" in launched and "ffn_dx_dma_kernel" not in launched
     for got, want, what in zip((dxd, dwg, dwu, dwd), ref, ("dXd", "dWg", "dWu", "dWd")):
         assert_close(to_host(got), want, dt, what, floor="row" if what == "dXd" else "expert")
     for e in range(E):
         if rows[e] == 0:
             assert not dwg[e].any() and not dwu[e].any() and not dwd[e].any()
+
+
+def test_expert_ffn_bwd_as_separate_launches():
+    """The library reads XMOE_BWD_MERGE once per process, so the three-launch form of the backward runs the same
+    parity cases in a child process (which checks, through the launch profiler, that it did take that form)."""
+    if os.environ.get("XMOE_BWD_MERGE", "1")[:1] == "0":
+        pytest.skip("already the separate-launch form")
+    env = dict(os.environ, XMOE_BWD_MERGE="0")
+    here = os.path.dirname(os.path.abspath(__file__))
+    r = subprocess.run([sys.executable, "-u", "-m", "pytest", os.path.abspath(__file__),
+                        os.path.join(here, "test_gpu_mlp2.py"), "-x", "-q", "-m", "gpu", "-p", "no:cacheprovider", "-k",
+                        "test_expert_ffn_fwd_bwd or test_expert_ffn_bwd_long_ragged_segments or "
+                        "test_expert_mlp2_fwd_bwd"],
+                       env=env, capture_output=True, text=True, timeout=900,
+                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert r.returncode == 0, r.stdout[-4000:] + r.stderr[-2000:]
+    assert " passed" in r.stdout and "skipped" not in r.stdout.splitlines()[-1], r.stdout[-500:]
 
 
 # ------------------------------------------------------------------------------------------------ whole layer
