@@ -141,18 +141,21 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3463409620,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1408432662,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2934179163,
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2660460069,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1518195874,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2861881569,
-    ("large", "ffn_gateup_dma_kernel"): 18316390495,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 8932319433,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9251261118,
-    ("large", "ffn_dx_dma_kernel"): 17127280665,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10218733859,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 17481697790,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3444187918,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1423689044,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2955591757,
+    ("dsmoe16b", "ffn_bwd_rest_dma_kernel"): 7839695896,
+    ("large", "ffn_gateup_dma_kernel"): 18287137751,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 8916750508,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9350526837,
+    ("large", "ffn_bwd_rest_dma_kernel"): 45162765590,
+    # with XMOE_BWD_MERGE=0 (the backward's last three GEMMs as launches of their own)
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2670333736,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1522013388,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2858494165,
+    ("large", "ffn_dx_dma_kernel"): 17161058560,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10219957502,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17481456590,
 }
 
 
