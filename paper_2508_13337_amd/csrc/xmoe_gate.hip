@@ -106,6 +106,96 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(const T* __restrict__ 
     }
 }
 
+// The same sums for bf16 operands whose rows are 16-byte aligned and d % 64 == 0, with the operands staged through
+// LDS.  In the kernel above a wave's load of w touches 64 different 128-byte lines for 1 KiB of data (lane l reads
+// 16 bytes of row l), four waves of a block do that side by side, and every wave fetches the same x values again: the
+// L1, not the float32 pipe, sets the pace.  Here the block fetches each 64-row chunk of w (its 32 experts: 64 bytes
+// per row) and of x (its 8 tokens) once, coalesced, a chunk ahead through registers, and a lane reads its row of w
+// and its 8 token values with two 16-byte LDS reads.  Work split, accumulation order and the fold are those of the
+// kernel above, so the results are the same bits.
+constexpr int kGWStride = 80;   // bytes per staged row of w: 4 x 16 bytes + 16 bytes of padding
+
+__global__ __launch_bounds__(256) void gate_logits_lds_kernel(const bf16_t* __restrict__ x,
+                                                              const bf16_t* __restrict__ w,
+                                                              const float* __restrict__ bias,
+                                                              float* __restrict__ logits, int Tn, int d, int E) {
+    __shared__ __align__(16) char sw[2][64 * kGWStride];   // [i][32 experts]
+    __shared__ __align__(16) char sx[2][64 * 16];          // [i][8 tokens]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * kGT;
+    const int eb = blockIdx.y * 4 * kGE;
+    // staging roles: w row tid/4, 16-byte piece tid%4;  x token tid/32, elements 2*(tid%32) and the next
+    const int wr = tid >> 2, wpiece = tid & 3;
+    const bool w_ok = eb + kGE * wpiece < E;
+    const int xt = tid >> 5, xi = 2 * (tid & 31);
+    int tok = t0 + xt;
+    tok = tok < Tn ? tok : Tn - 1;
+    const bf16_t* xp = x + (size_t)tok * d + xi;
+    const bf16_t* wp = w + (size_t)wr * E + eb + kGE * wpiece;
+    uint4 wq = make_uint4(0, 0, 0, 0);
+    uint32_t xq;
+    auto fetch = [&](int i0) {
+        if (w_ok) wq = *reinterpret_cast<const uint4*>(wp + (size_t)i0 * E);
+        xq = *reinterpret_cast<const uint32_t*>(xp + i0);
+    };
+    auto stage = [&](int buf) {
+        *reinterpret_cast<uint4*>(sw[buf] + wr * kGWStride + wpiece * 16) = wq;
+        *reinterpret_cast<uint16_t*>(sx[buf] + xi * 16 + xt * 2) = (uint16_t)(xq & 0xffffu);
+        *reinterpret_cast<uint16_t*>(sx[buf] + (xi + 1) * 16 + xt * 2) = (uint16_t)(xq >> 16);
+    };
+
+    float acc[kGT * kGE];
+#pragma unroll
+    for (int v = 0; v < kGT * kGE; ++v) acc[v] = 0.0f;
+
+    const int chunks = d / 64;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int c = 0; c < chunks; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < chunks) fetch((c + 1) * 64);
+        const uint4 wv4 = *reinterpret_cast<const uint4*>(sw[buf] + lane * kGWStride + wave * 16);
+        const uint4 xv4 = *reinterpret_cast<const uint4*>(sx[buf] + lane * 16);
+        const uint32_t wu[4] = {wv4.x, wv4.y, wv4.z, wv4.w}, xu[4] = {xv4.x, xv4.y, xv4.z, xv4.w};
+        float wv[kGE], xv[kGT];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            wv[2 * j] = __uint_as_float(wu[j] << 16);
+            wv[2 * j + 1] = __uint_as_float(wu[j] & 0xffff0000u);
+            xv[2 * j] = __uint_as_float(xu[j] << 16);
+            xv[2 * j + 1] = __uint_as_float(xu[j] & 0xffff0000u);
+        }
+#pragma unroll
+        for (int tt = 0; tt < kGT; ++tt)
+#pragma unroll
+            for (int ee = 0; ee < kGE; ++ee) acc[tt * kGE + ee] = fmaf(xv[tt], wv[ee], acc[tt * kGE + ee]);
+        if (c + 1 < chunks) stage(buf ^ 1);
+        // the chunk staged above is read after this barrier, and the buffer it went to was last read before the
+        // barrier of the previous round
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int width = 32; width >= 1; width >>= 1) {
+        const bool upper = (lane & width) != 0;
+#pragma unroll
+        for (int v = 0; v < width; ++v) {
+            float send = upper ? acc[v] : acc[v + width];
+            float keep = upper ? acc[v + width] : acc[v];
+            float recv = __shfl_xor(send, width, 64);
+            acc[v] = keep + recv;
+        }
+    }
+    const int t = t0 + (lane / kGE);
+    const int e = eb + wave * kGE + (lane % kGE);
+    if (t < Tn && e < E) {
+        float v = acc[0];
+        if (bias) v = v + bias[e];
+        logits[(size_t)t * E + e] = v;
+    }
+}
+
 // =========================================================================================================
 // softmax + top-k: one wave per token
 // =========================================================================================================
@@ -450,6 +540,12 @@ static int launch_gate_logits(const void* x, const void* w, const float* bias, f
                               int E, hipStream_t s) {
     int vec = (E % kGE == 0) && aligned16(w) && ((E * sizeof(T)) % 16 == 0);
     dim3 grid((Tn + kGT - 1) / kGT, (E + 4 * kGE - 1) / (4 * kGE));
+    if (sizeof(T) == 2 && vec && d % 64 == 0 && (reinterpret_cast<uintptr_t>(x) & 3u) == 0) {
+        XMOE_LAUNCH(K_GATE_LOGITS, s,
+                    hipLaunchKernelGGL(gate_logits_lds_kernel, grid, dim3(256), 0, s, (const bf16_t*)x,
+                                       (const bf16_t*)w, bias, logits, Tn, d, E));
+        return XMOE_OK;
+    }
     XMOE_LAUNCH(K_GATE_LOGITS, s,
                 hipLaunchKernelGGL(gate_logits_kernel<T>, grid, dim3(256), 0, s, (const T*)x, (const T*)w, bias,
                                    logits, Tn, d, E, vec));
