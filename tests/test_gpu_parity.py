@@ -60,6 +60,23 @@ def test_gate_logits_bit_exact(name):
     assert bits_equal(logits, want)
 
 
+@pytest.mark.parametrize("T,d,E,bias", [(13, 64, 8, False), (9, 64, 24, True), (257, 128, 40, True),
+                                         (100, 192, 72, False), (64, 1024, 256, True), (8, 4096, 32, False)])
+def test_gate_logits_staged_kernel_edge_shapes(T, d, E, bias):
+    """bf16 operands with d % 64 == 0 and E % 8 == 0 take the kernel that stages its operands through LDS: token counts
+    that are not a multiple of a wave's 8, expert counts that do not fill a block's 32 (or need several blocks), one
+    chunk and many chunks of d - against the contract, bit for bit."""
+    rng = np.random.default_rng(T * 1000 + d + E)
+    x = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), "bf16")
+    w = xi.round_to_storage((rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32), "bf16")
+    b = rng.standard_normal(E).astype(np.float32) if bias else None
+    want = oracle.gate_logits_contract(x, w, b)
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    xm().xmoe_gate_logits(to_dev(x, "bf16"), to_dev(w, "bf16"), None if b is None else f32(b), logits)
+    torch.cuda.synchronize()
+    assert bits_equal(logits, want)
+
+
 ROUTE_CASES = [(256, 8, 2, 0, 1.0), (1000, 64, 6, 1, 1.0), (513, 256, 8, 2, 1.0), (77, 7, 3, 3, 1.0),
                (300, 512, 8, 4, 1.0), (64, 5, 5, 5, 1.0), (10, 1, 1, 6, 1.0), (129, 130, 64, 7, 3.0)]
 
