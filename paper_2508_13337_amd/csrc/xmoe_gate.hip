@@ -535,6 +535,214 @@ __global__ __launch_bounds__(256) void gate_bwd_dx_kernel(const float* __restric
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The same two products for bf16 operands on the bf16 matrix instruction (16 summands per instruction and operand
+// row instead of 2).  x and w are bf16 as stored; dlogits is float32 and goes in as the sum of two bf16 terms,
+// hi = bf16(v) and lo = bf16(v - hi), i.e. with 16 significant bits: every product is exact in float32, the sums are
+// float32, and what is dropped (2^-17 of a term) is far below the bf16 rounding of the results.
+// Used when d % 64 == 0, E % 64 == 0 and the operands are 16-byte aligned; otherwise the kernels above.
+// ---------------------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 gate_bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short gate_s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short gate_s16x8_t;
+
+// v[0..7] -> hi and lo as packed bf16 pairs
+__device__ __forceinline__ void split_bf16x8(const float (&v)[8], uint4& hi, uint4& lo) {
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        h[q] = pack_bf16x2(v[2 * q], v[2 * q + 1]);
+        const float r0 = v[2 * q] - __uint_as_float(h[q] << 16);
+        const float r1 = v[2 * q + 1] - __uint_as_float(h[q] & 0xffff0000u);
+        l[q] = pack_bf16x2(r0, r1);
+    }
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
+// partial[s][i][e] = sum over the s-th slice of tokens of x[t,i] * dlogits[t,e].  Both operands are stored
+// token-major while the instruction wants 8 consecutive tokens per lane, so a block stages 64 tokens x (64 columns i
+// of x, 64 experts of dlogits as hi and lo) in LDS as they lie in memory and takes its operands with the
+// transposing LDS read.  Four waves: one 32 x 32 block of the 64 x 64 output each.  grid = (d/64, E/64, splits).
+constexpr int kDwTok = 64;
+constexpr int kDwStride = 144;   // bytes per staged token row: 64 bf16 + 16 bytes of padding
+
+// operand for v_mfma_f32_32x32x16_bf16 from a token-major tile: column col_base + lane%32, tokens
+// 16*ks + 8*(lane/32) .. +7.  In a group of 16 lanes, lane s addresses 4 consecutive columns (s%4) of token row
+// (s/4); the transposing read hands every lane one column with 4 consecutive tokens.
+__device__ __forceinline__ gate_bf16x8_t dw_frag(const char* tile, int col_base, int ks) {
+    const int lane = threadIdx.x & 63;
+    const int G = lane >> 4, s = lane & 15;
+    const int col = col_base + 16 * (G & 1) + 4 * (s & 3);
+    const int k0 = 16 * ks + 8 * (G >> 1) + (s >> 2);
+    gate_s16x4_t h[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const char* a = tile + (k0 + 4 * q) * kDwStride + col * 2;
+        h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) gate_s16x4_t*)(
+            (__attribute__((address_space(3))) void*)a));
+    }
+    const gate_s16x8_t v = {h[0][0], h[0][1], h[0][2], h[0][3], h[1][0], h[1][1], h[1][2], h[1][3]};
+    return __builtin_bit_cast(gate_bf16x8_t, v);
+}
+
+__global__ __launch_bounds__(256) void gate_bwd_dw_mfma_kernel(const bf16_t* __restrict__ x,
+                                                               const float* __restrict__ dl,
+                                                               float* __restrict__ partial, int Tn, int d, int E,
+                                                               int t_per_split) {
+    __shared__ __align__(16) char xs[kDwTok * kDwStride];
+    __shared__ __align__(16) char dhi[kDwTok * kDwStride];
+    __shared__ __align__(16) char dlo[kDwTok * kDwStride];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i0 = blockIdx.x * 64, e0 = blockIdx.y * 64;
+    const int tb = blockIdx.z * t_per_split;
+    int te = tb + t_per_split;
+    te = te < Tn ? te : Tn;
+    const int mi = wave >> 1, ni = wave & 1;
+    // staging: token rows tid/8 and tid/8 + 32 of a chunk; 8 columns of x (16 bytes) and 8 experts of dlogits each
+    const int sr = tid >> 3, sp = tid & 7;
+    uint4 xr[2];
+    float4 dr[2][2];
+    auto fetch = [&](int t0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int t = t0 + sr + 32 * j;
+            xr[j] = make_uint4(0, 0, 0, 0);
+            dr[j][0] = dr[j][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < te) {
+                xr[j] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + i0 + sp * 8);
+                const float4* p = reinterpret_cast<const float4*>(dl + (size_t)t * E + e0 + sp * 8);
+                dr[j][0] = p[0];
+                dr[j][1] = p[1];
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int o = (sr + 32 * j) * kDwStride + sp * 16;
+            const float v[8] = {dr[j][0].x, dr[j][0].y, dr[j][0].z, dr[j][0].w,
+                                dr[j][1].x, dr[j][1].y, dr[j][1].z, dr[j][1].w};
+            uint4 hi, lo;
+            split_bf16x8(v, hi, lo);
+            *reinterpret_cast<uint4*>(xs + o) = xr[j];
+            *reinterpret_cast<uint4*>(dhi + o) = hi;
+            *reinterpret_cast<uint4*>(dlo + o) = lo;
+        }
+    };
+    gate_f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    if (tb < te) fetch(tb);
+    for (int t0 = tb; t0 < te; t0 += kDwTok) {
+        stage();
+        __syncthreads();
+        if (t0 + kDwTok < te) fetch(t0 + kDwTok);   // in flight while this chunk is multiplied
+#pragma unroll
+        for (int ks = 0; ks < kDwTok / 16; ++ks) {
+            const gate_bf16x8_t a = dw_frag(xs, 32 * mi, ks);
+            const gate_bf16x8_t bh = dw_frag(dhi, 32 * ni, ks);
+            const gate_bf16x8_t bl = dw_frag(dlo, 32 * ni, ks);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bh, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bl, acc, 0, 0, 0);
+        }
+        __syncthreads();   // everybody is done reading before the next chunk is staged
+    }
+    float* out = partial + (size_t)blockIdx.z * d * E;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int i = i0 + 32 * mi + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int e = e0 + 32 * ni + (lane & 31);
+        out[(size_t)i * E + e] = acc[v];
+    }
+}
+
+// dx_gate[t,i] = sum_e dlogits[t,e] * w[i,e]: e is contiguous in both operands, so a lane takes its 8 consecutive
+// experts straight from memory (dlogits: 8 floats -> hi, lo; w: 16 bytes).  One wave: 32 tokens x kDxCols columns.
+// The wave's rows of dlogits are fetched and split once per 64 experts: for E == 64 they stay in registers across the
+// column blocks; for larger E the chunks of 64 experts are the outer loop and the kDxCols / 32 column blocks keep
+// an accumulator each.  (Fewer columns per wave, i.e. more and shorter waves, is slower: 64 columns 32 us against 26
+// at config 2 - fetching and splitting the rows of dlogits costs more than short waves hide.)
+// w is the instruction's first operand: the result block is [column i][token], so that a lane ends up with runs of 4
+// consecutive columns of one token row and stores 8 bytes at a time.
+constexpr int kDxColsManyExperts = 128;   // E > 64: four accumulators per wave (eight leave one wave per SIMD)
+template <bool ONE_CHUNK>
+__global__ __launch_bounds__(256) void gate_bwd_dx_mfma_kernel(const float* __restrict__ dl,
+                                                               const bf16_t* __restrict__ w,
+                                                               bf16_t* __restrict__ dxg, int Tn, int d, int E) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t0 = (blockIdx.x * 4 + wave) * 32;
+    if (t0 >= Tn) return;
+    const int h = lane >> 5, c = lane & 31;
+    // columns per wave; d % 64 == 0, so every 32-column block below is complete
+    constexpr int COLS = ONE_CHUNK ? kDxCols : kDxColsManyExperts;
+    const int ibeg = blockIdx.y * COLS;
+    const int iend = ibeg + COLS < d ? ibeg + COLS : d;
+    const bool ok_t = t0 + c < Tn;
+    const float* arow = dl + (size_t)(ok_t ? t0 + c : 0) * E + 8 * h;
+    uint4 ah[4], al[4];
+    auto load_a = [&](int e0) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (ok_t) {
+                const float4* p = reinterpret_cast<const float4*>(arow + e0 + 16 * ks);
+                const float4 f0 = p[0], f1 = p[1];
+                v[0] = f0.x; v[1] = f0.y; v[2] = f0.z; v[3] = f0.w;
+                v[4] = f1.x; v[5] = f1.y; v[6] = f1.z; v[7] = f1.w;
+            }
+            split_bf16x8(v, ah[ks], al[ks]);
+        }
+    };
+    auto multiply = [&](int i0, int e0, gate_f32x16_t& acc) {
+        const bf16_t* brow = w + (size_t)(i0 + c) * E + 8 * h + e0;
+        uint4 b[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) b[ks] = *reinterpret_cast<const uint4*>(brow + 16 * ks);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const gate_bf16x8_t bb = __builtin_bit_cast(gate_bf16x8_t, b[ks]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, __builtin_bit_cast(gate_bf16x8_t, ah[ks]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, __builtin_bit_cast(gate_bf16x8_t, al[ks]), acc, 0, 0, 0);
+        }
+    };
+    // lane (h, c): token t0 + c, columns i0 + 8j + 4h .. +3 in acc[4j .. 4j+3]
+    auto store = [&](int i0, const gate_f32x16_t& acc) {
+        if (!ok_t) return;
+        bf16_t* orow = dxg + (size_t)(t0 + c) * d + i0 + 4 * h;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<uint2*>(orow + 8 * j) =
+                make_uint2(pack_bf16x2(acc[4 * j], acc[4 * j + 1]), pack_bf16x2(acc[4 * j + 2], acc[4 * j + 3]));
+    };
+    if (ONE_CHUNK) {
+        load_a(0);
+        for (int i0 = ibeg; i0 < iend; i0 += 32) {
+            gate_f32x16_t acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            multiply(i0, 0, acc);
+            store(i0, acc);
+        }
+    } else {
+        constexpr int NB = COLS / 32;
+        gate_f32x16_t acc[NB];
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+        for (int e0 = 0; e0 < E; e0 += 64) {
+            load_a(e0);
+#pragma unroll
+            for (int n = 0; n < NB; ++n)
+                if (ibeg + 32 * n < iend) multiply(ibeg + 32 * n, e0, acc[n]);
+        }
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+            if (ibeg + 32 * n < iend) store(ibeg + 32 * n, acc[n]);
+    }
+}
+
 template <typename T>
 static int launch_gate_logits(const void* x, const void* w, const float* bias, float* logits, int Tn, int d,
                               int E, hipStream_t s) {
@@ -558,6 +766,28 @@ static int launch_gate_bwd(const void* x, const void* w, const float* dl, int Tn
     const int splits = gate_bwd_splits(Tn);
     const int tps = (Tn + splits - 1) / splits;
     dim3 g1((d + 63) / 64, (E + 63) / 64, splits);
+    if (sizeof(T) == 2 && d % 64 == 0 && E % 64 == 0 && aligned16(x) && aligned16(w) && aligned16(dl) &&
+        aligned16(dxg)) {
+        XMOE_LAUNCH(K_GATE_BWD_DW, s,
+                    hipLaunchKernelGGL(gate_bwd_dw_mfma_kernel, g1, dim3(256), 0, s, (const bf16_t*)x, dl, partial, Tn,
+                                       d, E, tps));
+        const size_t n_ = (size_t)d * E;
+        XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, s,
+                    hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<T>, dim3((unsigned)((n_ + 255) / 256)), dim3(256), 0,
+                                       s, partial, splits, n_, (T*)dwr));
+        if (E == 64) {
+            dim3 g2m((Tn + 127) / 128, (d + kDxCols - 1) / kDxCols);
+            XMOE_LAUNCH(K_GATE_BWD_DX, s,
+                        hipLaunchKernelGGL(gate_bwd_dx_mfma_kernel<true>, g2m, dim3(256), 0, s, dl, (const bf16_t*)w,
+                                           (bf16_t*)dxg, Tn, d, E));
+        } else {
+            dim3 g2m((Tn + 127) / 128, (d + kDxColsManyExperts - 1) / kDxColsManyExperts);
+            XMOE_LAUNCH(K_GATE_BWD_DX, s,
+                        hipLaunchKernelGGL(gate_bwd_dx_mfma_kernel<false>, g2m, dim3(256), 0, s, dl, (const bf16_t*)w,
+                                           (bf16_t*)dxg, Tn, d, E));
+        }
+        return XMOE_OK;
+    }
     const int vec_x = (d % 2 == 0) && ((reinterpret_cast<uintptr_t>(x) & (2 * sizeof(T) - 1)) == 0);
     const int vec_e = (E % 2 == 0) && ((reinterpret_cast<uintptr_t>(dl) & 7u) == 0);
     XMOE_LAUNCH(K_GATE_BWD_DW, s,

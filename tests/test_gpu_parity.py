@@ -313,6 +313,26 @@ def test_route_bwd_and_gate_bwd(name):
     assert_close(to_host(dxg), dl32.astype(np.float64) @ w64.T, dt, "gate_bwd dx_gate", floor="row")
 
 
+@pytest.mark.parametrize("T,d,E", [(300, 64, 64), (1000, 128, 128), (257, 192, 256), (64, 512, 64), (2049, 64, 64)])
+def test_gate_bwd_matrix_core_kernels(T, d, E):
+    """bf16 with d % 64 == 0 and E % 64 == 0 takes the bf16 matrix-instruction kernels (dlogits enters as hi + lo bf16
+    terms): token counts that end inside a chunk, a slice and a wave's 32 rows; several expert blocks.  Against float64
+    products of the same inputs; the only rounding that shows is that of the bf16 results (2^-9), far inside the bar."""
+    m = xm()
+    rng = np.random.default_rng(T + d + E)
+    x = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), "bf16")
+    w = xi.round_to_storage((rng.standard_normal((d, E)) / np.sqrt(d)).astype(np.float32), "bf16")
+    dl = (rng.standard_normal((T, E)) * np.exp(rng.uniform(-6, 2, size=(T, 1)))).astype(np.float32)
+    dwr = torch.full((d, E), 7.0, dtype=torch.bfloat16, device="cuda")
+    dxg = torch.full((T, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    ws = m.alloc_workspace(m.xmoe_workspace_bytes(m.WS_GATE_BWD, T, d, E, 1, 64, 0))
+    m.xmoe_gate_logits_bwd(to_dev(x, "bf16"), to_dev(w, "bf16"), f32(dl), dwr, dxg, ws)
+    torch.cuda.synchronize()
+    x64, w64, dl64 = x.astype(np.float64), w.astype(np.float64), dl.astype(np.float64)
+    assert rel_err(to_host(dwr), x64.T @ dl64, "tensor") <= 5e-3
+    assert rel_err(to_host(dxg), dl64 @ w64.T, "row") <= 5e-3
+
+
 # ------------------------------------------------------------------------------------------------ expert MLP
 @pytest.mark.parametrize("name", SMALL)
 def test_expert_ffn_fwd_bwd(name):
