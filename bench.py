@@ -67,7 +67,12 @@ def small_kernel_work(cfg):
     }
     f32_flops = {"gate_logits_kernel": 2 * T * d * E, "gate_bwd_dw_kernel": 2 * T * d * E,
                  "gate_bwd_dx_kernel": 2 * T * d * E}
-    return bytes_, f32_flops
+    # bf16 workloads with d % 64 == 0 and E % 64 == 0: the two backward products run on the bf16 matrix instruction
+    # (dlogits as two bf16 terms, i.e. twice these flops are executed)
+    bf16_mfma = {}
+    if cfg.dtype == "bf16" and d % 64 == 0 and E % 64 == 0:
+        bf16_mfma = {k_: f32_flops.pop(k_) for k_ in ("gate_bwd_dw_kernel", "gate_bwd_dx_kernel")}
+    return bytes_, f32_flops, bf16_mfma
 
 
 def kernel_work(cfg, materialise_dy=False):
@@ -141,21 +146,21 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3444187918,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1423689044,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2955591757,
-    ("dsmoe16b", "ffn_bwd_rest_dma_kernel"): 7839695896,
-    ("large", "ffn_gateup_dma_kernel"): 18287137751,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 8916750508,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9350526837,
-    ("large", "ffn_bwd_rest_dma_kernel"): 45162765590,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3532695972,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1421952225,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2916356849,
+    ("dsmoe16b", "ffn_bwd_rest_dma_kernel"): 7914454403,
+    ("large", "ffn_gateup_dma_kernel"): 18283264853,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 8890745984,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9346145881,
+    ("large", "ffn_bwd_rest_dma_kernel"): 45100158656,
     # with XMOE_BWD_MERGE=0 (the backward's last three GEMMs as launches of their own)
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2670333736,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1522013388,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2858494165,
-    ("large", "ffn_dx_dma_kernel"): 17161058560,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10219957502,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 17481456590,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2737770913,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1526006904,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2865591351,
+    ("large", "ffn_dx_dma_kernel"): 16965927558,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10219419940,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17480100369,
 }
 
 
@@ -274,7 +279,7 @@ def main():
     xm.xmoe_prof_reset()
 
     flops, bytes_ = kernel_work(cfg, args.materialise_dy)
-    small_bytes, f32_flops = small_kernel_work(cfg)
+    small_bytes, f32_flops, small_mfma_flops = small_kernel_work(cfg)
     bytes_.update(small_bytes)
     gemm_work = GEMM_WORK_MLP2 if mlp2 else GEMM_WORK
     kernels = {}
@@ -286,6 +291,9 @@ def main():
             ent["tflops"] = round(flops[gemm_work[name]] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
             ent["algorithmic_gbs"] = round(bytes_["gemm:" + gemm_work[name]] / (per_step_ms * 1e-3) / 1e9, 1)
+        if name in small_mfma_flops:
+            ent["tflops"] = round(small_mfma_flops[name] / (per_step_ms * 1e-3) / 1e12, 3)
+            ent["frac_mfma_peak"] = round(ent["tflops"] / PEAK_BF16_MFMA_TFLOPS, 5)
         if name in f32_flops:
             ent["f32_tflops"] = round(f32_flops[name] / (per_step_ms * 1e-3) / 1e12, 3)
             ent["frac_f32_peak"] = round(ent["f32_tflops"] / PEAK_FP32_TFLOPS, 5)
