@@ -672,7 +672,7 @@ __global__ __launch_bounds__(256) void gate_bwd_dx_mfma_kernel(const float* __re
                                                                bf16_t* __restrict__ dxg, int Tn, int d, int E) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t0 = (blockIdx.x * 4 + wave) * 32;
-    if (t0 >= Tn) return;
+    if (!ONE_CHUNK && t0 >= Tn) return;   // (E == 64: every wave takes part in the staging and its barrier)
     const int h = lane >> 5, c = lane & 31;
     // columns per wave; d % 64 == 0, so every 32-column block below is complete
     constexpr int COLS = ONE_CHUNK ? kDxCols : kDxColsManyExperts;
@@ -716,12 +716,34 @@ __global__ __launch_bounds__(256) void gate_bwd_dx_mfma_kernel(const float* __re
                 make_uint2(pack_bf16x2(acc[4 * j], acc[4 * j + 1]), pack_bf16x2(acc[4 * j + 2], acc[4 * j + 3]));
     };
     if (ONE_CHUNK) {
+        // E == 64.  The four waves of a block work on the same columns, so the block stages its kDxCols rows of w in
+        // LDS once (rows of 128 bytes padded to kDwStride) and the column blocks take their operands from there:
+        // with loads from memory between the stores, every wait for an operand would also wait for the stores
+        // issued before it (the counter is in issue order).
+        __shared__ __align__(16) char wsm[kDxCols * kDwStride];
+        {
+            const int r = threadIdx.x >> 3, piece = threadIdx.x & 7;   // 32 rows x 8 pieces of 16 bytes per pass
+#pragma unroll
+            for (int pass = 0; pass < kDxCols / 32; ++pass) {
+                const int row = pass * 32 + r;
+                uint4 q = make_uint4(0, 0, 0, 0);
+                if (ibeg + row < iend) q = *reinterpret_cast<const uint4*>(w + (size_t)(ibeg + row) * E + piece * 8);
+                *reinterpret_cast<uint4*>(wsm + row * kDwStride + piece * 16) = q;
+            }
+        }
         load_a(0);
+        __syncthreads();
         for (int i0 = ibeg; i0 < iend; i0 += 32) {
             gate_f32x16_t acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-            multiply(i0, 0, acc);
+            const char* brow = wsm + (i0 - ibeg + c) * kDwStride + 16 * h;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                const gate_bf16x8_t bb = *reinterpret_cast<const gate_bf16x8_t*>(brow + 32 * ks);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, __builtin_bit_cast(gate_bf16x8_t, ah[ks]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bb, __builtin_bit_cast(gate_bf16x8_t, al[ks]), acc, 0, 0, 0);
+            }
             store(i0, acc);
         }
     } else {
