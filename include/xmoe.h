@@ -26,6 +26,12 @@
  *   - Inputs must be finite; behaviour on NaN/Inf logits is unspecified.  Index arrays handed to a call must
  *     be the ones an earlier call of this library produced for the same sizes (they are not re-validated on
  *     the device).
+ *   - Two environment variables, each read once per process, choose between equivalent kernels (for comparisons
+ *     and per-kernel profiles; results stay within the same tolerances):
+ *       XMOE_FFN_FAMILY = dma | reg | simt   caps the kernel family of the expert MLP (default: the best one that
+ *                                            supports the shapes: bf16 matrix-core kernels, else float32 ALU kernels)
+ *       XMOE_BWD_MERGE = 0                   runs the last three GEMMs of the expert MLP's backward (dXd and the two
+ *                                            weight gradients) as three launches instead of one
  */
 #ifndef XMOE_H
 #define XMOE_H
