@@ -732,6 +732,11 @@ struct TileWalker {
     }
     // after the tile's main loop (the slot written here was last read before the barrier that ended the previous tile)
     __device__ __forceinline__ void hand_over() {
+        // The draw's result is consumed under a branch (thread 0 only).  On the other path the compiler still counts
+        // it as pending, and would wait for it - that is, for everything outstanding, the tile's result stores
+        // included - where the register is next written: at the top of the next tile, in front of its first
+        // requests.  A use by every lane here, where nothing is in flight, settles it.
+        asm volatile("" ::"v"(drawn));
         if (threadIdx.x == 0) slot[(it + 1) & 1] = q.pop(drawn);
     }
     // ends the tile (every wave has left its staging strip before the next tile's loads land in the ring) and
