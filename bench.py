@@ -146,21 +146,21 @@ GEMM_WORK_MLP2 = {
 # WRITE_SIZE, each scaled by what the same counter shows for xmoe_prof_copy's known traffic); the summaries with
 # the commands are in profiles/.  Keyed by (workload, kernel); absent -> "traffic": null.
 MEASURED_TRAFFIC_BYTES = {
-    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3532695972,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1421952225,
-    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2916356849,
-    ("dsmoe16b", "ffn_bwd_rest_dma_kernel"): 7914454403,
-    ("large", "ffn_gateup_dma_kernel"): 18283264853,
-    ("large", "ffn_rowgemm_dma_kernel<false>"): 8890745984,
-    ("large", "ffn_rowgemm_dma_kernel<true>"): 9346145881,
-    ("large", "ffn_bwd_rest_dma_kernel"): 45100158656,
+    ("dsmoe16b", "ffn_gateup_dma_kernel"): 3436532654,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<false>"): 1440582642,
+    ("dsmoe16b", "ffn_rowgemm_dma_kernel<true>"): 2931228234,
+    ("dsmoe16b", "ffn_bwd_rest_dma_kernel"): 7806262998,
+    ("large", "ffn_gateup_dma_kernel"): 18235410452,
+    ("large", "ffn_rowgemm_dma_kernel<false>"): 8919924841,
+    ("large", "ffn_rowgemm_dma_kernel<true>"): 9339771956,
+    ("large", "ffn_bwd_rest_dma_kernel"): 44965444938,
     # with XMOE_BWD_MERGE=0 (the backward's last three GEMMs as launches of their own)
-    ("dsmoe16b", "ffn_dx_dma_kernel"): 2737770913,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1526006904,
-    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2865591351,
-    ("large", "ffn_dx_dma_kernel"): 16965927558,
-    ("large", "ffn_wgrad_dma_kernel<false>"): 10219419940,
-    ("large", "ffn_wgrad_dma_kernel<true>"): 17480100369,
+    ("dsmoe16b", "ffn_dx_dma_kernel"): 2615565865,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<false>"): 1518724246,
+    ("dsmoe16b", "ffn_wgrad_dma_kernel<true>"): 2862533844,
+    ("large", "ffn_dx_dma_kernel"): 16972216823,
+    ("large", "ffn_wgrad_dma_kernel<false>"): 10219727135,
+    ("large", "ffn_wgrad_dma_kernel<true>"): 17483049465,
 }
 
 
