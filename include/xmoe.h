@@ -12,7 +12,7 @@
  *
  * Conventions that hold for every call
  *   - Every pointer except `stream` is a DEVICE pointer owned by the caller; the library never allocates,
- *     frees or synchronises.  All work is enqueued on the hipStream_t passed as `void* stream` (NULL = the
+ *     frees or synchronises (the xmoe_prof_* read-outs below excepted).  All work is enqueued on the hipStream_t passed as `void* stream` (NULL = the
  *     null stream).  Sizes are host integers.  Matrices are row-major and dense.
  *   - `dt` is the storage type of activations and weights: XMOE_F32 (4 bytes) or XMOE_BF16 (2 bytes).
  *     All arithmetic accumulates in float32; results are rounded once (nearest-even) when stored as bf16.
@@ -26,12 +26,17 @@
  *   - Inputs must be finite; behaviour on NaN/Inf logits is unspecified.  Index arrays handed to a call must
  *     be the ones an earlier call of this library produced for the same sizes (they are not re-validated on
  *     the device).
- *   - Two environment variables, each read once per process, choose between equivalent kernels (for comparisons
- *     and per-kernel profiles; results stay within the same tolerances):
- *       XMOE_FFN_FAMILY = dma | reg | simt   caps the kernel family of the expert MLP (default: the best one that
- *                                            supports the shapes: bf16 matrix-core kernels, else float32 ALU kernels)
- *       XMOE_BWD_MERGE = 0                   runs the last three GEMMs of the expert MLP's backward (dXd and the two
- *                                            weight gradients) as three launches instead of one
+ *   - Process-wide state.  No call depends on an earlier call's arguments, and calls on different streams share no
+ *     device memory beyond what the caller passes (xmoe_build_eri_static excepted, see there).  What the library does
+ *     keep per process, all of it host-side and none of it synchronised (the first call on a device, xmoe_prof_* and
+ *     any other call must not race with each other from different threads):
+ *       - per device, set on the first expert-MLP call there: the compute-unit count (size of the persistent grids)
+ *         and the raised dynamic-LDS limit of the matrix-core kernels;
+ *       - the event profiler of xmoe_prof_* (off by default).  Only while it is enabled do the matrix-core kernels
+ *         also write their clock samples into a device-global table, which launches on different streams then share;
+ *       - one environment variable, read once: XMOE_BWD_MERGE = 0 runs the last three GEMMs of the expert MLP's
+ *         backward (dXd and the two weight gradients) as three launches instead of one (for comparisons and
+ *         per-kernel profiles; the results are the same bits).
  */
 #ifndef XMOE_H
 #define XMOE_H
@@ -179,7 +184,7 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
  * xd [B,d]; wg, wu [E,d,f]; wd [E,f,d] ("in x out"); expert_offsets [E+1] int32 on the device with
  * offsets[0] = 0 and offsets[E] = B.  Outputs: y [B,d]; g_save, u_save [B,f] (kept for backward).
  * An expert with no rows reads no weights.
- * row_index: NULL, or the gather of dispatch fused into the operand load (Section 4.1.2 names the dispatched copy
+ * row_index: NULL, or the gather of dispatch fused into the operand load (Section 3.2 / Table 2 names the dispatched copy
  * as one of the two activation tensors worth removing): xd is then the token matrix x [T,d] itself, row_index [B]
  * int32 holds token ids (token_ids of the ERI-arrays), and row i of the expert input is x[row_index[i]]; no [B,d]
  * copy of the tokens exists.  Entries of rows outside every segment are never read.  Results are bit-identical to
@@ -219,7 +224,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
 /* The paper's own expert (Listing 1 mlp(pft, w1, w2): two sequential GeMMs over the ragged segments; Table 1 counts
  * 2 h' h parameters per expert and Table 3's totals need exactly two matrices).  For each expert e and its rows:
  *   H = Xd_e W1_e  (the listing's inter_activ),   A = act(H),   Y_e = A W2_e          (no biases)
- * The listing prints no activation between the two GeMMs while Section 3.1 counts two intermediate activations
+ * The listing prints no activation between the two GeMMs while Section 3.2 (Table 2) counts two intermediate activations
  * between the FFN sub-layers, so `act` (an xmoe_act) is a parameter.
  * xd, row_index, expert_offsets, B, E, d, f: as in xmoe_expert_ffn_fwd.  w1 [E,d,f]; w2 [E,f,d] ("in x out").
  * Outputs: y [B,d]; h_save [B,f] (kept for backward).  ws: XMOE_WS_MLP2_FWD bytes.

@@ -27,7 +27,7 @@ Readings of the paper that this oracle fixes (the paper is silent or garbled on 
     the top-k indices held constant.
   * the paper's own expert (Listing 1 mlp(): two sequential GeMMs w1, w2; Table 1 counts 2 h' h parameters per
     expert; Table 3's totals need two matrices per expert) is also provided: Y = act(X W1) W2.  The listing
-    prints no activation between the two GeMMs while Section 3.1 speaks of two intermediate activations between
+    prints no activation between the two GeMMs while Section 3.2 (Table 2) speaks of two intermediate activations between
     the FFN sub-layers; act is therefore a parameter: "identity" (the listing as printed), "gelu" (x Phi(x), the
     exact erf form: the default of the Megatron-style MLP that the paper's framework trains) or "silu".
   * Redundancy-Bypassing Dispatch, stage 0 (Section 4.2): experts are laid out over nodes in contiguous blocks
@@ -618,7 +618,7 @@ def moe_layer_bwd(inp: dict, fwd: dict, k: int) -> dict:
 
 
 # ----------------------------------------------------------------------------------------------------------
-# activation footprint (Section 3.1, Table 2; the paper's printed instance is Table 4's "Theoretical" row)
+# activation footprint (Section 3.2, Table 2; the paper's printed instance is Table 4's "Theoretical" row)
 # ----------------------------------------------------------------------------------------------------------
 def activation_bytes(T: int, k: int, d: int, f: int, bytes_per_el: int, c: float = 1.0) -> float:
     """A_dispatch + A_combine (k*T*d each) plus the two FFN intermediates (k*T*f each), times capacity c."""

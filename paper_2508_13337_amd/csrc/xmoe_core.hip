@@ -39,11 +39,6 @@ const char* const kKernelNames[K_COUNT] = {
     "ffn_dact_simt_kernel",
     "ffn_dx_simt_kernel",
     "ffn_wgrad_simt_kernel",
-    "ffn_gateup_mfma_kernel",
-    "ffn_down_mfma_kernel",
-    "ffn_dact_mfma_kernel",
-    "ffn_dx_mfma_kernel",
-    "ffn_wgrad_mfma_kernel",
     "ffn_gateup_dma_kernel",
     "ffn_rowgemm_dma_kernel<false>",
     "ffn_rowgemm_dma_kernel<true>",
@@ -76,12 +71,25 @@ hipEvent_t get_event() {
 }
 }  // namespace
 
-// A copy whose traffic is known exactly (bytes read + bytes written): the yardstick for hardware byte counters.
-__global__ __launch_bounds__(256) void prof_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                        size_t n16) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+// A copy whose traffic is known exactly (bytes read + bytes written): the yardstick for hardware byte counters, and
+// what a streaming kernel reaches on this GPU.  Every thread keeps four independent 16-byte loads in flight (lanes of
+// a wave on consecutive 16-byte pieces, the four loads 4 KiB apart) and writes with streaming stores.
+typedef __attribute__((ext_vector_type(4))) unsigned int prof_u32x4_t;
+__global__ __launch_bounds__(256) void prof_copy_kernel(const prof_u32x4_t* __restrict__ src,
+                                                        prof_u32x4_t* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 1024;
+    for (size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x; base < n16; base += stride) {
+        prof_u32x4_t v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (base + 256 * j < n16) v[j] = __builtin_nontemporal_load(src + base + 256 * j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (base + 256 * j < n16) __builtin_nontemporal_store(v[j], dst + base + 256 * j);
+    }
 }
+
+bool prof_enabled() { return g_prof.on; }
 
 void prof_begin(int kid, hipStream_t s) {
     (void)kid;
@@ -176,10 +184,10 @@ int xmoe_prof_copy(const void* src, void* dst, size_t bytes, void* stream) {
         return XMOE_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     const size_t n16 = bytes / 16;
-    const size_t want = (n16 + 255) / 256;
-    const unsigned grid = (unsigned)(want < 8192 ? want : 8192);
-    XMOE_LAUNCH(K_PROF_COPY, s, hipLaunchKernelGGL(prof_copy_kernel, dim3(grid), dim3(256), 0, s, (const uint4*)src,
-                                                   (uint4*)dst, n16));
+    const size_t want = (n16 + 1023) / 1024;
+    const unsigned grid = (unsigned)(want < 4096 ? want : 4096);
+    XMOE_LAUNCH(K_PROF_COPY, s, hipLaunchKernelGGL(prof_copy_kernel, dim3(grid), dim3(256), 0, s,
+                                                   (const prof_u32x4_t*)src, (prof_u32x4_t*)dst, n16));
     return XMOE_OK;
 }
 

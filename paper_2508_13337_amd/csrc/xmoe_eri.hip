@@ -141,7 +141,8 @@ __global__ __launch_bounds__(256) void eri_scatter_kernel(const int32_t* __restr
 // the rows behind the last retained one.  No floating-point arithmetic takes part in the decision.
 // ---------------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t weight_key(float w) {
-    const uint32_t u = __float_as_uint(w);
+    uint32_t u = __float_as_uint(w);
+    if (u == 0x80000000u) u = 0u;                          // -0.0 ties with +0.0
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // ascending in w
 }
 

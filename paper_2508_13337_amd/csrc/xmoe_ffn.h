@@ -46,15 +46,11 @@ int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int
 int ffn_fwd_simt(const FfnArgs& a, hipStream_t s);
 int ffn_bwd_simt(const FfnArgs& a, hipStream_t s);
 
-// bf16 MFMA families: both need d % 64 == 0, f % 64 == 0 and 16-byte aligned operands
-//   "dma": 256x256 tiles, operands streamed global -> LDS directly, transposing LDS reads (the default)
-//   "reg": 128x128 tiles, operands staged through registers
+// bf16 MFMA family (needs d % 64 == 0, f % 64 == 0 and 16-byte aligned operands): 256x256 tiles, operands streamed
+// global -> LDS directly, transposing LDS reads
 bool ffn_dma_supported(const FfnArgs& a);
 int ffn_fwd_dma(const FfnArgs& a, hipStream_t s);
 int ffn_bwd_dma(const FfnArgs& a, hipStream_t s);
-bool ffn_mfma_supported(const FfnArgs& a);
-int ffn_fwd_mfma(const FfnArgs& a, hipStream_t s);
-int ffn_bwd_mfma(const FfnArgs& a, hipStream_t s);
 
 int mlp2_fwd_simt(const Mlp2Args& a, hipStream_t s);
 int mlp2_bwd_simt(const Mlp2Args& a, hipStream_t s);

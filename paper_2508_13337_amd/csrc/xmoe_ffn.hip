@@ -1,25 +1,10 @@
 // Entry points of the expert MLP (paper: Listing 1 mlp(); Appendix B.4): argument checks, workspace carve-up,
-// and the choice between the bf16 MFMA kernels and the float32-ALU kernels.
-#include <stdlib.h>
-#include <string.h>
+// and the choice between the bf16 MFMA kernels (bf16 storage, d and f multiples of 64, 16-byte aligned operands)
+// and the float32-ALU kernels (everything else).
 
 #include "xmoe_ffn.h"
 
 namespace xmoe {
-
-// Kernel family for the expert MLP: the environment variable XMOE_FFN_FAMILY = dma | reg | simt caps the choice
-// (for tests and comparisons); by default the best family that supports the shapes is taken.
-enum Family { FAM_DMA = 0, FAM_REG = 1, FAM_SIMT = 2 };
-static int g_family_cap = -1;
-static int family_cap() {
-    if (g_family_cap < 0) {
-        const char* v = getenv("XMOE_FFN_FAMILY");
-        g_family_cap = FAM_DMA;
-        if (v && strcmp(v, "reg") == 0) g_family_cap = FAM_REG;
-        if (v && strcmp(v, "simt") == 0) g_family_cap = FAM_SIMT;
-    }
-    return g_family_cap;
-}
 
 static int check_common(int B, int E, int d, int f, int dt) {
     if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
@@ -58,8 +43,7 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t*
     p += ffn_tilemap_bytes(B, E);
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
-    if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_fwd_dma(a, s);
-    if (family_cap() <= FAM_REG && !row_index && ffn_mfma_supported(a)) return ffn_fwd_mfma(a, s);
+    if (ffn_dma_supported(a)) return ffn_fwd_dma(a, s);
     return ffn_fwd_simt(a, s);
 }
 
@@ -94,8 +78,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     p += ffn_act_bytes(B, f, dt);
     a.act = p;
     hipStream_t s = (hipStream_t)stream;
-    if (family_cap() <= FAM_DMA && ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
-    if (family_cap() <= FAM_REG && !row_index && !dy_row_index && ffn_mfma_supported(a)) return ffn_bwd_mfma(a, s);
+    if (ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
     return ffn_bwd_simt(a, s);
 }
 
@@ -122,7 +105,7 @@ int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t
     p += ffn_tilemap_bytes(B, E);
     a.a_buf = p;
     hipStream_t s = (hipStream_t)stream;
-    if (family_cap() <= FAM_DMA && mlp2_dma_supported(a)) return mlp2_fwd_dma(a, s);
+    if (mlp2_dma_supported(a)) return mlp2_fwd_dma(a, s);
     return mlp2_fwd_simt(a, s);
 }
 
@@ -155,7 +138,7 @@ int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h
     p += ffn_act_bytes(B, f, dt);
     a.a_buf = p;
     hipStream_t s = (hipStream_t)stream;
-    if (family_cap() <= FAM_DMA && mlp2_dma_supported(a)) return mlp2_bwd_dma(a, s);
+    if (mlp2_dma_supported(a)) return mlp2_bwd_dma(a, s);
     return mlp2_bwd_simt(a, s);
 }
 

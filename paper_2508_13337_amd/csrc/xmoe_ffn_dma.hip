@@ -58,68 +58,15 @@ __device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
 enum ClockSlot { CS_GATEUP = 0, CS_DOWN, CS_DACT, CS_DX, CS_WGRAD, CS_WGRAD_DUAL, CS_MLP2_UP, CS_MLP2_DACT, CS_BWD_REST,
                  CS_COUNT };
 __device__ unsigned long long g_clock_probe[CS_COUNT][4];
-__device__ __forceinline__ void clock_note(int slot, int at_end) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        g_clock_probe[slot][2 * at_end] = clock64();
-        g_clock_probe[slot][2 * at_end + 1] = wall_clock64();
+// clk: the kernel's slot of g_clock_probe while the launch profiler is enabled, else NULL (nothing is written then,
+// so launches on different streams share no device memory outside their arguments)
+__device__ __forceinline__ void clock_note(unsigned long long* clk, int at_end) {
+    if (clk && blockIdx.x == 0 && threadIdx.x == 0) {
+        clk[2 * at_end] = clock64();
+        clk[2 * at_end + 1] = wall_clock64();
     }
 }
 
-#ifdef XMOE_PROBE_TIMING
-// probe build only: per-tile phase timestamps (100 MHz clock) written by thread 0 of each workgroup
-struct ProbeRec {
-    int kind, block, tile, rows;
-    unsigned long long t[4];   // tile start, first k-tile ready, main loop done, epilogue done
-    unsigned long long c[2];   // shader-clock counter at tile start / main loop done
-};
-__device__ ProbeRec g_probe[1 << 17];
-__device__ int g_probe_n;
-#define PROBE_BEGIN(kind_, tile_, rows_)                                                  \
-    int pr_ = -1;                                                                         \
-    if (threadIdx.x == 0) {                                                               \
-        pr_ = atomicAdd(&g_probe_n, 1);                                                   \
-        if (pr_ < (1 << 17)) {                                                            \
-            g_probe[pr_].kind = (kind_);                                                  \
-            g_probe[pr_].block = blockIdx.x;                                              \
-            g_probe[pr_].tile = (tile_);                                                  \
-            g_probe[pr_].rows = (rows_);                                                  \
-            g_probe[pr_].t[0] = wall_clock64();                                           \
-            g_probe[pr_].c[0] = clock64();                                                \
-        } else {                                                                          \
-            pr_ = -1;                                                                     \
-        }                                                                                 \
-    }
-#define PROBE_MARK(idx_, i_)                                  \
-    if ((idx_) >= 0) {                                        \
-        g_probe[idx_].t[i_] = wall_clock64();                 \
-        if ((i_) == 2) g_probe[idx_].c[1] = clock64();        \
-    }
-#define PROBE_IDX pr_
-#else
-#define PROBE_BEGIN(kind_, tile_, rows_)
-#define PROBE_MARK(idx_, i_)
-#define PROBE_IDX -1
-#endif
-
-#ifdef XMOE_PROBE_ONE_EXPERT
-#define PROBE_E(e_) 0   // probe build: every expert reads expert 0's weights (they then stay cache-resident)
-#else
-#define PROBE_E(e_) (e_)
-#endif
-#ifdef XMOE_PROBE_NOLOAD_A
-constexpr bool kProbeNoA = true;
-#else
-constexpr bool kProbeNoA = false;
-#endif
-#ifdef XMOE_PROBE_NOLOAD_B
-constexpr bool kProbeNoB = true;
-#else
-constexpr bool kProbeNoB = false;
-#endif
-
-#ifndef XMOE_DMA_AUX
-#define XMOE_DMA_AUX 0   // probe: cache-policy bits of the operand loads (bit 0 sc0, bit 1 nt, bit 4 sc1)
-#endif
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -318,7 +265,7 @@ struct Loader {
         if (GATHER && COL) idx_read(kt, idx_rd);
     }
     template <bool PROLOGUE>
-    __device__ __forceinline__ void issue(char* tile, int kt, bool probe_zero) const {
+    __device__ __forceinline__ void issue(char* tile, int kt) const {
         int src_row[2] = {0, 0};
         if (GATHER && COL) {
             src_row[0] = gk2[0];
@@ -340,11 +287,7 @@ struct Loader {
             } else {
                 p = pnext[i];
             }
-#ifdef XMOE_PROBE_NOLOAD
-            p = reinterpret_cast<const bf16_t*>(kZero16);
-#endif
-            if (probe_zero) p = reinterpret_cast<const bf16_t*>(kZero16);
-            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, XMOE_DMA_AUX);
+            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(tile + lds_off[i]), 16, 0, 0);
         }
     }
 };
@@ -407,10 +350,6 @@ __device__ __forceinline__ void read_frags(Frags& f, const char* ta, const char*
 
 // acc[mi][ni][v] holds C(row = wm*128 + mi*32 + lane%32, col = b_col(wn, ni) + 8*(v/4) + 4*(lane/32) + v%4)
 __device__ __forceinline__ void mma_step(f32x16_t (&acc)[4][2], const Frags& f) {
-#ifdef XMOE_PROBE_NOMMA
-    if (f.a[0][0] == (__bf16)123.0f) acc[0][0][0] += 1.0f;   // keeps the fragment reads alive
-    return;
-#endif
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
@@ -439,8 +378,8 @@ __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt
 template <class LA, class LB>
 __device__ __forceinline__ void feed_step(const LA& la, const LB& lb, char* __restrict__ st_next, int nt,
                                           const char* __restrict__ ia_rd, const char* __restrict__ ib_rd) {
-    la.template issue<false>(st_next, nt, kProbeNoA);
-    lb.template issue<false>(st_next + kOpBytes, nt, kProbeNoB);
+    la.template issue<false>(st_next, nt);
+    lb.template issue<false>(st_next + kOpBytes, nt);
     la.read_rows(nt + 1, ia_rd);
     lb.read_rows(nt + 1, ib_rd);
     la.prepare_next(nt + 1);
@@ -467,18 +406,14 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
     // +4 to +10 % in the kernels with a K-contiguous operand, where it is therefore left alone.  (Raising the
     // priority during the matrix instructions instead costs 5 to 10 % everywhere.)
     if (A_COL && B_COL) __builtin_amdgcn_s_setprio(1);
-    la.template issue<false>(st_next, nt, kProbeNoA);
-    lb.template issue<false>(st_next + kOpBytes, nt, kProbeNoB);
+    la.template issue<false>(st_next, nt);
+    lb.template issue<false>(st_next + kOpBytes, nt);
     if (A_COL && B_COL) __builtin_amdgcn_s_setprio(0);
     read_frags<A_COL, B_COL, DUAL>(f0, st, st + kOpBytes, 0);
     mma_step(acc, f1);
     la.read_rows(nt + 1, ia_rd);
     lb.read_rows(nt + 1, ib_rd);
-#ifdef XMOE_PROBE_HALFLDS
-    f1 = f0;   // probe build: half the fragment reads (results are wrong, timing only)
-#else
     read_frags<A_COL, B_COL, DUAL>(f1, st, st + kOpBytes, 1);
-#endif
     mma_step(acc, f0);
     if (A_COL || B_COL) {
         // instruction order: every MFMA is followed by a share of the k-tile's direct-to-LDS loads and LDS
@@ -517,7 +452,7 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
 template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER = false, bool B_GATHER = false>
 __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                           const Operand& oa2, const Operand& ob2, int K2, int mi_count,
-                                          char* smem, int probe_idx = -1) {
+                                          char* smem) {
     const int nk1 = (K + TK - 1) / TK;
     const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
     if (nk <= 0) return;
@@ -533,8 +468,8 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     // number of outstanding loads uniform)
 #pragma unroll
     for (int s = 0; s < kStages - 1; ++s) {
-        la.template issue<true>(smem + s * kStageBytes, s, kProbeNoA);
-        lb.template issue<true>(smem + s * kStageBytes + kOpBytes, s, kProbeNoB);
+        la.template issue<true>(smem + s * kStageBytes, s);
+        lb.template issue<true>(smem + s * kStageBytes + kOpBytes, s);
         if (!(A_GATHER && A_COL)) la.prepare_next(s + 1);   // (a gathered K-strided operand does it inside issue())
         if (!(B_GATHER && B_COL)) lb.prepare_next(s + 1);
     }
@@ -543,7 +478,6 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     // k-tiles kt+1 .. kt+3 are in flight while k-tile kt is multiplied.
     constexpr int kInFlight = (kStages - 2) * kLoadsPerTile;   // loads that may still be outstanding at the barrier
     wait_loads_and_barrier<kInFlight>();
-    PROBE_MARK(probe_idx, 1)
     if (mi_count > 0) {
         Frags f0, f1;
         zero_frags(f1);   // the first call multiplies the carried fragments: zeros
@@ -574,24 +508,9 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
 
 template <bool A_COL, bool B_COL, bool DUAL, bool A_GATHER = false, bool B_GATHER = false>
 __device__ __forceinline__ void mainloop(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
-                                         int mi_count, char* smem, int probe_idx = -1) {
-    mainloop2<A_COL, B_COL, DUAL, false, A_GATHER, B_GATHER>(acc, oa, ob, K, oa, ob, 0, mi_count, smem, probe_idx);
+                                         int mi_count, char* smem) {
+    mainloop2<A_COL, B_COL, DUAL, false, A_GATHER, B_GATHER>(acc, oa, ob, K, oa, ob, 0, mi_count, smem);
 }
-
-#ifdef XMOE_PROBE_NOEPI
-// probe build: skips the epilogue but keeps the accumulators alive
-#define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)                                   \
-    {                                                                         \
-        float s_ = 0.f;                                                       \
-        for (int mi_ = 0; mi_ < 4; ++mi_)                                     \
-            for (int ni_ = 0; ni_ < 2; ++ni_)                                 \
-                for (int v_ = 0; v_ < 16; ++v_) s_ += acc[mi_][ni_][v_];      \
-        if (s_ == 123.456f) (ptr)[0].bits = 1;                                \
-        continue;                                                               \
-    }
-#else
-#define XMOE_PROBE_SKIP_EPILOGUE(acc, ptr)
-#endif
 
 // sigmoid with the hardware exp2 and reciprocal (each good to about 1 ulp): the results are rounded to bf16, and
 // the library-grade expf and IEEE division cost as much as a quarter of a tile's main loop in the fused epilogues.
@@ -830,32 +749,29 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
                                                              const bf16_t* __restrict__ wg,
                                                              const bf16_t* __restrict__ wu, bf16_t* __restrict__ G,
                                                              bf16_t* __restrict__ U, bf16_t* __restrict__ A,
-                                                             int32_t* __restrict__ counters) {
+                                                             int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(CS_GATEUP, 0);
+    clock_note(clk, 0);
     const int nt = (f + 127) / 128;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
     tw.draw();
     const RowTile rt = get_tile(map, off, t, nt);
-    PROBE_BEGIN(0, t, rt.rows)
     const int n0 = rt.col * 128;
     const int ncols = f - n0 < 128 ? f - n0 : 128;
     Operand a = row_op(GATHER ? xd : xd + (long)rt.row0 * d, d, rt.rows);
     if (GATHER) a.gather = row_index + rt.row0;
     Operand b;
-    b.p_lo = wg + (long)PROBE_E(rt.e) * d * f + n0;
-    b.p_hi = wu + (long)PROBE_E(rt.e) * d * f + n0;
+    b.p_lo = wg + (long)rt.e * d * f + n0;
+    b.p_hi = wu + (long)rt.e * d * f + n0;
     b.ld = f;
     b.n_lo = b.n_hi = ncols;
     b.k_valid = d;
     f32x16_t acc[4][2];
     zero_acc(acc);
     const int mi_count = wave_mi_count(rt.rows);
-    mainloop<false, true, true, GATHER>(acc, a, b, d, mi_count, smem, PROBE_IDX);
+    mainloop<false, true, true, GATHER>(acc, a, b, d, mi_count, smem);
     tw.hand_over();
-    PROBE_MARK(PROBE_IDX, 2)
-    XMOE_PROBE_SKIP_EPILOGUE(acc, G)
 
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
     char* strip = smem + wave * kStripBytes;
@@ -883,9 +799,8 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
         strip_flush<32>(strip, 0, A + base, f, rows_valid, cols_valid);
         strip_sync();
     }
-        PROBE_MARK(PROBE_IDX, 3)
     }
-    clock_note(CS_GATEUP, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -905,20 +820,19 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                                                               const bf16_t* __restrict__ G,
                                                               const bf16_t* __restrict__ U, bf16_t* __restrict__ dG,
                                                               bf16_t* __restrict__ dU, bf16_t* __restrict__ A,
-                                                              int32_t* __restrict__ counters) {
+                                                              int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(DACT ? CS_DACT : CS_DOWN, 0);
+    clock_note(clk, 0);
     const int nt = (N + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
     tw.draw();
     const RowTile rt = get_tile(map, off, t, nt);
-    PROBE_BEGIN(DACT ? 2 : 1, t, rt.rows)
     const int n0 = rt.col * TN;
     const int ncols = N - n0 < TN ? N - n0 : TN;
     Operand a = row_op(DY_GATHER ? X : X + (long)rt.row0 * K, K, rt.rows);
     if (DY_GATHER) a.gather = x_index + rt.row0;
-    const bf16_t* We = W + (long)PROBE_E(rt.e) * K * N;
+    const bf16_t* We = W + (long)rt.e * K * N;
     f32x16_t acc[4][2];
     zero_acc(acc);
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
@@ -926,14 +840,12 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
     const int mi_count = (wn * 64 < ncols) ? wave_mi_count(rt.rows) : 0;
     if (DACT) {
         Operand b = row_op(We + (long)n0 * K, K, ncols);   // Wd is [f, d]: its rows are the output columns
-        mainloop<false, false, false, DY_GATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<false, false, false, DY_GATHER>(acc, a, b, K, mi_count, smem);
     } else {
         Operand b = col_op(We + n0, N, ncols, K);          // Wd is [f, d]: k-rows, output columns contiguous
-        mainloop<false, true, false>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<false, true, false>(acc, a, b, K, mi_count, smem);
     }
     tw.hand_over();
-    PROBE_MARK(PROBE_IDX, 2)
-    XMOE_PROBE_SKIP_EPILOGUE(acc, dG ? dG : Y)
     char* strip = smem + wave * kStripBytes;
     const int lane = threadIdx.x & 63;
     const int cols_valid = ncols - wn * 64;
@@ -1035,9 +947,8 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             strip_sync();
         }
     }
-        PROBE_MARK(PROBE_IDX, 3)
     }
-    clock_note(DACT ? CS_DACT : CS_DOWN, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1053,7 +964,6 @@ __device__ __forceinline__ void dx_tile(int t, TileWalker& tw, char* smem, const
                                         bf16_t* __restrict__ dXd) {
     const int nt = (d + TN - 1) / TN;
     const RowTile rt = get_tile(map, off, t, nt);
-    PROBE_BEGIN(3, t, rt.rows)
     const int n0 = rt.col * TN;
     const int ncols = d - n0 < TN ? d - n0 : TN;
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
@@ -1062,14 +972,12 @@ __device__ __forceinline__ void dx_tile(int t, TileWalker& tw, char* smem, const
     zero_acc(acc);
     {
         Operand a1 = row_op(dG + (long)rt.row0 * f, f, rt.rows);
-        Operand b1 = row_op(wg + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols);
+        Operand b1 = row_op(wg + (long)rt.e * d * f + (long)n0 * f, f, ncols);
         Operand a2 = TWO ? row_op(dU + (long)rt.row0 * f, f, rt.rows) : a1;
-        Operand b2 = TWO ? row_op(wu + (long)PROBE_E(rt.e) * d * f + (long)n0 * f, f, ncols) : b1;
-        mainloop2<false, false, false, TWO>(acc, a1, b1, f, a2, b2, TWO ? f : 0, mi_count, smem, PROBE_IDX);
+        Operand b2 = TWO ? row_op(wu + (long)rt.e * d * f + (long)n0 * f, f, ncols) : b1;
+        mainloop2<false, false, false, TWO>(acc, a1, b1, f, a2, b2, TWO ? f : 0, mi_count, smem);
     }
     tw.hand_over();
-    PROBE_MARK(PROBE_IDX, 2)
-    XMOE_PROBE_SKIP_EPILOGUE(acc, dXd)
     char* strip = smem + wave * kStripBytes;
     const int cols_valid = ncols - wn * 64;
 #pragma unroll
@@ -1087,7 +995,6 @@ __device__ __forceinline__ void dx_tile(int t, TileWalker& tw, char* smem, const
         strip_flush<64, true>(strip, 0, dXd + (long)(rt.row0 + r0) * d + n0 + wn * 64, d, rt.rows - r0, cols_valid);
         strip_sync();
     }
-    PROBE_MARK(PROBE_IDX, 3)
 }
 
 template <bool TWO>
@@ -1095,16 +1002,16 @@ __global__ __launch_bounds__(512) void ffn_dx_dma_kernel(const bf16_t* __restric
                                                          const int32_t* __restrict__ off,
                                                          const int32_t* __restrict__ map, int d, int f,
                                                          const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu,
-                                                         bf16_t* __restrict__ dXd, int32_t* __restrict__ counters) {
+                                                         bf16_t* __restrict__ dXd, int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(CS_DX, 0);
+    clock_note(clk, 0);
     const int nt = (d + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
         tw.draw();
         dx_tile<TWO>(t, tw, smem, dG, dU, off, map, d, f, wg, wu, dXd);
     }
-    clock_note(CS_DX, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1157,9 +1064,9 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
                                                           const int32_t* __restrict__ off,
                                                           const int32_t* __restrict__ map, int d, int f,
                                                           const bf16_t* __restrict__ w1, bf16_t* __restrict__ H,
-                                                          bf16_t* __restrict__ A, int32_t* __restrict__ counters) {
+                                                          bf16_t* __restrict__ A, int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(CS_MLP2_UP, 0);
+    clock_note(clk, 0);
     const int nt = (f + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -1206,7 +1113,7 @@ __global__ __launch_bounds__(512) void mlp2_up_dma_kernel(const bf16_t* __restri
             strip_sync();
         }
     }
-    clock_note(CS_MLP2_UP, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1223,9 +1130,9 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ w2,
                                                             const bf16_t* __restrict__ H, bf16_t* __restrict__ dH,
                                                             bf16_t* __restrict__ A,
-                                                            int32_t* __restrict__ counters) {
+                                                            int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(CS_MLP2_DACT, 0);
+    clock_note(clk, 0);
     const int nt = (f + TN - 1) / TN;
     TileWalker tw;
     for (int t = tw.start(counters, map[0] * nt, smem); t >= 0; t = tw.next()) {
@@ -1308,7 +1215,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
             strip_sync();
         }
     }
-    clock_note(CS_MLP2_DACT, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1341,7 +1248,6 @@ __device__ __forceinline__ void wgrad_tile(int t, TileWalker& tw, char* smem, co
     const int m0 = (band * kWgradBand + in_band % band_rows) * TM, n0 = (in_band / band_rows) * NB;
     const int lo = off[e], hi = off[e + 1];
     const int K = hi - lo;
-    PROBE_BEGIN(DUAL ? 5 : 4, t, K)
     const int mrows = M - m0 < TM ? M - m0 : TM, ncols = N - n0 < NB ? N - n0 : NB;
     const int wave = threadIdx.x >> 6, wm = wave >> 2, wn = wave & 3;
     f32x16_t acc[4][2];
@@ -1366,11 +1272,9 @@ __device__ __forceinline__ void wgrad_tile(int t, TileWalker& tw, char* smem, co
         const int wcol = DUAL ? (wn & 1) * 64 : wn * 64;
         const int mi_count = (wcol < ncols) ? wave_mi_count(mrows) : 0;
         static_assert(!(DUAL && QGATHER), "the gathered right-hand side is a single matrix");
-        mainloop<true, true, false, GATHER, QGATHER>(acc, a, b, K, mi_count, smem, PROBE_IDX);
+        mainloop<true, true, false, GATHER, QGATHER>(acc, a, b, K, mi_count, smem);
     }
     tw.hand_over();
-    PROBE_MARK(PROBE_IDX, 2)
-    XMOE_PROBE_SKIP_EPILOGUE(acc, dW1)
     char* strip = smem + wave * kStripBytes;
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
@@ -1393,7 +1297,6 @@ __device__ __forceinline__ void wgrad_tile(int t, TileWalker& tw, char* smem, co
         }
         strip_sync();
     }
-    PROBE_MARK(PROBE_IDX, 3)
 }
 
 template <bool DUAL, bool GATHER, bool QGATHER = false>
@@ -1407,9 +1310,9 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ order,
                                                             int32_t* __restrict__ counters, int E, int M, int N,
-                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
+                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 0);
+    clock_note(clk, 0);
     constexpr int NB = DUAL ? 128 : TN;
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
     TileWalker tw;
@@ -1418,7 +1321,7 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
         wgrad_tile<DUAL, GATHER, QGATHER>(t, tw, smem, P, row_index, Q1, Q2, q_index, row_index_dma, q_index_dma, off,
                                           order, M, N, dW1, dW2);
     }
-    clock_note(DUAL ? CS_WGRAD_DUAL : CS_WGRAD, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1438,9 +1341,9 @@ __global__ __launch_bounds__(512) void ffn_bwd_rest_dma_kernel(
     const int32_t* __restrict__ off, const int32_t* __restrict__ map, const int32_t* __restrict__ order,
     int32_t* __restrict__ cnt_dx, int32_t* __restrict__ cnt_wd, int32_t* __restrict__ cnt_wgu, int E, int d, int f,
     const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu, bf16_t* __restrict__ dXd, bf16_t* __restrict__ dWd,
-    bf16_t* __restrict__ dWg, bf16_t* __restrict__ dWu) {
+    bf16_t* __restrict__ dWg, bf16_t* __restrict__ dWu, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
-    clock_note(CS_BWD_REST, 0);
+    clock_note(clk, 0);
     TileWalker tw;
     for (int t = tw.start(cnt_dx, map[0] * ((d + TN - 1) / TN), smem); t >= 0; t = tw.next()) {
         tw.draw();
@@ -1460,7 +1363,7 @@ __global__ __launch_bounds__(512) void ffn_bwd_rest_dma_kernel(
         wgrad_tile<SWIGLU, GATHER, false>(t, tw, smem, xd, row_index, dG, dU, nullptr, row_index_dma, nullptr, off,
                                           order, d, f, dWg, dWu);
     }
-    clock_note(CS_BWD_REST, 1);
+    clock_note(clk, 1);
 }
 
 // =========================================================================================================
@@ -1475,10 +1378,23 @@ bool ffn_dma_supported(const FfnArgs& a) {
     return true;
 }
 
-static int g_num_cu = 0;
+// Host-side state of this family, all of it set up once per device on the first call there (the calls themselves
+// stay stateless: nothing below depends on an earlier call's arguments):
+//   num_cu       compute units of the device, rounded down to a multiple of the XCD count (persistent grid size)
+//   clock_probe  device address of g_clock_probe on that device
+//   the raised dynamic-LDS limit of every kernel of the family
+// Not synchronised: the first call on a device must not race with another call on the same device.
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+    int status = -1;   // -1: not initialised; else an xmoe_status
+    int num_cu = 0;
+    unsigned long long* clock_probe = nullptr;
+};
+static DeviceState g_dev[kMaxDevices];
+static thread_local DeviceState* t_dev = nullptr;   // the device of the call in progress on this thread
 
 // The backward's three independent GEMMs run as one launch unless the environment variable XMOE_BWD_MERGE is 0
-// (for comparisons and for the per-kernel profiles).
+// (for comparisons and for the per-kernel profiles); read once per process.
 static bool bwd_merged() {
     static int v = -1;
     if (v < 0) {
@@ -1496,8 +1412,14 @@ static inline int32_t* row_counters(int32_t* sched, int E, int i) { return sched
 // multiple of the XCD count
 static inline unsigned round_up8(long v) {
     long g = (v + 7) / 8 * 8;
-    if (g_num_cu > 0 && g > g_num_cu) g = g_num_cu;
+    const int num_cu = t_dev ? t_dev->num_cu : 0;
+    if (num_cu > 0 && g > num_cu) g = num_cu;
     return (unsigned)(g < 8 ? 8 : g);
+}
+
+// the kernel's clock-probe slot while the launch profiler is on, else NULL
+static inline unsigned long long* clock_slot(int slot) {
+    return (prof_enabled() && t_dev && t_dev->clock_probe) ? t_dev->clock_probe + 4 * slot : nullptr;
 }
 
 template <class Kern>
@@ -1509,52 +1431,56 @@ static int allow_big_lds(Kern k) {
                : XMOE_ERR_HIP;
 }
 
-static int init_once() {
-    static int state = -1;
-    if (state < 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            g_num_cu = prop.multiProcessorCount / kNumXcd * kNumXcd;
-        int st = allow_big_lds(ffn_gateup_dma_kernel<false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, true>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_IDENTITY>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_GELU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_SILU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_IDENTITY>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_GELU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_SILU>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, false>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, true>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, false>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, true>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, false>);
-        if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, true>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
-        if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
-        state = st;
-    }
-    return state;
+static int init_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return XMOE_ERR_HIP;
+    DeviceState& ds = g_dev[dev];
+    t_dev = &ds;
+    if (ds.status >= 0) return ds.status;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return ds.status = XMOE_ERR_HIP;
+    ds.num_cu = prop.multiProcessorCount / kNumXcd * kNumXcd;
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_clock_probe)) != hipSuccess) return ds.status = XMOE_ERR_HIP;
+    ds.clock_probe = static_cast<unsigned long long*>(sym);
+    int st = XMOE_OK;
+    if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_gateup_dma_kernel<true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<false, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_rowgemm_dma_kernel<true, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, false, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<true, true, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, false, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_bwd_rest_dma_kernel<false, true, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_dx_dma_kernel<false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, true>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_IDENTITY>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_GELU>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<false, XMOE_ACT_SILU>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_IDENTITY>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_GELU>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_up_dma_kernel<true, XMOE_ACT_SILU>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, false>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_IDENTITY, true>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, false>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_GELU, true>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, false>);
+    if (st == XMOE_OK) st = allow_big_lds(mlp2_dact_dma_kernel<XMOE_ACT_SILU, true>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<false, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
+    if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
+    return ds.status = st;
 }
 
 int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
-    int st = init_once();
+    int st = init_device();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
     st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
@@ -1566,22 +1492,22 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
                     hipLaunchKernelGGL(ffn_gateup_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
                                        kLdsBytes, s, xd, a.row_index, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
-                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0)));
+                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0), clock_slot(CS_GATEUP)));
     else
         XMOE_LAUNCH(K_FFN_GATEUP_DMA, s,
                     hipLaunchKernelGGL(ffn_gateup_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntg)), dim3(512),
                                        kLdsBytes, s, xd, nullptr, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.g,
-                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0)));
+                                       (bf16_t*)a.u, (bf16_t*)a.act, row_counters(a.sched, a.E, 0), clock_slot(CS_GATEUP)));
     XMOE_LAUNCH(K_FFN_DOWN_DMA, s,
                 hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.act, nullptr, nullptr, a.off, a.map, a.f, a.d, wd,
                                    (bf16_t*)a.y, nullptr,
-                                   nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
+                                   nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
     return XMOE_OK;
 }
 
 int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
-    int st = init_once();
+    int st = init_device();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
     st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
@@ -1595,13 +1521,13 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                     hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, true>), dim3(round_up8((long)max_tiles * ntf)),
                                        dim3(512), kLdsBytes, s, dy, a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f, wd,
                                        nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
-                                       row_counters(a.sched, a.E, 0)));
+                                       row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
     else
         XMOE_LAUNCH(K_FFN_DACT_DMA, s,
                     hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, false>), dim3(round_up8((long)max_tiles * ntf)),
                                        dim3(512), kLdsBytes, s, dy, nullptr, nullptr, a.off, a.map, a.d, a.f, wd,
                                        nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
-                                       row_counters(a.sched, a.E, 0)));
+                                       row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     const int ntf2 = (a.f + 127) / 128;
     if (bwd_merged()) {
@@ -1614,7 +1540,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                                    act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off, a.map,       \
                                    a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E, a.sched + a.E + kNumXcd,    \
                                    a.E, a.d, a.f, wg, wu, (bf16_t*)a.dxd, (bf16_t*)a.dwd, (bf16_t*)a.dwg,             \
-                                   (bf16_t*)a.dwu))
+                                   (bf16_t*)a.dwu, clock_slot(CS_BWD_REST)))
         if (a.row_index && a.dy_index) XMOE_REST(true, true);
         else if (a.row_index) XMOE_REST(true, false);
         else if (a.dy_index) XMOE_REST(false, true);
@@ -1624,7 +1550,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
     }
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<true>, dim3(round_up8((long)max_tiles * ntd)), dim3(512), kLdsBytes, s, dg,
-                                   du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd, row_counters(a.sched, a.E, 1)));
+                                   du, a.off, a.map, a.d, a.f, wg, wu, (bf16_t*)a.dxd, row_counters(a.sched, a.E, 1), clock_slot(CS_DX)));
     // dWd [f, d] = A^T dY
     if (a.dy_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
@@ -1632,25 +1558,25 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
                                        nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
                                        a.d,
-                                       (bf16_t*)a.dwd, nullptr));
+                                       (bf16_t*)a.dwd, nullptr, clock_slot(CS_WGRAD)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
                                        dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr));
+                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr, clock_slot(CS_WGRAD)));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
                                        dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, nullptr, a.row_index, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
                                        dim3(512), kLdsBytes, s, xd, nullptr, dg, du, nullptr, nullptr, nullptr, a.off, a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu));
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
     return XMOE_OK;
 }
 
@@ -1664,7 +1590,7 @@ bool mlp2_dma_supported(const Mlp2Args& a) {
 }
 
 int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
-    int st = init_once();
+    int st = init_device();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
     st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
@@ -1677,7 +1603,7 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
                 hipLaunchKernelGGL((mlp2_up_dma_kernel<true, ACT>), grid, dim3(512), kLdsBytes, s, xd, a.row_index,  \
                                    a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf,              \
-                                   row_counters(a.sched, a.E, 0)))
+                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_UP)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     } else {
@@ -1685,7 +1611,7 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_UP_DMA, s,                                                                                    \
                 hipLaunchKernelGGL((mlp2_up_dma_kernel<false, ACT>), grid, dim3(512), kLdsBytes, s, xd, nullptr,     \
                                    a.off, a.map, a.d, a.f, w1, (bf16_t*)a.h, (bf16_t*)a.a_buf,              \
-                                   row_counters(a.sched, a.E, 0)))
+                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_UP)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     }
@@ -1693,12 +1619,12 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
                 hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.a_buf, nullptr, nullptr, a.off, a.map, a.f, a.d, w2,
                                    (bf16_t*)a.y,
-                                   nullptr, nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1)));
+                                   nullptr, nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
     return XMOE_OK;
 }
 
 int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
-    int st = init_once();
+    int st = init_device();
     if (st != XMOE_OK) return st;
     const int max_tiles = ffn_max_tiles(a.B, a.E, TM);
     st = launch_tile_map(a.off, a.E, TM, max_tiles, a.map, a.sched, s);
@@ -1713,7 +1639,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
                 hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, true>), grid, dim3(512), kLdsBytes, s, dy, a.dy_index, \
                                    a.dy_scale, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,            \
-                                   row_counters(a.sched, a.E, 0)))
+                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     } else {
@@ -1721,7 +1647,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
                 hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, false>), grid, dim3(512), kLdsBytes, s, dy, nullptr,  \
                                    nullptr, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,               \
-                                   row_counters(a.sched, a.E, 0)))
+                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     }
@@ -1736,7 +1662,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
                                    nullptr, act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off,     \
                                    a.map, a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E,                      \
                                    a.sched + a.E + kNumXcd, a.E, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,               \
-                                   (bf16_t*)a.dw2, (bf16_t*)a.dw1, nullptr))
+                                   (bf16_t*)a.dw2, (bf16_t*)a.dw1, nullptr, clock_slot(CS_BWD_REST)))
         if (a.row_index && a.dy_index) XMOE_REST(true, true);
         else if (a.row_index) XMOE_REST(true, false);
         else if (a.dy_index) XMOE_REST(false, true);
@@ -1747,7 +1673,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_FFN_DX_DMA, s,
                 hipLaunchKernelGGL(ffn_dx_dma_kernel<false>, dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, dh, nullptr, a.off, a.map, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,
-                                   row_counters(a.sched, a.E, 1)));
+                                   row_counters(a.sched, a.E, 1), clock_slot(CS_DX)));
     // dW2 [f, d] = A^T dY
     if (a.dy_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
@@ -1755,26 +1681,26 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
                                        nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
                                        a.d,
-                                       (bf16_t*)a.dw2, nullptr));
+                                       (bf16_t*)a.dw2, nullptr, clock_slot(CS_WGRAD)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
                                        dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr));
+                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr, clock_slot(CS_WGRAD)));
     // dW1 [d, f] = Xd^T dH
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, true>), dim3(round_up8((long)a.E * mtd * ntf)),
                                        dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, nullptr, a.row_index, nullptr,
                                        a.off, a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtd * ntf)),
                                        dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr));
+                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
     return XMOE_OK;
 }
 
@@ -1798,24 +1724,9 @@ extern "C" int xmoe_prof_shader_clock(int kernel_id, double* ghz) {
     *ghz = 0.0;
     if (slot < 0) return XMOE_OK;
     unsigned long long v[4];
-    if (hipMemcpyFromSymbol(v, HIP_SYMBOL(xmoe::g_clock_probe), sizeof(v), (size_t)slot * sizeof(v)) != hipSuccess)
+    if (xmoe::init_device() != XMOE_OK || !xmoe::t_dev->clock_probe) return XMOE_ERR_HIP;
+    if (hipMemcpy(v, xmoe::t_dev->clock_probe + 4 * slot, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
         return XMOE_ERR_HIP;
     if (v[3] > v[1] && v[2] > v[0]) *ghz = (double)(v[2] - v[0]) / ((double)(v[3] - v[1]) * 10.0);   // 100 MHz ticks
     return XMOE_OK;
 }
-
-#ifdef XMOE_PROBE_TIMING
-extern "C" int xmoe_probe_dump(void* host_recs, int max_recs, int reset) {
-    int n = 0;
-    if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(xmoe::g_probe_n), sizeof(int)) != hipSuccess) return -1;
-    int m = n < max_recs ? n : max_recs;
-    if (m > (1 << 17)) m = 1 << 17;
-    if (m > 0 && hipMemcpyFromSymbol(host_recs, HIP_SYMBOL(xmoe::g_probe), (size_t)m * sizeof(xmoe::ProbeRec)) != hipSuccess)
-        return -1;
-    if (reset) {
-        int z = 0;
-        if (hipMemcpyToSymbol(HIP_SYMBOL(xmoe::g_probe_n), &z, sizeof(int)) != hipSuccess) return -1;
-    }
-    return m;
-}
-#endif

@@ -201,8 +201,11 @@ __global__ __launch_bounds__(256) void gate_logits_lds_kernel(const bf16_t* __re
 // =========================================================================================================
 constexpr int kMaxPerLane = XMOE_MAX_EXPERTS / 64;   // 8
 
+// order-preserving bit pattern of a float; -0.0 and +0.0 compare equal as numbers, so both map to +0.0's key and
+// the lower expert index decides between them like any other tie
 __device__ __forceinline__ uint32_t order_key(float v) {
     uint32_t u = __float_as_uint(v);
+    if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
@@ -890,9 +893,23 @@ int xmoe_route_bwd(const float* logits, const int32_t* topk_idx, const float* dw
 int xmoe_gate_logits_bwd(const void* x, const void* w_router, const float* dlogits, int T, int d, int E, int dt,
                          void* dw_router, void* dx_gate, void* ws, size_t ws_bytes, void* stream) {
     if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
-    if (T < 1 || d < 1 || E < 1) return XMOE_ERR_INVALID_ARG;
+    if (T < 0 || d < 1 || E < 1) return XMOE_ERR_INVALID_ARG;
     if ((long long)T * E >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
-    if (!x || !w_router || !dlogits || !dw_router || !dx_gate) return XMOE_ERR_INVALID_ARG;
+    if (!dw_router) return XMOE_ERR_INVALID_ARG;
+    if (T == 0) {   // a sum over no tokens: dw_router = 0, dx_gate has no rows
+        const size_t n = (size_t)d * E;
+        const dim3 grid((unsigned)((n + 255) / 256));
+        if (dt == XMOE_F32)
+            XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, (hipStream_t)stream,
+                        hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream,
+                                           (const float*)nullptr, 0, n, (float*)dw_router));
+        else
+            XMOE_LAUNCH(K_GATE_BWD_DW_REDUCE, (hipStream_t)stream,
+                        hipLaunchKernelGGL(gate_bwd_dw_reduce_kernel<bf16_t>, grid, dim3(256), 0, (hipStream_t)stream,
+                                           (const float*)nullptr, 0, n, (bf16_t*)dw_router));
+        return XMOE_OK;
+    }
+    if (!x || !w_router || !dlogits || !dx_gate) return XMOE_ERR_INVALID_ARG;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < gate_bwd_ws_bytes(T, d, E))
         return XMOE_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;

@@ -31,11 +31,6 @@ enum KernelId : int {
     K_FFN_DACT_SIMT,
     K_FFN_DX_SIMT,
     K_FFN_WGRAD_SIMT,
-    K_FFN_GATEUP_MFMA,
-    K_FFN_DOWN_MFMA,
-    K_FFN_DACT_MFMA,
-    K_FFN_DX_MFMA,
-    K_FFN_WGRAD_MFMA,
     K_FFN_GATEUP_DMA,
     K_FFN_DOWN_DMA,
     K_FFN_DACT_DMA,
@@ -57,6 +52,7 @@ enum KernelId : int {
     K_COUNT
 };
 
+bool prof_enabled();   // the launch profiler of xmoe_prof_enable
 void prof_begin(int kid, hipStream_t s);
 void prof_end(int kid, hipStream_t s);
 

@@ -96,6 +96,24 @@ def test_route_bit_exact(T, E, k, seed, std):
     assert rel_err(to_host(w), w_ref) <= 1e-5
 
 
+def test_route_signed_zero_is_a_tie():
+    """-0.0 and +0.0 are equal as numbers: whichever sign the zeros carry, the lower expert index wins, also across
+    the k-th / (k+1)-th boundary and next to nonzero logits."""
+    T, E, k = 70, 9, 3
+    rng = np.random.default_rng(5)
+    logits = np.where(rng.random((T, E)) < 0.5, np.float32(-0.0), np.float32(0.0)).astype(np.float32)
+    logits[::2, 4] = np.float32(1.0)            # one clear winner in every other row
+    logits[1::3, 7] = np.float32(-2.0)          # and a clear loser elsewhere
+    logits[0, :2] = np.float32([-0.0, 0.0])     # the pair of the contract's example: expert 0 wins
+    idx_ref, w_ref, _ = oracle.route(logits, k)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    xm().xmoe_route(f32(logits), k, idx, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), idx_ref)
+    assert rel_err(to_host(w), w_ref) <= 1e-5
+
+
 # ------------------------------------------------------------------------------------------------ ERI arrays
 def run_build_eri(topk_idx, topk_w, E, max_token_count=None):
     T, k = topk_idx.shape
@@ -232,7 +250,7 @@ def test_dispatch_combine_and_backward(name):
                                             np.argsort(eri["row_of_slot"], kind="stable")].astype(np.float64),
                                         eri["row_of_slot"], cfg.k)
     assert_close(to_host(dy), dY_ref, dt, "combine_bwd dy", scale=0.5, floor="row")
-    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw", scale=2.0)
+    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw")
     dw_only = torch.full_like(dw, -1.0)   # without dY: the same dw, bit for bit
     m.xmoe_combine_bwd(to_dev(inp["dout"], dt), to_dev(Y, dt), ros, None, None, dw_only)
     assert torch.equal(dw_only, dw)
@@ -281,7 +299,7 @@ def test_combine_and_backward_any_k(T, E, k, d, dtype, drop):
                                         eri["row_of_slot"], k)
     assert_close(to_host(dy[:nk]), dY_ref, dtype, "combine_bwd dy", scale=0.5, floor="row")
     assert (dy[nk:] == 7.0).all()                                   # rows of dropped entries are not written
-    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw", scale=2.0)
+    assert_close(to_host(dw), dw_ref, "f32", "combine_bwd dw")
     dropped = (eri["row_of_slot"] < 0).reshape(T, k)
     assert not dw.cpu().numpy()[dropped].any()
     dx = torch.empty((T, d), dtype=torch_dtype(dtype), device="cuda")
@@ -301,7 +319,7 @@ def test_route_bwd_and_gate_bwd(name):
     dw32 = bwd["dw"].astype(np.float32)
     m.xmoe_route_bwd(f32(fwd["logits"]), i32(fwd["topk_idx"]), f32(dw32), dl)
     want = oracle.route_bwd(fwd["p"], fwd["topk_idx"], dw32.astype(np.float64))
-    assert_close(to_host(dl), want, "f32", "route_bwd dlogits", scale=2.0)
+    assert_close(to_host(dl), want, "f32", "route_bwd dlogits")
 
     dl32 = bwd["dlogits"].astype(np.float32)
     dwr = torch.empty((cfg.d, cfg.E), dtype=torch_dtype(dt), device="cuda")
