@@ -123,6 +123,22 @@ int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int T, int E, i
                    int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* xmoe_build_eri for callers that cannot allocate device memory or size a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as xmoe_build_eri (bit for
+ * bit); the chunk histograms that xmoe_build_eri keeps in the caller's workspace live in a static device array of
+ * XMOE_STATIC_ERI_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends.  Sizes whose
+ * histograms do not fit - ceil(T*k / 1024) * E * 4 bytes > XMOE_STATIC_ERI_SCRATCH_BYTES - are rejected with
+ * XMOE_ERR_WORKSPACE before anything is enqueued.  The call allocates nothing and frees nothing (the array's device
+ * address is looked up once per device, on the first call there).  All calls on one GPU share that GPU's array: two
+ * calls that overlap in time on one GPU (different streams, different threads) race on it and give undefined results;
+ * calls that follow each other on one stream, or are otherwise ordered, are fine - nothing in the array has to start
+ * at zero, every entry is written before it is read.
+ */
+#define XMOE_STATIC_ERI_SCRATCH_BYTES (1 << 20)
+int xmoe_build_eri_static(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                          int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                          int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot, void* stream);
+
 /* PFT construction with token dropping (Listing 1 PFT_construction(), step 2; Appendix B.2): as xmoe_build_eri,
  * but every expert keeps at most max_token_count of the rows routed to it - those with the largest combine
  * weights; among equal weights the lower flat entry n = t*k + j is kept first; retained rows keep the order they

@@ -20,6 +20,7 @@ SIGNATURES = {
     "xmoe_gate_logits": (_c_int, [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p]),
     "xmoe_route": (_c_int, [_c_void_p] + [_c_int] * 3 + [_c_void_p] * 3),
     "xmoe_build_eri": (_c_int, [_c_void_p] * 2 + [_c_int] * 3 + [_c_void_p] * 7 + [_c_size_t, _c_void_p]),
+    "xmoe_build_eri_static": (_c_int, [_c_void_p] * 2 + [_c_int] * 3 + [_c_void_p] * 7),
     "xmoe_build_eri_capped": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_size_t, _c_void_p]),
     "xmoe_dispatch": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_expert_ffn_fwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 6 + [_c_int, _c_void_p, _c_size_t,

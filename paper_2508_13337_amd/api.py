@@ -25,7 +25,7 @@ __all__ = [
     "xmoe_prof_read", "xmoe_prof_copy", "xmoe_prof_shader_clocks", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
     "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
-    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0",
+    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0", "xmoe_build_eri_static",
 ]
 
 
@@ -105,6 +105,22 @@ def xmoe_build_eri(topk_idx, topk_w, E: int, tokens_per_expert, expert_offsets, 
         _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
         _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_build_eri")
+
+
+def xmoe_build_eri_static(topk_idx, topk_w, E: int, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                          combine_weights, row_of_slot) -> None:
+    """xmoe_build_eri without a workspace: the scratch is a static array inside the library (for callers that cannot
+    allocate)."""
+    T, k = topk_idx.shape
+    B = T * k
+    assert tokens_per_expert.numel() == E and expert_offsets.numel() == E + 1
+    assert token_ids.numel() == B and expert_ids.numel() == B and combine_weights.numel() == B
+    assert row_of_slot.numel() == B
+    _check(lib().xmoe_build_eri_static(
+        _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"), T, E, k,
+        _ptr(tokens_per_expert, torch.int32), _ptr(expert_offsets, torch.int32), _ptr(token_ids, torch.int32),
+        _ptr(expert_ids, torch.int32), _ptr(combine_weights, torch.float32), _ptr(row_of_slot, torch.int32),
+        _stream()), "xmoe_build_eri_static")
 
 
 def xmoe_build_eri_capped(topk_idx, topk_w, E: int, max_token_count: int, tokens_per_expert, expert_offsets, token_ids,

@@ -327,21 +327,14 @@ __global__ __launch_bounds__(256) void eri_cap_kernel(const int32_t* __restrict_
 
 using namespace xmoe;
 
-extern "C" int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
-                              int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
-                              int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot, void* ws,
-                              size_t ws_bytes, void* stream) {
-    if (T < 0 || E < 1 || k < 1 || k > E) return XMOE_ERR_INVALID_ARG;
-    if (E > XMOE_MAX_EXPERTS) return XMOE_ERR_UNSUPPORTED;
-    if ((long long)T * k >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
-    if (!tokens_per_expert || !expert_offsets) return XMOE_ERR_INVALID_ARG;
-    if (T > 0 && (!topk_idx || !topk_w || !token_ids || !expert_ids || !combine_weights || !row_of_slot))
-        return XMOE_ERR_INVALID_ARG;
-    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < eri_ws_bytes(T, E, k)) return XMOE_ERR_WORKSPACE;
-    hipStream_t s = (hipStream_t)stream;
+// the three launches of the dropless construction; counts: eri_num_chunks(B) * E ints of scratch (every one of them is
+// written by the histogram kernel before it is read, so the memory needs no clearing)
+static int build_eri_launch(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                            int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                            int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot, int32_t* counts,
+                            hipStream_t s) {
     const int B = T * k;
     const int nchunks = eri_num_chunks(B);
-    int32_t* counts = (int32_t*)ws;
     int ebits = 0;
     while ((1 << ebits) < E) ++ebits;
     if (nchunks > 0)
@@ -356,6 +349,69 @@ extern "C" int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int 
                                        (size_t)kSubPerChunk * E * sizeof(int), s, topk_idx, topk_w, B, E, k, ebits,
                                        counts, expert_offsets, token_ids, expert_ids, combine_weights, row_of_slot));
     return XMOE_OK;
+}
+
+static int build_eri_check(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                           int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                           int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot) {
+    if (T < 0 || E < 1 || k < 1 || k > E) return XMOE_ERR_INVALID_ARG;
+    if (E > XMOE_MAX_EXPERTS) return XMOE_ERR_UNSUPPORTED;
+    if ((long long)T * k >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (!tokens_per_expert || !expert_offsets) return XMOE_ERR_INVALID_ARG;
+    if (T > 0 && (!topk_idx || !topk_w || !token_ids || !expert_ids || !combine_weights || !row_of_slot))
+        return XMOE_ERR_INVALID_ARG;
+    return XMOE_OK;
+}
+
+extern "C" int xmoe_build_eri(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                              int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                              int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot, void* ws,
+                              size_t ws_bytes, void* stream) {
+    const int st = build_eri_check(topk_idx, topk_w, T, E, k, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                                   combine_weights, row_of_slot);
+    if (st != XMOE_OK) return st;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < eri_ws_bytes(T, E, k)) return XMOE_ERR_WORKSPACE;
+    return build_eri_launch(topk_idx, topk_w, T, E, k, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                            combine_weights, row_of_slot, (int32_t*)ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// xmoe_build_eri for callers that cannot allocate: the chunk histograms live in a static device array instead of a
+// caller-provided workspace.  Every device holds its own copy of the array at its own address, looked up once per
+// device (hipGetSymbolAddress with that device current); host code only ever uses that address.
+// ---------------------------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[XMOE_STATIC_ERI_SCRATCH_BYTES / sizeof(int32_t)];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+int32_t* g_scratch_ptr[kMaxScratchDevices];   // device address of `scratch` on device i, or NULL before the first call there
+
+int scratch_for_current_device(int32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return XMOE_ERR_HIP;
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return XMOE_ERR_HIP;
+        g_scratch_ptr[dev] = static_cast<int32_t*>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return XMOE_OK;
+}
+}  // namespace
+
+extern "C" int xmoe_build_eri_static(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
+                                     int32_t* tokens_per_expert, int32_t* expert_offsets, int32_t* token_ids,
+                                     int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
+                                     void* stream) {
+    const int st = build_eri_check(topk_idx, topk_w, T, E, k, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                                   combine_weights, row_of_slot);
+    if (st != XMOE_OK) return st;
+    if (eri_ws_bytes(T, E, k) > (size_t)XMOE_STATIC_ERI_SCRATCH_BYTES) return XMOE_ERR_WORKSPACE;
+    int32_t* counts = nullptr;
+    const int sp = scratch_for_current_device(&counts);
+    if (sp != XMOE_OK) return sp;
+    return build_eri_launch(topk_idx, topk_w, T, E, k, tokens_per_expert, expert_offsets, token_ids, expert_ids,
+                            combine_weights, row_of_slot, counts, (hipStream_t)stream);
 }
 
 extern "C" int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
