@@ -105,3 +105,37 @@ def assert_close(got, ref, dtype_name: str, what: str, scale: float = 1.0, floor
     assert np.isfinite(np.asarray(got, np.float64)).all(), f"{what}: non-finite values"
     assert e <= TOL[dtype_name] * scale, f"{what}: max relative error {e:.3e} > {TOL[dtype_name] * scale:.1e}"
     return e
+
+
+def chain_errors_dev(got: torch.Tensor, ref: np.ndarray):
+    """(max row-wise 2-norm relative error, max element-wise relative error against max(|ref|, row RMS)) of a
+    device tensor against a float64 reference, computed in float64 on the device: the metric of
+    assert_close_chain(floor="row", norm="row") for tensors too large to compare on the host in reasonable time
+    (one expert's weight gradients at the large shapes).  Only the comparison runs on the device; the reference is
+    the oracle's."""
+    r = torch.from_numpy(np.ascontiguousarray(ref, dtype=np.float64)).cuda()
+    g = got.to(torch.float64)
+    assert g.shape == r.shape, (tuple(g.shape), tuple(r.shape))
+    if r.numel() == 0:
+        return 0.0, 0.0
+    assert torch.isfinite(g).all(), "non-finite values"
+    diff = g - r
+    n = r.pow(2).sum(dim=-1).sqrt()
+    e = diff.pow(2).sum(dim=-1).sqrt()
+    if bool((e[n == 0] != 0).any()):
+        return float("inf"), float("inf")
+    en = float((e / torch.where(n == 0, torch.ones_like(n), n)).max())
+    s_ = r.pow(2).mean(dim=-1, keepdim=True).sqrt()
+    den = torch.maximum(r.abs(), s_)
+    ee = float((diff.abs() / torch.where(den == 0, torch.ones_like(den), den)).max())
+    return en, ee
+
+
+def assert_close_chain_dev(got: torch.Tensor, ref: np.ndarray, dtype_name: str, what: str):
+    """assert_close_chain(floor="row", norm="row") with the comparison done on the device."""
+    en, ee = chain_errors_dev(got, ref)
+    tol = TOL[dtype_name]
+    cap = tol if dtype_name == "f32" else 4 * tol
+    assert en <= tol, f"{what}: max row-wise relative error {en:.3e} > {tol:.1e}"
+    assert ee <= cap, f"{what}: max element-wise relative error {ee:.3e} > {cap:.1e}"
+    return en, ee

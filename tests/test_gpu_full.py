@@ -1,22 +1,33 @@
 """GPU parity at the benchmark definition's full sizes, in the launch configuration bench.py times.
 
 Configs 2 and 3 (DeepSeek-MoE-16B-shaped layer, uniform and Zipf-skewed routing) are compared with the whole
-oracle.  Config 4 (large fine-grained layer, 22.6 GB of expert weights) and config 5 (long-sequence sweep) are too
-big for the float64 oracle to redo in full, so there every integer array is compared in full and the floating
-point tensors on a seeded sample the oracle computes one piece at a time: whole expert segments (forward
-activations, dXd and that expert's three weight gradients) and whole output rows (out and dx of sampled tokens,
-which pull in every expert those tokens were routed to, the shared experts and the gate path).  The gate weights'
-gradient needs every token's dlogits and is only checked in the whole-oracle tests."""
+oracle in one piece.  Config 4 (large fine-grained layer, 22.6 GB of expert weights), config 5 (long-sequence
+sweep) and the two-matrix expert at the Medium / Large / Super shapes of the paper's Table 3 are too big to hold the
+oracle's float64 tensors for all experts at once, so the oracle's steps are run expert by expert: an expert's weights
+are regenerated, the oracle computes that expert's forward (and backward) on its segment, the GPU's tensors for that
+segment and that expert are compared, and everything but the expert's output rows is discarded.  Integer arrays are
+always compared in full.  With `full_backward` every expert's dXd and weight gradients, the shared experts'
+gradients, every row of out and dx and the gate weights' gradient are compared (config 4 and the Table 3 shapes);
+without it (config 5, where the backward alone is 13 TFLOP of float64 at T = 65536) the forward, out, dw and the
+gate weights' gradient are still compared in full, and the backward on a seeded sample: whole segments of 8 experts
+(dXd and their weight gradients) and the dx rows of 1024 tokens."""
+import collections
+import concurrent.futures
+
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import xmoe_inputs as xi
-from gpu_util import assert_close_chain, rel_err, to_dev, to_host, torch_dtype
+from gpu_util import (assert_close_chain, assert_close_chain_dev, rel_err, to_dev, to_host, torch_dtype)
 from test_gpu_parity import bits_equal, check_layer, f32, xm
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def weight_keys(cfg):
+    return ("w1", "w2") if cfg.expert == "mlp2" else ("wg", "wu", "wd")
 
 
 def build_gpu_layer(cfg):
@@ -27,20 +38,24 @@ def build_gpu_layer(cfg):
     w = {"w_router": to_dev(xi.make_w_router(cfg), dt)}
     bias = xi.make_gate_bias(cfg)
     w["bias"] = None if bias is None else f32(bias)
-    for key in ("wg", "wu", "wd"):
+    keys = weight_keys(cfg)
+    for key in keys:
         Ea = cfg.E + cfg.E_s   # the shared experts' weights follow the routed ones
-        shape = (Ea, cfg.d, cfg.f) if key != "wd" else (Ea, cfg.f, cfg.d)
+        shape = (Ea, cfg.d, cfg.f) if key not in ("wd", "w2") else (Ea, cfg.f, cfg.d)
         w[key] = torch.empty(shape, dtype=tdt, device="cuda")
         for e, a in xi.iter_expert_weights(cfg, key):
             w[key][e].copy_(to_dev(a, dt))
         if cfg.E_s:
             w[key][cfg.E:].copy_(to_dev(xi.make_shared_weights(cfg, key), dt))
     grads = {"dw_router": torch.empty_like(w["w_router"])}
-    for key in ("wg", "wu", "wd"):
+    for key in keys:
         grads["d" + key] = torch.empty_like(w[key])
     x_np, dout_np = xi.make_x(cfg), xi.make_dout(cfg)
     x, dout = to_dev(x_np, dt), to_dev(dout_np, dt)
-    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
+    if cfg.expert == "mlp2":
+        layer = m.XMoE2Layer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, act=cfg.act)
+    else:
+        layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, tdt, E_s=cfg.E_s)
     out = layer.forward(x, w)
     dx = layer.backward(x, w, dout, grads)
     torch.cuda.synchronize()
@@ -61,25 +76,48 @@ def test_full_size_whole_oracle(name):
         assert tpe.max() >= 9 * tpe.mean() and (tpe == 0).any()
 
 
-class ExpertWeights:
-    """Regenerates single experts' matrices on demand (float64), keeping a few in memory."""
+def expert_stream(cfg, ahead=4):
+    """Yields (e, tuple of the expert's matrices as float64) for e = 0 .. E-1, regenerating each expert's weights on
+    host threads a few experts ahead of the consumer (pure data plumbing)."""
+    keys = weight_keys(cfg)
 
-    def __init__(self, cfg, keep=12):
-        self.cfg, self.keep, self.cache = cfg, keep, {}
+    def make(e):
+        return tuple(xi.make_expert_weight(cfg, k_, e).astype(np.float64) for k_ in keys)
 
-    def get(self, e):
-        if e not in self.cache:
-            if len(self.cache) >= self.keep:
-                self.cache.pop(next(iter(self.cache)))
-            self.cache[e] = tuple(xi.make_expert_weight(self.cfg, k_, e).astype(np.float64)
-                                  for k_ in ("wg", "wu", "wd"))
-        return self.cache[e]
+    with concurrent.futures.ThreadPoolExecutor(max_workers=ahead) as pool:
+        pending = collections.deque()
+        nxt = 0
+        while nxt < min(ahead, cfg.E):
+            pending.append((nxt, pool.submit(make, nxt)))
+            nxt += 1
+        while pending:
+            e, fut = pending.popleft()
+            mats = fut.result()
+            if nxt < cfg.E:
+                pending.append((nxt, pool.submit(make, nxt)))
+                nxt += 1
+            yield e, mats
 
 
-def verify_sampled(cfg, n_experts, n_tokens, seed=0):
+class Maxima:
+    """Largest (row-wise, element-wise) error seen per tensor name."""
+
+    def __init__(self):
+        self.m = {}
+
+    def add(self, name, pair):
+        a = self.m.get(name, (0.0, 0.0))
+        self.m[name] = (max(a[0], pair[0]), max(a[1], pair[1]))
+
+    def __str__(self):
+        return ", ".join(f"{k_} {v[0]:.2e}/{v[1]:.2e}" for k_, v in self.m.items())
+
+
+def verify_streamed(cfg, full_backward, n_experts=8, n_tokens=1024, seed=0):
     dt = cfg.dtype
+    mlp2 = cfg.expert == "mlp2"
     layer, out, dx, grads, x_np, dout_np, bias = build_gpu_layer(cfg)
-    k, E, T = cfg.k, cfg.E, cfg.T
+    k, E, T, d, B = cfg.k, cfg.E, cfg.T, cfg.d, cfg.B
     wr = xi.make_w_router(cfg)
 
     # ---- integers, in full
@@ -92,75 +130,124 @@ def verify_sampled(cfg, n_experts, n_tokens, seed=0):
         assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
     assert rel_err(to_host(layer.topk_w), topk_w) <= 1e-5
     off, tok, ros, cw = eri["expert_offsets"], eri["token_ids"], eri["row_of_slot"], eri["combine_weights"]
+    tpe = eri["tokens_per_expert"]
 
     x64, dout64 = x_np.astype(np.float64), dout_np.astype(np.float64)
-    ew = ExpertWeights(cfg)
     rng = np.random.default_rng(seed)
-    tpe = eri["tokens_per_expert"]
     nonempty = np.flatnonzero(tpe > 0)
-    chosen = {int(nonempty[np.argmax(tpe[nonempty])]), int(nonempty[np.argmin(tpe[nonempty])])}
-    chosen |= set(int(e) for e in rng.choice(nonempty, size=min(n_experts, len(nonempty)), replace=False))
-    chosen = sorted(chosen)[:max(n_experts, 2)]
+    if full_backward:
+        chosen = set(int(e) for e in nonempty)
+        toks = np.arange(T)
+    else:
+        chosen = {int(nonempty[np.argmax(tpe[nonempty])]), int(nonempty[np.argmin(tpe[nonempty])])}
+        chosen |= set(int(e) for e in rng.choice(nonempty, size=min(n_experts, len(nonempty)), replace=False))
+        chosen = set(sorted(chosen)[:max(n_experts, 2)])
+        toks = np.sort(rng.choice(T, size=min(n_tokens, T), replace=False))
+    # rows whose dXd the dx rows of `toks` need, and where each is kept
+    need_rows = ros.reshape(T, k)[toks].reshape(-1)
+    row_pos = np.full(B, -1, dtype=np.int64)
+    row_pos[need_rows] = np.arange(len(need_rows))
+    dXd_kept = np.zeros((len(need_rows), d))
+    Y = np.zeros((B, d))
+    mx = Maxima()
+    saved_names = ("h",) if mlp2 else ("g", "u")
+    grad_names = ("dw1", "dw2") if mlp2 else ("dwg", "dwu", "dwd")
 
-    # ---- whole expert segments
-    for e in chosen:
+    # ---- expert by expert: regenerate, compare, discard
+    for e, mats in expert_stream(cfg):
         lo, hi = int(off[e]), int(off[e + 1])
-        wg, wu, wd = ew.get(e)
+        if hi == lo:   # an expert with no rows: zero gradients
+            for gname in grad_names:
+                assert not grads[gname][e].any(), (gname, e)
+            continue
         Xd = x64[tok[lo:hi]]
-        Y, G, U = oracle.swiglu_ffn(Xd, wg, wu, wd)
-        assert_close_chain(to_host(layer.g[lo:hi]), G, dt, f"G e{e}")
-        assert_close_chain(to_host(layer.u[lo:hi]), U, dt, f"U e{e}")
-        assert_close_chain(to_host(layer.y[lo:hi]), Y, dt, f"Y e{e}")
+        if mlp2:
+            Ye, H = oracle.mlp2_ffn(Xd, mats[0], mats[1], cfg.act)
+            saved = (H,)
+        else:
+            Ye, G, U = oracle.swiglu_ffn(Xd, *mats)
+            saved = (G, U)
+        for nm, ref in zip(saved_names, saved):
+            mx.add(nm.upper(), assert_close_chain(to_host(getattr(layer, nm)[lo:hi]), ref, dt, f"{nm.upper()} e{e}"))
+        mx.add("Y", assert_close_chain(to_host(layer.y[lo:hi]), Ye, dt, f"Y e{e}"))
+        Y[lo:hi] = Ye
         dY = cw[lo:hi, None] * dout64[tok[lo:hi]]
-        dXd, dWg, dWu, dWd = oracle.swiglu_ffn_bwd(Xd, G, U, dY, wg, wu, wd)
-        assert_close_chain(to_host(layer.dxd[lo:hi]), dXd, dt, f"dXd e{e}")
-        assert_close_chain(to_host(grads["dwg"][e]), dWg, dt, f"dWg e{e}", floor="row")
-        assert_close_chain(to_host(grads["dwu"][e]), dWu, dt, f"dWu e{e}", floor="row")
-        assert_close_chain(to_host(grads["dwd"][e]), dWd, dt, f"dWd e{e}", floor="row")
-    for e in np.flatnonzero(tpe == 0):
-        assert not grads["dwg"][e].any() and not grads["dwu"][e].any() and not grads["dwd"][e].any()
+        if e in chosen:
+            if mlp2:
+                ref_b = oracle.mlp2_ffn_bwd(Xd, H, dY, mats[0], mats[1], cfg.act)
+            else:
+                ref_b = oracle.swiglu_ffn_bwd(Xd, G, U, dY, *mats)
+            mx.add("dXd", assert_close_chain(to_host(layer.dxd[lo:hi]), ref_b[0], dt, f"dXd e{e}"))
+            for gname, ref in zip(grad_names, ref_b[1:]):
+                mx.add(gname, assert_close_chain_dev(grads[gname][e], ref, dt, f"{gname} e{e}"))
+            keep = row_pos[lo:hi]
+            dXd_kept[keep[keep >= 0]] = ref_b[0][keep >= 0]
+        else:
+            # only the rows the sampled tokens own in this segment
+            sel = np.flatnonzero(row_pos[lo:hi] >= 0)
+            if len(sel):
+                if mlp2:
+                    dxr = oracle.mlp2_ffn_bwd(Xd[sel], H[sel], dY[sel], mats[0], mats[1], cfg.act)[0]
+                else:
+                    dxr = oracle.swiglu_ffn_bwd(Xd[sel], G[sel], U[sel], dY[sel], *mats)[0]
+                dXd_kept[row_pos[lo + sel]] = dxr
 
-    # ---- whole output rows of sampled tokens: out[t] and dx[t]
-    toks = np.sort(rng.choice(T, size=min(n_tokens, T), replace=False))
-    sh = [tuple(xi.make_shared_weight(cfg, k_, s).astype(np.float64) for k_ in ("wg", "wu", "wd"))
-          for s in range(cfg.E_s)]
-    want_out = np.zeros((len(toks), cfg.d))
-    want_dx = np.zeros((len(toks), cfg.d))
-    # group the (token, slot) pairs by expert so that each expert's weights are generated once
-    pairs = sorted((int(topk_idx[t, j]), ti, j) for ti, t in enumerate(toks) for j in range(k))
-    ys = np.zeros((len(toks), k, cfg.d))
-    for e, ti, j in pairs:
-        wg, wu, wd = ew.get(e)
-        t = toks[ti]
-        y, g, u = oracle.swiglu_ffn(x64[t:t + 1], wg, wu, wd)
-        ys[ti, j] = y[0]
-        want_out[ti] += topk_w[t, j] * y[0]
-        dxr, _, _, _ = oracle.swiglu_ffn_bwd(x64[t:t + 1], g, u, topk_w[t, j] * dout64[t:t + 1], wg, wu, wd)
-        want_dx[ti] += dxr[0]
-    for wg, wu, wd in sh:
-        y, g, u = oracle.swiglu_ffn(x64[toks], wg, wu, wd)
+    # ---- shared experts (every token, weight 1): forward, gradients, their share of out and dx
+    want_out = oracle.combine(Y, tok, cw, T)
+    dx_shared = np.zeros((T, d))
+    for s in range(cfg.E_s):
+        wg, wu, wd = (xi.make_shared_weight(cfg, k_, s).astype(np.float64) for k_ in ("wg", "wu", "wd"))
+        y, g, u = oracle.swiglu_ffn(x64, wg, wu, wd)
         want_out += y
-        want_dx += oracle.swiglu_ffn_bwd(x64[toks], g, u, dout64[toks], wg, wu, wd)[0]
-    dw = np.einsum("td,tkd->tk", dout64[toks], ys)
-    dlogits = oracle.route_bwd(p[toks], topk_idx[toks], dw)
-    want_dx += dlogits @ wr.astype(np.float64).T
+        seg = slice(B + s * T, B + (s + 1) * T)
+        mx.add("shared G", assert_close_chain(to_host(layer.g[seg]), g, dt, f"shared G {s}"))
+        mx.add("shared Y", assert_close_chain(to_host(layer.y[seg]), y, dt, f"shared Y {s}"))
+        dxs, dswg, dswu, dswd = oracle.swiglu_ffn_bwd(x64, g, u, dout64, wg, wu, wd)
+        dx_shared += dxs
+        for gname, ref in zip(("dwg", "dwu", "dwd"), (dswg, dswu, dswd)):
+            mx.add("shared " + gname, assert_close_chain_dev(grads[gname][E + s], ref, dt, f"shared {gname} {s}"))
+
+    # ---- every row of out; the combine weights' gradient, dlogits and the gate weights' gradient in full
+    mx.add("out", assert_close_chain(to_host(out), want_out, dt, "out"))
+    _, dw = oracle.combine_bwd(dout64, Y, tok, cw, ros, k)
+    dlogits = oracle.route_bwd(p, topk_idx, dw)
+    mx.add("dw_router", assert_close_chain(to_host(grads["dw_router"]), x64.T @ dlogits, dt, "dw_router",
+                                           floor="tensor", norm="tensor"))
+
+    # ---- dx: every row (full_backward) or the sampled tokens' rows
+    want_dx = (dlogits @ wr.astype(np.float64).T + dx_shared)[toks]
+    want_dx += dXd_kept.reshape(len(toks), k, d).sum(axis=1)
     tsel = torch.from_numpy(toks).long().cuda()
-    e_out = assert_close_chain(to_host(out[tsel]), want_out, dt, "out rows")
-    e_dx = assert_close_chain(to_host(dx[tsel]), want_dx, dt, "dx rows")
-    print(cfg.name, "experts", chosen, "tokens", len(toks), "out", e_out, "dx", e_dx)
-    # activation footprint held for backward: the closed form s*T*k*(2d+2f) counts Xd, Y, G, U; the gather is fused
-    # into the expert MLP's loads here, so Xd (s*T*k*d) does not exist and Y, G, U remain
-    B = layer.B
-    held = sum(t_[:B].numel() * t_.element_size() for t_ in (layer.y, layer.g, layer.u))
+    mx.add("dx", assert_close_chain(to_host(dx[tsel]), want_dx, dt, "dx rows"))
+    print(cfg.name, "backward of", len(chosen), "experts,", len(toks), "dx rows; max errors (row/element):", mx)
+
+    # activation footprint held for backward: the closed form s*T*k*(2d+2f) counts Xd, Y, G, U.  Here the gather is
+    # fused into the expert MLP's loads (no Xd) and the backward takes the combine weights' gradient from its own
+    # GEMM (Y is not read after the forward combine; test_backward_does_not_read_expert_outputs): G and U remain
     s_ = 2 if dt == "bf16" else 4
-    assert held == oracle.activation_bytes(T, k, cfg.d, cfg.f, s_) - s_ * T * k * cfg.d
-    assert not hasattr(layer, "xd")
+    held_t = (layer.h,) if mlp2 else (layer.g, layer.u)
+    held = sum(t_[:B].numel() * t_.element_size() for t_ in held_t)
+    if mlp2:
+        assert held == s_ * T * k * cfg.f
+    else:
+        assert held == oracle.activation_bytes(T, k, d, cfg.f, s_) - 2 * s_ * T * k * d
+    assert not hasattr(layer, "xd") and layer.dy is None
+    return mx
 
 
-def test_full_size_large_sampled():
-    verify_sampled(xi.CONFIGS["large"], n_experts=8, n_tokens=12)
+def test_full_size_large_every_expert():
+    """Config 4 in full: all 256 routed experts and the shared one, every row of out and dx, the gate weights'
+    gradient.  Segments here are half a row tile and the weight gradients are bound by memory, paths no other
+    config reaches."""
+    verify_streamed(xi.CONFIGS["large"], full_backward=True)
 
 
 @pytest.mark.parametrize("T", [16384, 32768, 65536])
-def test_full_size_longseq_sampled(T):
-    verify_sampled(xi.CONFIGS["longseq"].with_T(T), n_experts=8, n_tokens=1024)
+def test_full_size_longseq(T):
+    verify_streamed(xi.CONFIGS["longseq"].with_T(T), full_backward=False, n_experts=8, n_tokens=1024)
+
+
+@pytest.mark.parametrize("name", ["medium_mlp2", "large_mlp2", "super_mlp2"])
+def test_full_size_table3_mlp2(name):
+    """The two-matrix expert at the Medium, Large and Super shapes of Table 3 (one GPU's share of tokens), in full."""
+    verify_streamed(xi.CONFIGS[name], full_backward=True)
