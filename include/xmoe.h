@@ -227,12 +227,19 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t*
  * no [B,d] gradient of the expert outputs exists.  The scale is applied in float32 behind the matrix product
  * (dA = s * (dout Wd^T), dWd = (s * A)^T dout), so the product s * dout is not rounded to dt first; results agree
  * with the call on a materialised dY to rounding.  Entries of rows outside every segment are never read.
+ * dy_row_scale_grad: NULL, or [B] float32 (out): the gradient of the loss with respect to every row's scale,
+ *   dy_row_scale_grad[i] = <row i of dY before the scale, Y[i]>,  Y[i] = A[i] Wd_e the expert's output for that row,
+ * taken as sum_n (dY_unscaled[i] Wd^T)[n] * A[i,n] from the product the dAct GEMM forms anyway and the recomputed A,
+ * in a fixed summation order.  With dy_row_index / dy_row_scale = token_ids / combine_weights this is the gradient
+ * of the combine weights, row by row (xmoe_combine_bwd_weights puts it into slot order): Y, the second activation
+ * tensor that Section 3.2 / Table 2 counts as held for backward (A_combine), then need not be kept after the
+ * forward combine.  Entries of rows outside every segment are not written.
  * Outputs: dxd [B,d]; dwg, dwu [E,d,f]; dwd [E,f,d] - overwritten, all zero for an expert with no rows.
  * ws: XMOE_WS_FFN_BWD bytes.
  */
 int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
                         const void* dy, const int32_t* dy_row_index, const float* dy_row_scale,
-                        const int32_t* expert_offsets, int B, int E, int d, int f,
+                        float* dy_row_scale_grad, const int32_t* expert_offsets, int B, int E, int d, int f,
                         const void* wg, const void* wu, const void* wd,
                         void* dxd, void* dwg, void* dwu, void* dwd, int dt,
                         void* ws, size_t ws_bytes, void* stream);
@@ -251,14 +258,14 @@ int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t
 
 /* Backward of the two-matrix expert (derived; A is recomputed from the saved H):
  *   dA = dY W2^T;  dW2_e = A_e^T dY_e;  dH = dA * act'(H);  dXd = dH W1^T;  dW1_e = Xd_e^T dH_e.
- * dy_row_index, dy_row_scale: as in xmoe_expert_ffn_bwd.
+ * dy_row_index, dy_row_scale, dy_row_scale_grad: as in xmoe_expert_ffn_bwd.
  * Outputs: dxd [B,d]; dw1 [E,d,f]; dw2 [E,f,d] - overwritten, all zero for an expert with no rows.
  * ws: XMOE_WS_MLP2_BWD bytes.
  */
 int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
-                         const int32_t* dy_row_index, const float* dy_row_scale, const int32_t* expert_offsets, int B,
-                         int E, int d, int f, const void* w1, const void* w2, int act, void* dxd, void* dw1, void* dw2,
-                         int dt, void* ws, size_t ws_bytes, void* stream);
+                         const int32_t* dy_row_index, const float* dy_row_scale, float* dy_row_scale_grad,
+                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
+                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream);
 
 /* Combine (Section 4.1.2 / Appendix B.4 scatter kernel, which must accumulate since k rows share a token),
  * written as a gather-reduce so that no atomics are needed and the sum order is fixed:
@@ -280,6 +287,13 @@ int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
  */
 int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w,
                      int T, int k, int d, int dt, void* dy, float* dw, void* stream);
+
+/* The gradient of the combine weights from per-row inner products: dw[t,j] = row_grad[row_of_slot[t*k+j]], and 0 for
+ * a dropped entry (row -1).  row_grad [B] float32 holds <dout[token of row i], y[i]> for every PFT row i
+ * (dy_row_scale_grad of the expert MLP's backward); dw [T,k] float32 (out).  Together with that output it replaces
+ * xmoe_combine_bwd in a layer that keeps neither dY nor Y.
+ */
+int xmoe_combine_bwd_weights(const float* row_grad, const int32_t* row_of_slot, int T, int k, float* dw, void* stream);
 
 /* Backward of dispatch: dx[t,:] = sum_j dxd[row_of_slot[t*k+j],:] + sum_s shared_rows[s*T + t,:] (+ addend).
  * Same kernel as xmoe_combine with unit weights. */

@@ -25,16 +25,17 @@ SIGNATURES = {
     "xmoe_dispatch": (_c_int, [_c_void_p] * 2 + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_expert_ffn_fwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 6 + [_c_int, _c_void_p, _c_size_t,
                                                                                         _c_void_p]),
-    "xmoe_expert_ffn_bwd": (_c_int, [_c_void_p] * 8 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_int, _c_void_p, _c_size_t,
+    "xmoe_expert_ffn_bwd": (_c_int, [_c_void_p] * 9 + [_c_int] * 4 + [_c_void_p] * 7 + [_c_int, _c_void_p, _c_size_t,
                                                                                         _c_void_p]),
     "xmoe_expert_mlp2_fwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 2 + [_c_int] + [_c_void_p] * 2 +
                              [_c_int, _c_void_p, _c_size_t, _c_void_p]),
-    "xmoe_expert_mlp2_bwd": (_c_int, [_c_void_p] * 7 + [_c_int] * 4 + [_c_void_p] * 2 + [_c_int] + [_c_void_p] * 3 +
+    "xmoe_expert_mlp2_bwd": (_c_int, [_c_void_p] * 8 + [_c_int] * 4 + [_c_void_p] * 2 + [_c_int] + [_c_void_p] * 3 +
                              [_c_int, _c_void_p, _c_size_t, _c_void_p]),
     "xmoe_rbd_stage0": (_c_int, [_c_void_p] * 6 + [_c_int] * 4 + [_c_void_p] * 12 + [_c_size_t, _c_void_p]),
     "xmoe_rbd_absolute_index": (_c_int, [_c_void_p] * 3 + [_c_int] * 2 + [_c_void_p] * 2),
     "xmoe_combine": (_c_int, [_c_void_p] * 4 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_combine_bwd": (_c_int, [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p] * 3),
+    "xmoe_combine_bwd_weights": (_c_int, [_c_void_p] * 2 + [_c_int] * 2 + [_c_void_p] * 2),
     "xmoe_dispatch_bwd": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_route_bwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 3 + [_c_void_p] * 2),
     "xmoe_gate_logits_bwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 3 + [_c_size_t, _c_void_p]),

@@ -25,7 +25,7 @@ __all__ = [
     "xmoe_prof_read", "xmoe_prof_copy", "xmoe_prof_shader_clocks", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
     "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
-    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0", "xmoe_build_eri_static",
+    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0", "xmoe_build_eri_static", "xmoe_combine_bwd_weights",
 ]
 
 
@@ -211,9 +211,10 @@ def _check_dy(dy, B, d, dy_row_index, dy_row_scale):
 
 
 def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd, dwg, dwu, dwd, ws,
-                        row_index=None, dy_row_index=None, dy_row_scale=None) -> None:
+                        row_index=None, dy_row_index=None, dy_row_scale=None, dy_row_scale_grad=None) -> None:
     """dy_row_index: None, or token ids [B]: dy is then dout [T,d] and row i of dY is dy_row_scale[i] * dout[dy_row_index[i]]
-    (dy_row_scale None = 1): the backward of combine fused into the operand loads."""
+    (dy_row_scale None = 1): the backward of combine fused into the operand loads.
+    dy_row_scale_grad: None, or a float32 [B] output for <row i of dY before the scale, Y[i]>."""
     B = xd.shape[0] if row_index is None else row_index.numel()
     d = xd.shape[1]
     E, d2, f = wg.shape
@@ -226,7 +227,7 @@ def xmoe_expert_ffn_bwd(xd, g_save, u_save, dy, expert_offsets, wg, wu, wd, dxd,
     _check(lib().xmoe_expert_ffn_bwd(
         _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(g_save, dt, "g_save"),
         _ptr(u_save, dt, "u_save"), _ptr(dy, dt, "dy"), _ptr(dy_row_index, torch.int32, "dy_row_index"),
-        _ptr(dy_row_scale, torch.float32, "dy_row_scale"),
+        _ptr(dy_row_scale, torch.float32, "dy_row_scale"), _ptr(dy_row_scale_grad, torch.float32, "dy_row_scale_grad"),
         _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(wg, dt), _ptr(wu, dt), _ptr(wd, dt),
         _ptr(dxd, dt, "dxd"), _ptr(dwg, dt, "dwg"), _ptr(dwu, dt, "dwu"), _ptr(dwd, dt, "dwd"), dtype_code(dt),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_ffn_bwd")
@@ -248,7 +249,7 @@ def xmoe_expert_mlp2_fwd(xd, expert_offsets, w1, w2, act: str, h_save, y, ws, ro
 
 
 def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, dw1, dw2, ws, row_index=None,
-                         dy_row_index=None, dy_row_scale=None) -> None:
+                         dy_row_index=None, dy_row_scale=None, dy_row_scale_grad=None) -> None:
     B = xd.shape[0] if row_index is None else row_index.numel()
     d = xd.shape[1]
     E, d2, f = w1.shape
@@ -260,7 +261,7 @@ def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, 
     _check(lib().xmoe_expert_mlp2_bwd(
         _ptr(xd, None, "xd"), _ptr(row_index, torch.int32, "row_index"), _ptr(h_save, dt, "h_save"),
         _ptr(dy, dt, "dy"), _ptr(dy_row_index, torch.int32, "dy_row_index"),
-        _ptr(dy_row_scale, torch.float32, "dy_row_scale"),
+        _ptr(dy_row_scale, torch.float32, "dy_row_scale"), _ptr(dy_row_scale_grad, torch.float32, "dy_row_scale_grad"),
         _ptr(expert_offsets, torch.int32, "expert_offsets"), B, E, d, f, _ptr(w1, dt, "w1"),
         _ptr(w2, dt, "w2"), ACT_CODES[act], _ptr(dxd, dt, "dxd"), _ptr(dw1, dt, "dw1"), _ptr(dw2, dt, "dw2"),
         dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_mlp2_bwd")
@@ -292,6 +293,15 @@ def xmoe_combine_bwd(dout, y, row_of_slot, topk_w, dy, dw) -> None:
                                   _ptr(row_of_slot, torch.int32, "row_of_slot"),
                                   _ptr(topk_w, torch.float32, "topk_w"), T, k, d, dtype_code(dt), _ptr(dy, dt, "dy"),
                                   _ptr(dw, torch.float32, "dw"), _stream()), "xmoe_combine_bwd")
+
+
+def xmoe_combine_bwd_weights(row_grad, row_of_slot, dw) -> None:
+    """dw[t,j] = row_grad[row_of_slot[t*k+j]] (0 for a dropped entry)."""
+    T, k = dw.shape
+    assert row_of_slot.numel() == T * k
+    _check(lib().xmoe_combine_bwd_weights(_ptr(row_grad, torch.float32, "row_grad"),
+                                          _ptr(row_of_slot, torch.int32, "row_of_slot"), T, k,
+                                          _ptr(dw, torch.float32, "dw"), _stream()), "xmoe_combine_bwd_weights")
 
 
 def xmoe_dispatch_bwd(dxd, row_of_slot, shared_rows, addend, k: int, dx) -> None:

@@ -34,6 +34,8 @@ const char* const kKernelNames[K_COUNT] = {
     "gate_bwd_dw_reduce_kernel",
     "gate_bwd_dx_kernel",
     "tile_map_kernel",
+    "row_grad_reduce_kernel",
+    "combine_bwd_weights_kernel",
     "ffn_gateup_simt_kernel",
     "ffn_down_simt_kernel",
     "ffn_dact_simt_kernel",

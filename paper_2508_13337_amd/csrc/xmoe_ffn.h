@@ -22,6 +22,10 @@ struct FfnArgs {
     int32_t* map;                // tile map
     int32_t* sched;              // experts by descending row count [E], then kSchedCounters counters
     void *act, *dg, *du;         // A = silu(G)*U, dG, dU   [B,f]
+    // backward, optional: row_grad [B] (caller's) receives <unscaled row of dY, Y[row]> for every row; row_part is
+    // the workspace for its partial sums, row_grad_parts(f) x B floats laid out [part][row]
+    float* row_grad;
+    float* row_part;
 };
 
 // the two-matrix expert (xmoe_expert_mlp2_fwd / _bwd)
@@ -38,10 +42,15 @@ struct Mlp2Args {
     int32_t* map;
     int32_t* sched;
     void *a_buf, *dh;            // A = act(H), dH   [B,f]
+    float* row_grad;             // as in FfnArgs
+    float* row_part;
 };
 
 int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int32_t* map, int32_t* sched,
                     hipStream_t s);
+
+// row_grad[i] = sum over p < parts of row_part[p * B + i], p ascending (fixed order: the result is reproducible)
+int launch_row_grad_reduce(const float* row_part, int parts, int B, float* row_grad, hipStream_t s);
 
 int ffn_fwd_simt(const FfnArgs& a, hipStream_t s);
 int ffn_bwd_simt(const FfnArgs& a, hipStream_t s);

@@ -49,6 +49,7 @@ int xmoe_expert_ffn_fwd(const void* xd, const int32_t* row_index, const int32_t*
 
 int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_save, const void* u_save,
                         const void* dy, const int32_t* dy_row_index, const float* dy_row_scale,
+                        float* dy_row_scale_grad,
                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* wg, const void* wu,
                         const void* wd, void* dxd, void* dwg, void* dwu, void* dwd, int dt, void* ws,
                         size_t ws_bytes, void* stream) {
@@ -77,6 +78,9 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     a.du = p;
     p += ffn_act_bytes(B, f, dt);
     a.act = p;
+    p += ffn_act_bytes(B, f, dt);
+    a.row_grad = dy_row_scale_grad;
+    a.row_part = dy_row_scale_grad ? (float*)p : nullptr;
     hipStream_t s = (hipStream_t)stream;
     if (ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
     return ffn_bwd_simt(a, s);
@@ -110,9 +114,9 @@ int xmoe_expert_mlp2_fwd(const void* xd, const int32_t* row_index, const int32_t
 }
 
 int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h_save, const void* dy,
-                         const int32_t* dy_row_index, const float* dy_row_scale, const int32_t* expert_offsets, int B,
-                         int E, int d, int f, const void* w1, const void* w2, int act, void* dxd, void* dw1, void* dw2,
-                         int dt, void* ws, size_t ws_bytes, void* stream) {
+                         const int32_t* dy_row_index, const float* dy_row_scale, float* dy_row_scale_grad,
+                         const int32_t* expert_offsets, int B, int E, int d, int f, const void* w1, const void* w2,
+                         int act, void* dxd, void* dw1, void* dw2, int dt, void* ws, size_t ws_bytes, void* stream) {
     int st = check_common(B, E, d, f, dt);
     if (st != XMOE_OK) return st;
     if (!act_ok(act)) return XMOE_ERR_UNSUPPORTED;
@@ -137,6 +141,9 @@ int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h
     a.dh = p;
     p += ffn_act_bytes(B, f, dt);
     a.a_buf = p;
+    p += ffn_act_bytes(B, f, dt);
+    a.row_grad = dy_row_scale_grad;
+    a.row_part = dy_row_scale_grad ? (float*)p : nullptr;
     hipStream_t s = (hipStream_t)stream;
     if (mlp2_dma_supported(a)) return mlp2_bwd_dma(a, s);
     return mlp2_bwd_simt(a, s);

@@ -553,6 +553,14 @@ __device__ __forceinline__ void strip_put(char* strip, int col0, const float (&x
     }
 }
 
+// the q-th quarter of strip_put: this lane's values 4q .. 4q+3 of a 32 x 32 accumulator tile (written as soon as they
+// exist, so that an epilogue that derives several tiles from one accumulator never holds them all as floats)
+__device__ __forceinline__ void strip_put4(char* strip, int col0, int q, float a, float b, float c, float d) {
+    const int lane = threadIdx.x & 63;
+    const int n = col0 + 8 * q + 4 * (lane >> 5);
+    *reinterpret_cast<uint2*>(strip + (lane & 31) * kStripStride + n * 2) = pack4(a, b, c, d);
+}
+
 // writes strip columns [col0, col0 + NC) of rows [0, rows_valid) to C (row stride ldc); columns >= cols_valid
 // (a multiple of 4) are skipped.  NC = 32 or 64.  NT: streaming stores for results that this launch never reads
 // again and that are written as whole 128-byte lines: they then do not displace the operand panels the workgroups of
@@ -810,6 +818,11 @@ __global__ __launch_bounds__(512) void ffn_gateup_dma_kernel(const bf16_t* __res
 // DY_GATHER (backward 1 only): X is the [T, K] gradient of the layer's output and row i of dY is
 // x_scale[i] * X[x_index[i]] (the backward of combine folded into this GEMM: dA = s * (dOut Wd^T), and the A that
 // the weight-gradient kernel multiplies with the gathered dOut rows is written as s * A); x_scale NULL = 1.
+// row_part (backward 1 only, may be NULL): partial sums of <unscaled row of dY, Y[row]> = sum_n P[row, n] A[row, n]
+// with P the accumulator before the scale and A the unscaled activation - the gradient of the row's scale, i.e. of
+// its combine weight, taken here so that nobody has to keep Y for it.  A wave writes the sum over its 64 columns of
+// the rows it owns to row_part[(column tile * 4 + wave column) * row_part_ld + row]; the order of the additions is
+// fixed, and a later kernel adds the partials of a row in ascending order.
 template <bool DACT, bool DY_GATHER = false>
 __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __restrict__ X,
                                                               const int32_t* __restrict__ x_index,
@@ -820,6 +833,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                                                               const bf16_t* __restrict__ G,
                                                               const bf16_t* __restrict__ U, bf16_t* __restrict__ dG,
                                                               bf16_t* __restrict__ dU, bf16_t* __restrict__ A,
+                                                              float* __restrict__ row_part, long row_part_ld,
                                                               int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
     clock_note(clk, 0);
@@ -895,6 +909,7 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             }
         };
         fetch(0, gq[0], uq[0]);
+        float rowpart = 0.f;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int mi = r >> 1, ni = r & 1;
@@ -919,26 +934,38 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             }
             float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
             if (DY_GATHER && x_scale && m < rows_valid) sc = x_scale[rt.row0 + r0 + m];
-            float dg[16], du[16], av[16];
+            float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row>
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const uint32_t gw[2] = {gv[q].x, gv[q].y}, uw[2] = {uv[q].x, uv[q].y};
+                float dg[4], du[4], av[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
                     const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
                     const float g = __uint_as_float(gb), u = __uint_as_float(ub);
-                    const float da = DY_GATHER ? acc[mi][ni][4 * q + j] * sc : acc[mi][ni][4 * q + j];
+                    const float pa = acc[mi][ni][4 * q + j];
+                    const float da = DY_GATHER ? pa * sc : pa;
                     const float sg = fast_sigmoid(g);
                     const float sl = g * sg;
-                    dg[4 * q + j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
-                    du[4 * q + j] = da * sl;
-                    av[4 * q + j] = DY_GATHER ? sl * u * sc : sl * u;
+                    const float a1 = sl * u;
+                    dg[j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
+                    du[j] = da * sl;
+                    av[j] = DY_GATHER ? a1 * sc : a1;
+                    part = fmaf(pa, a1, part);
+                }
+                strip_put4(strip, 0, q, dg[0], dg[1], dg[2], dg[3]);
+                strip_put4(strip, 32, q, du[0], du[1], du[2], du[3]);
+                strip_put4(strip, 64, q, av[0], av[1], av[2], av[3]);
+            }
+            if (row_part) {   // (wave-uniform) the two column halves of the row block, then the lane pair of a row
+                rowpart = ni == 0 ? part : rowpart + part;
+                if (ni == 1) {
+                    const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
+                    if (lane < 32 && m < rows_valid)
+                        row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
                 }
             }
-            strip_put(strip, 0, dg);
-            strip_put(strip, 32, du);
-            strip_put(strip, 64, av);
             strip_sync();
             const long o = base + ni * 32;
             strip_flush<32>(strip, 0, dG + o, N, rows_valid, cols_valid - ni * 32);
@@ -1130,6 +1157,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ w2,
                                                             const bf16_t* __restrict__ H, bf16_t* __restrict__ dH,
                                                             bf16_t* __restrict__ A,
+                                                            float* __restrict__ row_part, long row_part_ld,
                                                             int32_t* __restrict__ counters, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
     clock_note(clk, 0);
@@ -1173,6 +1201,7 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
             }
         };
         fetch(0, hq[0]);
+        float rowpart = 0.f;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int mi = r >> 1, ni = r & 1;
@@ -1193,21 +1222,32 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                 hv[q] = *reinterpret_cast<const uint2*>(inbuf + m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5));
             float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
             if (DY_GATHER && dy_scale && m < rows_valid) sc = dy_scale[rt.row0 + r0 + m];
-            float dh[16], av[16];
+            float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row> (see ffn_rowgemm_dma_kernel)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const uint32_t hw[2] = {hv[q].x, hv[q].y};
+                float dh[4], av[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t hb = (j & 1) ? (hw[j >> 1] & 0xffff0000u) : (hw[j >> 1] << 16);
                     float a_, g_;
                     act_fast_grad<ACT>(__uint_as_float(hb), a_, g_);
-                    dh[4 * q + j] = DY_GATHER ? acc[mi][ni][4 * q + j] * sc * g_ : acc[mi][ni][4 * q + j] * g_;
-                    av[4 * q + j] = DY_GATHER ? a_ * sc : a_;
+                    const float pa = acc[mi][ni][4 * q + j];
+                    dh[j] = DY_GATHER ? pa * sc * g_ : pa * g_;
+                    av[j] = DY_GATHER ? a_ * sc : a_;
+                    part = fmaf(pa, a_, part);
+                }
+                strip_put4(strip, 0, q, dh[0], dh[1], dh[2], dh[3]);
+                strip_put4(strip, 32, q, av[0], av[1], av[2], av[3]);
+            }
+            if (row_part) {
+                rowpart = ni == 0 ? part : rowpart + part;
+                if (ni == 1) {
+                    const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
+                    if (lane < 32 && m < rows_valid)
+                        row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
                 }
             }
-            strip_put(strip, 0, dh);
-            strip_put(strip, 32, av);
             strip_sync();
             const long o = base + ni * 32;
             strip_flush<32>(strip, 0, dH + o, f, rows_valid, cols_valid - ni * 32);
@@ -1502,7 +1542,7 @@ int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
                 hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.act, nullptr, nullptr, a.off, a.map, a.f, a.d, wd,
                                    (bf16_t*)a.y, nullptr,
-                                   nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
+                                   nullptr, nullptr, nullptr, nullptr, (float*)nullptr, 0L, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
     return XMOE_OK;
 }
 
@@ -1521,13 +1561,17 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                     hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, true>), dim3(round_up8((long)max_tiles * ntf)),
                                        dim3(512), kLdsBytes, s, dy, a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f, wd,
                                        nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
-                                       row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
+                                       a.row_part, (long)a.B, row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
     else
         XMOE_LAUNCH(K_FFN_DACT_DMA, s,
                     hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<true, false>), dim3(round_up8((long)max_tiles * ntf)),
                                        dim3(512), kLdsBytes, s, dy, nullptr, nullptr, a.off, a.map, a.d, a.f, wd,
                                        nullptr, (const bf16_t*)a.g, (const bf16_t*)a.u, dg, du, act,
-                                       row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
+                                       a.row_part, (long)a.B, row_counters(a.sched, a.E, 0), clock_slot(CS_DACT)));
+    if (a.row_grad) {
+        st = launch_row_grad_reduce(a.row_part, 4 * ntf, a.B, a.row_grad, s);
+        if (st != XMOE_OK) return st;
+    }
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     const int ntf2 = (a.f + 127) / 128;
     if (bwd_merged()) {
@@ -1619,7 +1663,7 @@ int mlp2_fwd_dma(const Mlp2Args& a, hipStream_t s) {
                 hipLaunchKernelGGL((ffn_rowgemm_dma_kernel<false, false>), dim3(round_up8((long)max_tiles * ntd)), dim3(512),
                                    kLdsBytes, s, (const bf16_t*)a.a_buf, nullptr, nullptr, a.off, a.map, a.f, a.d, w2,
                                    (bf16_t*)a.y,
-                                   nullptr, nullptr, nullptr, nullptr, nullptr, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
+                                   nullptr, nullptr, nullptr, nullptr, nullptr, (float*)nullptr, 0L, row_counters(a.sched, a.E, 1), clock_slot(CS_DOWN)));
     return XMOE_OK;
 }
 
@@ -1639,7 +1683,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
                 hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, true>), grid, dim3(512), kLdsBytes, s, dy, a.dy_index, \
                                    a.dy_scale, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,            \
-                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
+                                   a.row_part, (long)a.B, row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
     } else {
@@ -1647,9 +1691,13 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_DACT_DMA, s,                                                                                 \
                 hipLaunchKernelGGL((mlp2_dact_dma_kernel<ACT, false>), grid, dim3(512), kLdsBytes, s, dy, nullptr,  \
                                    nullptr, a.off, a.map, a.d, a.f, w2, (const bf16_t*)a.h, dh, act,               \
-                                   row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
+                                   a.row_part, (long)a.B, row_counters(a.sched, a.E, 0), clock_slot(CS_MLP2_DACT)))
         XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
+    }
+    if (a.row_grad) {
+        st = launch_row_grad_reduce(a.row_part, 4 * ntf, a.B, a.row_grad, s);
+        if (st != XMOE_OK) return st;
     }
     const int mtf = (a.f + TM - 1) / TM, mtd = (a.d + TM - 1) / TM;
     if (bwd_merged()) {

@@ -70,6 +70,31 @@ int launch_tile_map(const int32_t* off, int E, int tile_rows, int max_tiles, int
     return XMOE_OK;
 }
 
+// row_grad[i] = sum_p row_part[p * B + i], p ascending
+__global__ __launch_bounds__(256) void row_grad_reduce_kernel(const float* __restrict__ row_part, int parts, int B,
+                                                              float* __restrict__ row_grad) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= B) return;
+    float s = 0.f;
+    for (int p = 0; p < parts; ++p) s += row_part[(size_t)p * B + i];
+    row_grad[i] = s;
+}
+
+int launch_row_grad_reduce(const float* row_part, int parts, int B, float* row_grad, hipStream_t s) {
+    if (B <= 0) return XMOE_OK;
+    XMOE_LAUNCH(K_ROW_GRAD_REDUCE, s,
+                hipLaunchKernelGGL(row_grad_reduce_kernel, dim3((B + 255) / 256), dim3(256), 0, s, row_part, parts, B,
+                                   row_grad));
+    return XMOE_OK;
+}
+
+// sum of v over the 16 threads that share a row patch (tx = 0..15: consecutive lanes), in a fixed order
+__device__ __forceinline__ float sum_over_tx(float v) {
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // forward 1: G = Xd Wg, U = Xd Wu, A = silu(G) * U          rows: ragged, K = d, N = f
 // ---------------------------------------------------------------------------------------------------------
@@ -155,7 +180,8 @@ __global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict_
                                                             const int32_t* __restrict__ map, int d, int f,
                                                             const T* __restrict__ wd, const T* __restrict__ G,
                                                             const T* __restrict__ U, T* __restrict__ dG,
-                                                            T* __restrict__ dU, T* __restrict__ A) {
+                                                            T* __restrict__ dU, T* __restrict__ A,
+                                                            float* __restrict__ row_part, int B) {
     __shared__ SimtSmem sm;
     const int e = map[4 + 2 * blockIdx.x];
     if (e < 0) return;
@@ -175,7 +201,8 @@ __global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict_
         [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(wde[(size_t)n * d + kk]) : 0.f; });
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+        float part = 0.f;   // <unscaled dY row, Y row> over this thread's columns (the gradient of the row's scale)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
@@ -188,8 +215,15 @@ __global__ __launch_bounds__(256) void ffn_dact_simt_kernel(const T* __restrict_
                 dG[ix] = from_float<T>(da * u * (sg * (1.0f + g * (1.0f - sg))));
                 dU[ix] = from_float<T>(da * sl);
                 A[ix] = from_float<T>(sl * u * sc);   // scaled: the weight gradient multiplies it with unscaled rows
+                part = fmaf(acc[i][j], sl * u, part);
             }
         }
+        if (row_part) {   // block-uniform
+            part = sum_over_tx(part);
+            const int r = row0 + ty * 4 + i;
+            if (tx == 0 && r < row_end) row_part[(size_t)blockIdx.y * B + r] = part;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -318,7 +352,8 @@ __global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict
                                                              const int32_t* __restrict__ off,
                                                              const int32_t* __restrict__ map, int d, int f,
                                                              const T* __restrict__ w2, const T* __restrict__ H,
-                                                             T* __restrict__ dH, T* __restrict__ A) {
+                                                             T* __restrict__ dH, T* __restrict__ A,
+                                                             float* __restrict__ row_part, int B) {
     __shared__ SimtSmem sm;
     const int e = map[4 + 2 * blockIdx.x];
     if (e < 0) return;
@@ -338,7 +373,8 @@ __global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict
         [&](int kk, int nn) { int n = n0 + nn; return n < f ? to_float(w2e[(size_t)n * d + kk]) : 0.f; });
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+        float part = 0.f;   // as in ffn_dact_simt_kernel
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int r = row0 + ty * 4 + i, n = n0 + tx * 4 + j;
@@ -349,8 +385,15 @@ __global__ __launch_bounds__(256) void mlp2_dact_simt_kernel(const T* __restrict
                 const float sc = (dy_index && dy_scale) ? dy_scale[r] : 1.0f;
                 dH[ix] = from_float<T>(acc[i][j] * sc * g);
                 A[ix] = from_float<T>(a * sc);
+                part = fmaf(acc[i][j], a, part);
             }
         }
+        if (row_part) {
+            part = sum_over_tx(part);
+            const int r = row0 + ty * 4 + i;
+            if (tx == 0 && r < row_end) row_part[(size_t)blockIdx.y * B + r] = part;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -381,7 +424,11 @@ static int bwd_simt(const FfnArgs& a, hipStream_t s) {
     XMOE_LAUNCH(K_FFN_DACT_SIMT, s,
                 hipLaunchKernelGGL(ffn_dact_simt_kernel<T>, dim3(max_tiles, tf), dim3(256), 0, s, (const T*)a.dy,
                                    a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f, (const T*)a.wd, (const T*)a.g, (const T*)a.u, (T*)a.dg, (T*)a.du,
-                                   (T*)a.act));
+                                   (T*)a.act, a.row_part, a.B));
+    if (a.row_grad) {
+        st = launch_row_grad_reduce(a.row_part, tf, a.B, a.row_grad, s);
+        if (st != XMOE_OK) return st;
+    }
     XMOE_LAUNCH(K_FFN_DX_SIMT, s,
                 hipLaunchKernelGGL(ffn_dx_simt_kernel<T>, dim3(max_tiles, td), dim3(256), 0, s, (const T*)a.dg,
                                    (const T*)a.du, a.off, a.map, a.d, a.f, (const T*)a.wg, (const T*)a.wu, (T*)a.dxd));
@@ -425,9 +472,13 @@ static int mlp2_bwd_simt_t(const Mlp2Args& a, hipStream_t s) {
     XMOE_LAUNCH(K_MLP2_DACT_SIMT, s,                                                                            \
                 hipLaunchKernelGGL((mlp2_dact_simt_kernel<T, ACT>), dim3(max_tiles, tf), dim3(256), 0, s,       \
                                    (const T*)a.dy, a.dy_index, a.dy_scale, a.off, a.map, a.d, a.f,              \
-                                   (const T*)a.w2, (const T*)a.h, (T*)a.dh, (T*)a.a_buf))
+                                   (const T*)a.w2, (const T*)a.h, (T*)a.dh, (T*)a.a_buf, a.row_part, a.B))
     XMOE_DISPATCH_ACT(a.act, XMOE_CALL);
 #undef XMOE_CALL
+    if (a.row_grad) {
+        st = launch_row_grad_reduce(a.row_part, tf, a.B, a.row_grad, s);
+        if (st != XMOE_OK) return st;
+    }
     XMOE_LAUNCH(K_FFN_DX_SIMT, s,
                 hipLaunchKernelGGL(ffn_dx_simt_kernel<T>, dim3(max_tiles, td), dim3(256), 0, s, (const T*)a.dh,
                                    (const T*)nullptr, a.off, a.map, a.d, a.f, (const T*)a.w1, (const T*)nullptr,

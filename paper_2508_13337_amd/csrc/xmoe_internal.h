@@ -26,6 +26,8 @@ enum KernelId : int {
     K_GATE_BWD_DW_REDUCE,
     K_GATE_BWD_DX,
     K_TILE_MAP,
+    K_ROW_GRAD_REDUCE,
+    K_COMBINE_BWD_W,
     K_FFN_GATEUP_SIMT,
     K_FFN_DOWN_SIMT,
     K_FFN_DACT_SIMT,

@@ -284,6 +284,16 @@ static int launch_combine_bwd(const void* dout, const void* y, const int32_t* ro
     return XMOE_OK;
 }
 
+// dw[n] = row_grad[row_of_slot[n]], 0 for a dropped entry
+__global__ __launch_bounds__(256) void combine_bwd_weights_kernel(const float* __restrict__ row_grad,
+                                                                  const int32_t* __restrict__ ros, int n,
+                                                                  float* __restrict__ dw) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int r = ros[i];
+    dw[i] = r >= 0 ? row_grad[r] : 0.f;
+}
+
 static int check_rows_args(int T, int k, int d, int dt) {
     if (!dtype_ok(dt)) return XMOE_ERR_UNSUPPORTED;
     if (T < 0 || k < 1 || d < 1) return XMOE_ERR_INVALID_ARG;
@@ -334,6 +344,19 @@ int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot
     hipStream_t s = (hipStream_t)stream;
     return dt == XMOE_F32 ? launch_combine_bwd<float>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s)
                           : launch_combine_bwd<bf16_t>(dout, y, row_of_slot, topk_w, T, k, d, dy, dw, s);
+}
+
+int xmoe_combine_bwd_weights(const float* row_grad, const int32_t* row_of_slot, int T, int k, float* dw,
+                             void* stream) {
+    if (T < 0 || k < 1 || (long long)T * k >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (T == 0) return XMOE_OK;
+    if (!row_grad || !row_of_slot || !dw) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const int n = T * k;
+    XMOE_LAUNCH(K_COMBINE_BWD_W, s,
+                hipLaunchKernelGGL(combine_bwd_weights_kernel, dim3((n + 255) / 256), dim3(256), 0, s, row_grad,
+                                   row_of_slot, n, dw));
+    return XMOE_OK;
 }
 
 }  // extern "C"

@@ -39,13 +39,20 @@ static inline size_t ffn_tilemap_bytes(int B, int E) {
 }
 static inline size_t ffn_act_bytes(int B, int f, int dt) { return align_up((size_t)B * (size_t)f * dtype_size(dt), 256); }
 
+// partial sums of the per-row inner products <dY row, Y row> that the dAct kernels produce: one per row and per
+// 64 output columns of the matrix-core kernels' 256-column tiles (the float32-ALU kernels, 64-column tiles, use fewer)
+static inline int row_grad_parts(int f) { return (f + 255) / 256 * 4; }
+static inline size_t row_part_bytes(int B, int f) {
+    return align_up((size_t)row_grad_parts(f) * (size_t)(B > 0 ? B : 1) * sizeof(float), 256);
+}
+
 static inline size_t ffn_fwd_ws_bytes(int B, int E, int d, int f, int dt) {
     (void)d;
     return ffn_tilemap_bytes(B, E) + ffn_act_bytes(B, f, dt);                 // tile map | A = silu(G)*U
 }
 static inline size_t ffn_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
     (void)d;
-    return ffn_tilemap_bytes(B, E) + 3 * ffn_act_bytes(B, f, dt);             // tile map | dG | dU | A
+    return ffn_tilemap_bytes(B, E) + 3 * ffn_act_bytes(B, f, dt) + row_part_bytes(B, f);   // tile map | dG | dU | A | partials
 }
 
 // two-matrix expert: tile map | A = act(H)   and   tile map | dH | A
@@ -55,7 +62,7 @@ static inline size_t mlp2_fwd_ws_bytes(int B, int E, int d, int f, int dt) {
 }
 static inline size_t mlp2_bwd_ws_bytes(int B, int E, int d, int f, int dt) {
     (void)d;
-    return ffn_tilemap_bytes(B, E) + 2 * ffn_act_bytes(B, f, dt);
+    return ffn_tilemap_bytes(B, E) + 2 * ffn_act_bytes(B, f, dt) + row_part_bytes(B, f);
 }
 
 // ----- stage 0 of the redundancy-bypassing dispatch: pilot flags, pilot row of every row, pilot prefix, chunk counts

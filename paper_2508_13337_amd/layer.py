@@ -23,9 +23,12 @@ class XMoELayer:
 
     The gather of dispatch is fused into the expert MLP's operand loads: the MLP reads x through token_ids, and no
     [B,d] copy of the tokens exists.  The backward of combine is fused the same way (fuse_combine_bwd, the default):
-    the MLP's backward reads dOut through token_ids and scales by combine_weights, xmoe_combine_bwd only computes the
-    gradient of the combine weights, and no [B,d] gradient of the expert outputs exists.  (Without it dY is written
-    by xmoe_combine_bwd, and xmoe_dispatch copies dOut into the shared experts' dY rows.)
+    the MLP's backward reads dOut through token_ids and scales by combine_weights, so no [B,d] gradient of the expert
+    outputs exists, and it also returns the gradient of every row's combine weight (dy_row_scale_grad), which
+    xmoe_combine_bwd_weights puts into slot order: the expert outputs Y are then read by the forward combine only
+    and nothing but G and U is held between forward and backward.  (Without fuse_combine_bwd, xmoe_combine_bwd
+    reads Y back for the weights' gradient and writes dY, and xmoe_dispatch copies dOut into the shared experts'
+    dY rows.)
     Shared experts (every token, weight 1) run inside the same grouped-GEMM launches as the routed ones: they are
     experts E .. E+E_s-1 whose segments are rows [B + s*T, B + (s+1)*T) and read x[0..T-1], so the tail of
     expert_offsets and of token_ids is constant and written once here."""
@@ -69,6 +72,7 @@ class XMoELayer:
         self.out = torch.empty((T, d), **act)
         # backward
         self.dy = None if fuse_combine_bwd else torch.empty((R, d), **act)
+        self.row_grad = torch.empty(R, **f32) if fuse_combine_bwd else None   # gradient of every row's combine weight
         self.dw = torch.empty((T, k), **f32)
         self.dxd = torch.empty((R, d), **act)
         self.dlogits = torch.empty((T, E), **f32)
@@ -114,13 +118,14 @@ class XMoELayer:
         """grads: preallocated dw_router, dwg, dwu, dwd in the layouts of the weights."""
         B, E, T = self.B, self.E, self.T
         fused = self.fuse_combine_bwd
-        api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, None if fused else self.dy[:B], self.dw)
+        if not fused:
+            api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, self.dy[:B], self.dw)
         if self.max_token_count is None:
             if fused:
                 api.xmoe_expert_ffn_bwd(x, self.g, self.u, dout, self.offsets_all, w["wg"], w["wu"], w["wd"],
                                         self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
                                         row_index=self.token_ids_all, dy_row_index=self.token_ids_all,
-                                        dy_row_scale=self.combine_weights_all)
+                                        dy_row_scale=self.combine_weights_all, dy_row_scale_grad=self.row_grad)
             else:
                 if self.E_s > 0:   # dY of a shared expert's rows is dout itself
                     api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
@@ -132,13 +137,16 @@ class XMoELayer:
                                     w["wg"][:E], w["wu"][:E], w["wd"][:E], self.dxd[:B], grads["dwg"][:E],
                                     grads["dwu"][:E], grads["dwd"][:E], self.ws, row_index=self.token_ids,
                                     dy_row_index=self.token_ids if fused else None,
-                                    dy_row_scale=self.combine_weights if fused else None)
+                                    dy_row_scale=self.combine_weights if fused else None,
+                                    dy_row_scale_grad=self.row_grad[:B] if fused else None)
             for s in range(self.E_s):
                 seg = slice(B + s * T, B + (s + 1) * T)
                 one = slice(E + s, E + s + 1)
                 api.xmoe_expert_ffn_bwd(x, self.g[seg], self.u[seg], dout, self.one_segment, w["wg"][one],
                                         w["wu"][one], w["wd"][one], self.dxd[seg], grads["dwg"][one],
                                         grads["dwu"][one], grads["dwd"][one], self.ws)
+        if fused:
+            api.xmoe_combine_bwd_weights(self.row_grad, self.row_of_slot, self.dw)
         api.xmoe_route_bwd(self.logits, self.topk_idx, self.dw, self.dlogits)
         api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
         api.xmoe_dispatch_bwd(self.dxd[:B], self.row_of_slot, self._shared(self.dxd), self.dx_gate, self.k, self.dx)
@@ -191,6 +199,7 @@ class XMoE2Layer:
         self.y = torch.empty((B, d), **tt)
         self.out = torch.empty((T, d), **tt)
         self.dy = None if fuse_combine_bwd else torch.empty((B, d), **tt)
+        self.row_grad = torch.empty(B, **f32) if fuse_combine_bwd else None
         self.dw = torch.empty((T, k), **f32)
         self.dxd = torch.empty((B, d), **tt)
         self.dlogits = torch.empty((T, E), **f32)
@@ -215,11 +224,12 @@ class XMoE2Layer:
 
     def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
         """grads: preallocated dw_router, dw1, dw2 in the layouts of the weights."""
-        if self.fuse_combine_bwd:   # dY is never written: the MLP's backward reads dOut through token_ids
-            api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, None, self.dw)
+        if self.fuse_combine_bwd:   # dY is never written and Y is not read back (see XMoELayer)
             api.xmoe_expert_mlp2_bwd(x, self.h, dout, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,
                                      grads["dw1"], grads["dw2"], self.ws, row_index=self.token_ids,
-                                     dy_row_index=self.token_ids, dy_row_scale=self.combine_weights)
+                                     dy_row_index=self.token_ids, dy_row_scale=self.combine_weights,
+                                     dy_row_scale_grad=self.row_grad)
+            api.xmoe_combine_bwd_weights(self.row_grad, self.row_of_slot, self.dw)
         else:
             api.xmoe_combine_bwd(dout, self.y, self.row_of_slot, self.topk_w, self.dy, self.dw)
             api.xmoe_expert_mlp2_bwd(x, self.h, self.dy, self.expert_offsets, w["w1"], w["w2"], self.act, self.dxd,

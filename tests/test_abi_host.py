@@ -94,10 +94,15 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.xmoe_dispatch(null, p, 16, 32, 64, 0, p, null) == INVALID
     assert lib.xmoe_expert_ffn_fwd(p, null, p, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 16, null) == WORKSPACE
     assert lib.xmoe_expert_ffn_fwd(p, null, null, 32, 8, 64, 32, p, p, p, p, p, p, 1, p, 1 << 30, null) == INVALID
-    assert lib.xmoe_expert_ffn_bwd(p, null, p, p, p, null, null, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 16,
+    assert lib.xmoe_expert_ffn_bwd(p, null, p, p, p, null, null, null, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 16,
                                    null) == WORKSPACE
-    assert lib.xmoe_expert_ffn_bwd(p, null, p, p, p, null, p, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 1 << 20,
+    assert lib.xmoe_expert_ffn_bwd(p, null, p, p, p, null, p, null, p, 32, 8, 64, 32, p, p, p, p, p, p, p, 1, p, 1 << 20,
                                    null) == INVALID                          # a row scale without a row index
+    assert lib.xmoe_combine_bwd_weights(null, p, 16, 2, p, null) == INVALID
+    assert lib.xmoe_combine_bwd_weights(p, p, 16, 0, p, null) == INVALID     # k < 1
+    # the entry point with the static scratch array: sizes beyond the array are refused before anything is enqueued
+    assert lib.xmoe_build_eri_static(p, p, 600000, 512, 1, p, p, p, p, p, p, null) == WORKSPACE
+    assert lib.xmoe_build_eri_static(p, p, 16, 8, 9, p, p, p, p, p, p, null) == INVALID
     assert lib.xmoe_combine(p, p, p, null, 0, null, 16, 0, 64, 1, p, null) == INVALID
     assert lib.xmoe_combine(null, p, p, null, 0, null, 16, 2, 64, 1, p, null) == INVALID
     assert lib.xmoe_combine(p, p, p, null, 2, null, 16, 2, 64, 1, p, null) == INVALID     # shared rows missing

@@ -408,18 +408,42 @@ def test_expert_ffn_fwd_bwd(name):
     dout, cw = to_dev(inp["dout"], dt), f32(eri["combine_weights"])
     cw64 = eri["combine_weights"].astype(np.float32).astype(np.float64)
     dout64 = xi.round_to_storage(inp["dout"], dt).astype(np.float64)
+    # the expert outputs that belong to the saved (storage-rounded) G and U, for the gradient of the rows' scales
+    Y_saved = np.zeros((B, d))
+    offs = eri["expert_offsets"]
+    for e in range(E):
+        lo, hi = int(offs[e]), int(offs[e + 1])
+        Y_saved[lo:hi] = (oracle.silu(G[lo:hi].astype(np.float64)) * U[lo:hi]) @ np.asarray(inp["wd"][e], np.float64)
+    rg_tol = 1e-5 if dt == "f32" else 1e-4    # float32 sums of exact products; only the hardware sigmoid differs
     for scale, dY_exact in ((cw, cw64[:, None] * dout64[eri["token_ids"]]), (None, dout64[eri["token_ids"]])):
         ref3 = oracle.expert_ffn_bwd(fwd["Xd"], G.astype(np.float64), U.astype(np.float64), dY_exact,
                                      eri["expert_offsets"], inp["wg"], inp["wu"], inp["wd"])
         dxd3 = torch.empty_like(dxd)
         dwg3, dwu3, dwd3 = torch.full_like(dwg, 7.0), torch.full_like(dwu, 7.0), torch.full_like(dwd, 7.0)
+        rg = torch.full((B,), 7.0, dtype=torch.float32, device="cuda")
         m.xmoe_expert_ffn_bwd(x, to_dev(G, dt), to_dev(U, dt), dout, off, wg, wu, wd, dxd3, dwg3, dwu3, dwd3, ws,
-                              row_index=tok, dy_row_index=tok, dy_row_scale=scale)
+                              row_index=tok, dy_row_index=tok, dy_row_scale=scale, dy_row_scale_grad=rg)
         for got, want, what in zip((dxd3, dwg3, dwu3, dwd3), ref3, ("dXd", "dWg", "dWu", "dWd")):
             assert_close(to_host(got), want, dt, what + " (fused dY)", floor="row" if what == "dXd" else "expert")
         for e in range(E):
             if tpe[e] == 0:
                 assert not dwg3[e].any() and not dwu3[e].any() and not dwd3[e].any()
+        # the gradient of every row's scale: <row of dY before the scale, Y row>; in slot order it is the gradient of
+        # the combine weights that xmoe_combine_bwd takes from Y
+        _, dw_ref = oracle.combine_bwd(dout64, Y_saved, eri["token_ids"], cw64, eri["row_of_slot"], cfg.k)
+        rg_ref = dw_ref.reshape(-1)[np.argsort(eri["row_of_slot"], kind="stable")]
+        assert rel_err(to_host(rg), rg_ref) <= rg_tol, ("row scale gradient", rel_err(to_host(rg), rg_ref))
+        dw3 = torch.full((cfg.T, cfg.k), 7.0, dtype=torch.float32, device="cuda")
+        m.xmoe_combine_bwd_weights(rg, i32(eri["row_of_slot"]), dw3)
+        assert torch.equal(dw3.reshape(-1), rg[i32(eri["row_of_slot"]).long()])
+        assert rel_err(to_host(dw3), dw_ref) <= rg_tol
+    # and on a materialised dY: <dY row, Y row>
+    rg = torch.full((B,), 7.0, dtype=torch.float32, device="cuda")
+    m.xmoe_expert_ffn_bwd(xd, to_dev(G, dt), to_dev(U, dt), to_dev(dY, dt), off, wg, wu, wd, dxd3, dwg3, dwu3, dwd3, ws,
+                          dy_row_scale_grad=rg)
+    assert torch.equal(dxd3, dxd) and torch.equal(dwd3, dwd)      # the extra output changes nothing else
+    rg_ref = (dY.astype(np.float64) * Y_saved).sum(axis=1)
+    assert rel_err(to_host(rg), rg_ref) <= rg_tol, ("row scale gradient, materialised dY", rel_err(to_host(rg), rg_ref))
     with pytest.raises(Exception):   # a scale without an index
         m.xmoe_expert_ffn_bwd(x, to_dev(G, dt), to_dev(U, dt), to_dev(dY, dt), off, wg, wu, wd, dxd3, dwg3, dwu3, dwd3,
                               ws, row_index=tok, dy_row_index=None, dy_row_scale=cw)
@@ -592,6 +616,33 @@ def test_layer_with_materialised_dy(name, cap):
         assert_close_chain(to_host(grads[k_][:cfg.E]), bwd[k_], dt, k_, floor="row")
         if cfg.E_s > 0:
             assert_close_chain(to_host(grads[k_][cfg.E:]), bwd["dshared_" + k_[1:]], dt, "dshared_" + k_[1:], floor="row")
+
+
+@pytest.mark.parametrize("name,cap", [("mini_bf16_skew", None), ("tiny_f32", None), ("mid_bf16", 230)])
+def test_backward_does_not_read_expert_outputs(name, cap):
+    """Y (the paper's A_combine) is a forward-only transient: with the expert outputs overwritten between forward and
+    backward, every gradient comes out bit for bit as without."""
+    cfg = xi.CONFIGS[name]
+    inp = xi.make_layer_inputs(cfg)
+    _, _, dx_ref, g_ref = run_layer(cfg, inp, max_token_count=cap)
+    dx_ref = dx_ref.clone()
+    g_ref = {k_: v.clone() for k_, v in g_ref.items()}
+    m = xm()
+    dt = cfg.dtype
+    layer = m.XMoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, torch_dtype(dt), E_s=cfg.E_s, max_token_count=cap)
+    w = {"w_router": to_dev(inp["w_router"], dt), "bias": None if inp["bias"] is None else f32(inp["bias"])}
+    grads = {"dw_router": torch.empty_like(w["w_router"])}
+    for k_ in ("wg", "wu", "wd"):
+        w[k_] = m.append_shared(to_dev(inp[k_], dt), to_dev(inp["shared_" + k_], dt) if cfg.E_s > 0 else None)
+        grads["d" + k_] = torch.empty_like(w[k_])
+    x, dout = to_dev(inp["x"], dt), to_dev(inp["dout"], dt)
+    layer.forward(x, w)
+    layer.y.fill_(float("nan"))
+    dx = layer.backward(x, w, dout, grads)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx_ref)
+    for k_ in grads:
+        assert torch.equal(grads[k_], g_ref[k_]), k_
 
 
 def test_layer_is_reproducible_run_to_run():
