@@ -156,6 +156,17 @@ int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, i
                           int32_t* expert_ids, float* combine_weights, int32_t* row_of_slot,
                           void* ws, size_t ws_bytes, void* stream);
 
+/* Shared experts behind a PFT whose row count only the device knows.  Shared experts (every token, weight 1) run as
+ * n_shared further experts of the expert-MLP calls, their segments directly behind the PFT's rows.  Without token
+ * dropping those rows are constants the caller can write once (the PFT has T*k rows).  After xmoe_build_eri_capped the
+ * PFT ends at expert_offsets[E] = B_kept, so this call continues the arrays on the device:
+ *   expert_offsets[E+1+s] = B_kept + (s+1)*T            (expert_offsets must have room for E + 1 + n_shared entries)
+ *   token_ids[B_kept + s*T + t] = t,  combine_weights[B_kept + s*T + t] = 1     (room for T*k + n_shared*T entries)
+ * xmoe_combine / xmoe_dispatch_bwd then find the shared rows through shared_row0 = &expert_offsets[E].
+ */
+int xmoe_append_shared_segments(int32_t* expert_offsets, int32_t* token_ids, float* combine_weights, int T, int E,
+                                int n_shared, void* stream);
+
 /* Redundancy-Bypassing Dispatch, stage 0 (Section 4.2 "Pilot Selection and Instantiation"), the metadata part.
  * Experts live on nodes in contiguous blocks: node(e) = e / experts_per_node.  A group is the set of one token's
  * flat entries n = t*k + j whose experts share a destination node (all tokens of a PFT share the source).  The
@@ -273,11 +284,14 @@ int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h
  *              + sum_{s<n_shared} shared_rows[s*T + t,:]   (+ addend[t,:])
  * accumulated in float32 in this order, rounded once.  topk_w == NULL means all weights are 1 (this is then the
  * backward of dispatch).  shared_rows [n_shared*T, d] dt or NULL with n_shared = 0: outputs of experts that every
- * token visits with weight 1 (shared experts run as extra experts whose segment is all T tokens).  addend [T,d]
- * dt or NULL.
+ * token visits with weight 1 (shared experts run as extra experts whose segment is all T tokens).
+ * shared_row0: NULL, or a device pointer to one int32: shared_rows is then the base of a larger row buffer and the
+ * shared experts' rows start at its row *shared_row0 (the row count of a capacity-limited PFT exists on the device
+ * only, see xmoe_append_shared_segments).  addend [T,d] dt or NULL.
  */
 int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* shared_rows,
-                 int n_shared, const void* addend, int T, int k, int d, int dt, void* out, void* stream);
+                 int n_shared, const int32_t* shared_row0, const void* addend, int T, int k, int d, int dt, void* out,
+                 void* stream);
 
 /* Backward of combine:
  *   dy[row_of_slot[t*k+j],:] = topk_w[t,j] * dout[t,:];     dw[t,j] = <dout[t,:], y[row_of_slot[t*k+j],:]>
@@ -298,7 +312,8 @@ int xmoe_combine_bwd_weights(const float* row_grad, const int32_t* row_of_slot, 
 /* Backward of dispatch: dx[t,:] = sum_j dxd[row_of_slot[t*k+j],:] + sum_s shared_rows[s*T + t,:] (+ addend).
  * Same kernel as xmoe_combine with unit weights. */
 int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* shared_rows, int n_shared,
-                      const void* addend, int T, int k, int d, int dt, void* dx, void* stream);
+                      const int32_t* shared_row0, const void* addend, int T, int k, int d, int dt, void* dx,
+                      void* stream);
 
 /* Backward of softmax + top-k with the indices held constant:
  *   dp[t,e] = dw[t,j] if e == topk_idx[t,j] else 0;   dlogits = p * (dp - sum_e p*dp),  p = softmax(logits).

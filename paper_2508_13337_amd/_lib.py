@@ -33,10 +33,11 @@ SIGNATURES = {
                              [_c_int, _c_void_p, _c_size_t, _c_void_p]),
     "xmoe_rbd_stage0": (_c_int, [_c_void_p] * 6 + [_c_int] * 4 + [_c_void_p] * 12 + [_c_size_t, _c_void_p]),
     "xmoe_rbd_absolute_index": (_c_int, [_c_void_p] * 3 + [_c_int] * 2 + [_c_void_p] * 2),
-    "xmoe_combine": (_c_int, [_c_void_p] * 4 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
+    "xmoe_combine": (_c_int, [_c_void_p] * 4 + [_c_int, _c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
+    "xmoe_append_shared_segments": (_c_int, [_c_void_p] * 3 + [_c_int] * 3 + [_c_void_p]),
     "xmoe_combine_bwd": (_c_int, [_c_void_p] * 4 + [_c_int] * 4 + [_c_void_p] * 3),
     "xmoe_combine_bwd_weights": (_c_int, [_c_void_p] * 2 + [_c_int] * 2 + [_c_void_p] * 2),
-    "xmoe_dispatch_bwd": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
+    "xmoe_dispatch_bwd": (_c_int, [_c_void_p] * 3 + [_c_int, _c_void_p, _c_void_p] + [_c_int] * 4 + [_c_void_p] * 2),
     "xmoe_route_bwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 3 + [_c_void_p] * 2),
     "xmoe_gate_logits_bwd": (_c_int, [_c_void_p] * 3 + [_c_int] * 4 + [_c_void_p] * 3 + [_c_size_t, _c_void_p]),
     "xmoe_prof_enable": (None, [_c_int]),

@@ -25,7 +25,7 @@ __all__ = [
     "xmoe_prof_read", "xmoe_prof_copy", "xmoe_prof_shader_clocks", "dtype_code", "alloc_workspace",
     "XMOE_F32", "XMOE_BF16", "WS_BUILD_ERI", "WS_FFN_FWD", "WS_FFN_BWD", "WS_GATE_BWD", "WS_BUILD_ERI_CAPPED", "xmoe_build_eri_capped",
     "xmoe_expert_mlp2_fwd", "xmoe_expert_mlp2_bwd", "WS_MLP2_FWD", "WS_MLP2_BWD", "ACT_CODES",
-    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0", "xmoe_build_eri_static", "xmoe_combine_bwd_weights",
+    "xmoe_rbd_stage0", "xmoe_rbd_absolute_index", "WS_RBD_STAGE0", "xmoe_build_eri_static", "xmoe_combine_bwd_weights", "xmoe_append_shared_segments",
 ]
 
 
@@ -267,19 +267,43 @@ def xmoe_expert_mlp2_bwd(xd, h_save, dy, expert_offsets, w1, w2, act: str, dxd, 
         dtype_code(dt), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream()), "xmoe_expert_mlp2_bwd")
 
 
-def xmoe_combine(y, row_of_slot, topk_w, shared_rows, addend, k: int, out) -> None:
-    """shared_rows: None or an [n_shared*T, d] tensor (rows of experts every token visits with weight 1)."""
+def _shared_args(shared_rows, shared_row0, n_shared, T, d):
+    """(rows tensor, count): without shared_row0 the count follows from the tensor; with it (a device int32: the row
+    of the larger buffer `shared_rows` at which the shared experts' rows start) the caller states it."""
+    if shared_rows is None:
+        assert shared_row0 is None
+        return 0
+    assert shared_rows.shape[1] == d
+    if shared_row0 is None:
+        assert shared_rows.shape[0] % T == 0
+        return shared_rows.shape[0] // T
+    assert n_shared is not None and shared_row0.numel() == 1 and shared_rows.shape[0] >= n_shared * T
+    return int(n_shared)
+
+
+def xmoe_combine(y, row_of_slot, topk_w, shared_rows, addend, k: int, out, shared_row0=None, n_shared=None) -> None:
+    """shared_rows: None or an [n_shared*T, d] tensor (rows of experts every token visits with weight 1); with
+    shared_row0 (one int32 on the device) the whole row buffer, in which those rows start at row shared_row0[0]."""
     T, d = out.shape
     dt = out.dtype
     assert y.shape[1] == d and row_of_slot.numel() == T * k
-    n_shared = 0
-    if shared_rows is not None:
-        assert shared_rows.shape[1] == d and shared_rows.shape[0] % T == 0
-        n_shared = shared_rows.shape[0] // T
+    n_shared = _shared_args(shared_rows, shared_row0, n_shared, T, d)
     _check(lib().xmoe_combine(_ptr(y, dt, "y"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
                               _ptr(topk_w, torch.float32, "topk_w"), _ptr(shared_rows, dt, "shared_rows"), n_shared,
+                              _ptr(shared_row0, torch.int32, "shared_row0"),
                               _ptr(addend, dt, "addend"), T, k, d, dtype_code(dt), _ptr(out, None, "out"),
                               _stream()), "xmoe_combine")
+
+
+def xmoe_append_shared_segments(expert_offsets, token_ids, combine_weights, T: int, E: int, n_shared: int) -> None:
+    """Continues expert_offsets [E+1+n_shared], token_ids and combine_weights behind the last row of a PFT whose row
+    count only the device knows, with n_shared all-token segments."""
+    assert expert_offsets.numel() >= E + 1 + n_shared
+    assert token_ids.numel() == combine_weights.numel()
+    _check(lib().xmoe_append_shared_segments(_ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                             _ptr(token_ids, torch.int32, "token_ids"),
+                                             _ptr(combine_weights, torch.float32, "combine_weights"), T, E, n_shared,
+                                             _stream()), "xmoe_append_shared_segments")
 
 
 def xmoe_combine_bwd(dout, y, row_of_slot, topk_w, dy, dw) -> None:
@@ -304,16 +328,14 @@ def xmoe_combine_bwd_weights(row_grad, row_of_slot, dw) -> None:
                                           _ptr(dw, torch.float32, "dw"), _stream()), "xmoe_combine_bwd_weights")
 
 
-def xmoe_dispatch_bwd(dxd, row_of_slot, shared_rows, addend, k: int, dx) -> None:
+def xmoe_dispatch_bwd(dxd, row_of_slot, shared_rows, addend, k: int, dx, shared_row0=None, n_shared=None) -> None:
     T, d = dx.shape
     dt = dx.dtype
-    assert tuple(dxd.shape) == (T * k, d)
-    n_shared = 0
-    if shared_rows is not None:
-        assert shared_rows.shape[1] == d and shared_rows.shape[0] % T == 0
-        n_shared = shared_rows.shape[0] // T
+    assert dxd.shape[0] >= T * k and dxd.shape[1] == d
+    n_shared = _shared_args(shared_rows, shared_row0, n_shared, T, d)
     _check(lib().xmoe_dispatch_bwd(_ptr(dxd, dt, "dxd"), _ptr(row_of_slot, torch.int32, "row_of_slot"),
-                                   _ptr(shared_rows, dt, "shared_rows"), n_shared, _ptr(addend, dt, "addend"), T, k, d,
+                                   _ptr(shared_rows, dt, "shared_rows"), n_shared,
+                                   _ptr(shared_row0, torch.int32, "shared_row0"), _ptr(addend, dt, "addend"), T, k, d,
                                    dtype_code(dt), _ptr(dx, None, "dx"), _stream()), "xmoe_dispatch_bwd")
 
 

@@ -26,6 +26,7 @@ const char* const kKernelNames[K_COUNT] = {
     "eri_scan_kernel",
     "eri_scatter_kernel",
     "eri_cap_kernel",
+    "shared_segments_kernel",
     "dispatch_kernel",
     "combine_kernel",
     "combine_bwd_kernel",

@@ -414,6 +414,35 @@ extern "C" int xmoe_build_eri_static(const int32_t* topk_idx, const float* topk_
                             combine_weights, row_of_slot, counts, (hipStream_t)stream);
 }
 
+// Segments of n all-token experts directly behind the PFT's last row, which only the device knows after token
+// dropping: offsets[E + 1 + s] = offsets[E] + (s+1)*T, and for the rows of those segments token id t and weight 1.
+__global__ __launch_bounds__(256) void shared_segments_kernel(int32_t* __restrict__ offsets,
+                                                              int32_t* __restrict__ token_ids,
+                                                              float* __restrict__ combine_weights, int T, int E,
+                                                              int n) {
+    const int base = offsets[E];
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < (long)n * T) {
+        token_ids[base + i] = (int)(i % T);
+        combine_weights[base + i] = 1.0f;
+    }
+    if (i < n) offsets[E + 1 + i] = base + ((int)i + 1) * T;
+}
+
+extern "C" int xmoe_append_shared_segments(int32_t* expert_offsets, int32_t* token_ids, float* combine_weights, int T,
+                                           int E, int n_shared, void* stream) {
+    if (T < 0 || E < 1 || n_shared < 0) return XMOE_ERR_INVALID_ARG;
+    if ((long long)T * n_shared >= (1ll << 31)) return XMOE_ERR_INVALID_ARG;
+    if (n_shared == 0) return XMOE_OK;
+    if (!expert_offsets || (T > 0 && (!token_ids || !combine_weights))) return XMOE_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    const long n = (long)n_shared * T > n_shared ? (long)n_shared * T : n_shared;
+    XMOE_LAUNCH(K_SHARED_SEGMENTS, s,
+                hipLaunchKernelGGL(shared_segments_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                                   expert_offsets, token_ids, combine_weights, T, E, n_shared));
+    return XMOE_OK;
+}
+
 extern "C" int xmoe_build_eri_capped(const int32_t* topk_idx, const float* topk_w, int T, int E, int k,
                                      int max_token_count, int32_t* tokens_per_expert, int32_t* expert_offsets,
                                      int32_t* token_ids, int32_t* expert_ids, float* combine_weights,

@@ -18,6 +18,7 @@ enum KernelId : int {
     K_ERI_SCAN,
     K_ERI_SCATTER,
     K_ERI_CAP,
+    K_SHARED_SEGMENTS,
     K_DISPATCH,
     K_COMBINE,
     K_COMBINE_BWD,

@@ -81,10 +81,13 @@ __global__ __launch_bounds__(256) void dispatch_kernel(const T* __restrict__ x, 
 template <typename T, bool VEC, int KU>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ y, const int32_t* __restrict__ row_of_slot,
                                                       const float* __restrict__ topk_w, const T* __restrict__ shared,
-                                                      int n_shared, const T* __restrict__ add, int Tn, int k, int d,
+                                                      int n_shared, const int32_t* __restrict__ shared_row0,
+                                                      const T* __restrict__ add, int Tn, int k, int d,
                                                       int B, T* __restrict__ out) {
     const int t = blockIdx.x;
     constexpr int N = Vec16<T>::N;
+    // the shared rows start at a row that only the device knows (behind the retained rows of a capacity-limited PFT)
+    if (shared_row0 && n_shared > 0) shared += (size_t)shared_row0[0] * d;
     if (VEC) {
         const int nv = d / N;
         for (int c = threadIdx.x; c < nv; c += 256) {
@@ -246,19 +249,20 @@ static int launch_dispatch(const void* x, const int32_t* token_ids, int Tn, int 
     } while (0)
 
 template <typename T>
-static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* sh, int nsh, const void* add,
-                          int Tn, int k, int d, void* out, hipStream_t s) {
+static int launch_combine(const void* y, const int32_t* ros, const float* w, const void* sh, int nsh,
+                          const int32_t* sh_row0, const void* add, int Tn, int k, int d, void* out, hipStream_t s) {
     dim3 grid(Tn), block(256);
     const int B = Tn * k;
     if (can_vec<T>(d, {y, sh, add, out})) {
 #define XMOE_CALL(KU)                                                                                                \
     XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, true, KU>), grid, block, 0, s, (const T*)y, ros, \
-                                                 w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out))
+                                                 w, (const T*)sh, nsh, sh_row0, (const T*)add, Tn, k, d, B, (T*)out))
         XMOE_DISPATCH_KU(k, XMOE_CALL);
 #undef XMOE_CALL
     } else {
         XMOE_LAUNCH(K_COMBINE, s, hipLaunchKernelGGL((combine_kernel<T, false, 8>), grid, block, 0, s, (const T*)y,
-                                                     ros, w, (const T*)sh, nsh, (const T*)add, Tn, k, d, B, (T*)out));
+                                                     ros, w, (const T*)sh, nsh, sh_row0, (const T*)add, Tn, k, d, B,
+                                                     (T*)out));
     }
     return XMOE_OK;
 }
@@ -318,7 +322,8 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
 }
 
 int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w, const void* shared_rows,
-                 int n_shared, const void* addend, int T, int k, int d, int dt, void* out, void* stream) {
+                 int n_shared, const int32_t* shared_row0, const void* addend, int T, int k, int d, int dt, void* out,
+                 void* stream) {
     int st = check_rows_args(T, k, d, dt);
     if (st != XMOE_OK) return st;
     if (n_shared < 0 || (n_shared > 0 && !shared_rows)) return XMOE_ERR_INVALID_ARG;
@@ -326,13 +331,16 @@ int xmoe_combine(const void* y, const int32_t* row_of_slot, const float* topk_w,
     if (!y || !row_of_slot || !out) return XMOE_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     return dt == XMOE_F32
-               ? launch_combine<float>(y, row_of_slot, topk_w, shared_rows, n_shared, addend, T, k, d, out, s)
-               : launch_combine<bf16_t>(y, row_of_slot, topk_w, shared_rows, n_shared, addend, T, k, d, out, s);
+               ? launch_combine<float>(y, row_of_slot, topk_w, shared_rows, n_shared, shared_row0, addend, T, k, d, out,
+                                       s)
+               : launch_combine<bf16_t>(y, row_of_slot, topk_w, shared_rows, n_shared, shared_row0, addend, T, k, d,
+                                        out, s);
 }
 
 int xmoe_dispatch_bwd(const void* dxd, const int32_t* row_of_slot, const void* shared_rows, int n_shared,
-                      const void* addend, int T, int k, int d, int dt, void* dx, void* stream) {
-    return xmoe_combine(dxd, row_of_slot, nullptr, shared_rows, n_shared, addend, T, k, d, dt, dx, stream);
+                      const int32_t* shared_row0, const void* addend, int T, int k, int d, int dt, void* dx,
+                      void* stream) {
+    return xmoe_combine(dxd, row_of_slot, nullptr, shared_rows, n_shared, shared_row0, addend, T, k, d, dt, dx, stream);
 }
 
 int xmoe_combine_bwd(const void* dout, const void* y, const int32_t* row_of_slot, const float* topk_w, int T, int k,

@@ -38,8 +38,8 @@ class XMoELayer:
         self.T, self.d, self.E, self.k, self.f, self.E_s = T, d, E, k, f, E_s
         self.fuse_combine_bwd = fuse_combine_bwd
         # None: dropless.  Else the per-expert capacity of the token-dropping PFT construction; the number of
-        # retained rows is then known on the device only, so the shared experts (whose segments would have to start
-        # right behind the retained rows) run as calls of their own on x.
+        # retained rows is then known on the device only, and xmoe_append_shared_segments continues the index arrays
+        # with the shared experts' segments behind them, every step.
         self.max_token_count = max_token_count
         self.dtype, self.device = dtype, device
         B = T * k
@@ -84,72 +84,64 @@ class XMoELayer:
                  api.xmoe_workspace_bytes(api.WS_GATE_BWD, T, d, E, k, f, dt))
         if max_token_count is not None:
             ws = max(ws, api.xmoe_workspace_bytes(api.WS_BUILD_ERI_CAPPED, T, d, E, k, f, dt))
-            self.one_segment = torch.tensor([0, T], **i32)
         self.ws = api.alloc_workspace(ws, device)
-
-    def _shared(self, rows: torch.Tensor) -> Optional[torch.Tensor]:
-        return rows[self.B:] if self.E_s > 0 else None
 
     # weights: dict with w_router [d,E], bias [E]|None, wg/wu [E+E_s,d,f], wd [E+E_s,f,d] (routed experts first,
     # see append_shared)
     def forward(self, x: torch.Tensor, w: dict) -> torch.Tensor:
         api.xmoe_gate_logits(x, w["w_router"], w.get("bias"), self.logits)
         api.xmoe_route(self.logits, self.k, self.topk_idx, self.topk_w)
-        B, E, T = self.B, self.E, self.T
+        B, E, T, E_s = self.B, self.E, self.T, self.E_s
         if self.max_token_count is None:
             api.xmoe_build_eri(self.topk_idx, self.topk_w, E, self.tokens_per_expert, self.expert_offsets,
                                self.token_ids, self.expert_ids, self.combine_weights, self.row_of_slot, self.ws)
-            api.xmoe_expert_ffn_fwd(x, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
-                                    self.ws, row_index=self.token_ids_all)
         else:
             api.xmoe_build_eri_capped(self.topk_idx, self.topk_w, E, self.max_token_count, self.tokens_per_expert,
                                       self.expert_offsets, self.token_ids, self.expert_ids, self.combine_weights,
                                       self.row_of_slot, self.ws)
-            api.xmoe_expert_ffn_fwd(x, self.expert_offsets, w["wg"][:E], w["wu"][:E], w["wd"][:E],
-                                    self.g[:B], self.u[:B], self.y[:B], self.ws, row_index=self.token_ids)
-            for s in range(self.E_s):
-                seg = slice(B + s * T, B + (s + 1) * T)
-                api.xmoe_expert_ffn_fwd(x, self.one_segment, w["wg"][E + s:E + s + 1], w["wu"][E + s:E + s + 1],
-                                        w["wd"][E + s:E + s + 1], self.g[seg], self.u[seg], self.y[seg], self.ws)
-        api.xmoe_combine(self.y[:B], self.row_of_slot, self.topk_w, self._shared(self.y), None, self.k, self.out)
+            if E_s > 0:   # the shared experts' segments start behind the retained rows, a count only the device has
+                api.xmoe_append_shared_segments(self.offsets_all, self.token_ids_all, self.combine_weights_all, T, E,
+                                                E_s)
+        api.xmoe_expert_ffn_fwd(x, self.offsets_all, w["wg"], w["wu"], w["wd"], self.g, self.u, self.y,
+                                self.ws, row_index=self.token_ids_all)
+        y, y_shared, kw = self._row_args(self.y)
+        api.xmoe_combine(y, self.row_of_slot, self.topk_w, y_shared, None, self.k, self.out, **kw)
         return self.out
+
+    def _row_args(self, rows: torch.Tensor):
+        """How xmoe_combine / xmoe_dispatch_bwd find the routed and the shared experts' rows in `rows` [R,d]:
+        (routed rows, shared rows, keyword arguments)."""
+        B, E, E_s = self.B, self.E, self.E_s
+        if E_s == 0:
+            return rows[:B], None, {}
+        if self.max_token_count is None:
+            return rows[:B], rows[B:], {}
+        # the shared segments start behind the retained rows: their first row is expert_offsets[E], on the device
+        return rows, rows, {"shared_row0": self.offsets_all[E:E + 1], "n_shared": E_s}
 
     def backward(self, x: torch.Tensor, w: dict, dout: torch.Tensor, grads: dict) -> torch.Tensor:
         """grads: preallocated dw_router, dwg, dwu, dwd in the layouts of the weights."""
-        B, E, T = self.B, self.E, self.T
-        fused = self.fuse_combine_bwd
-        if not fused:
-            api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, self.dy[:B], self.dw)
-        if self.max_token_count is None:
-            if fused:
-                api.xmoe_expert_ffn_bwd(x, self.g, self.u, dout, self.offsets_all, w["wg"], w["wu"], w["wd"],
-                                        self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
-                                        row_index=self.token_ids_all, dy_row_index=self.token_ids_all,
-                                        dy_row_scale=self.combine_weights_all, dy_row_scale_grad=self.row_grad)
-            else:
-                if self.E_s > 0:   # dY of a shared expert's rows is dout itself
-                    api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
-                api.xmoe_expert_ffn_bwd(x, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
-                                        self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
-                                        row_index=self.token_ids_all)
-        else:
-            api.xmoe_expert_ffn_bwd(x, self.g[:B], self.u[:B], dout if fused else self.dy[:B], self.expert_offsets,
-                                    w["wg"][:E], w["wu"][:E], w["wd"][:E], self.dxd[:B], grads["dwg"][:E],
-                                    grads["dwu"][:E], grads["dwd"][:E], self.ws, row_index=self.token_ids,
-                                    dy_row_index=self.token_ids if fused else None,
-                                    dy_row_scale=self.combine_weights if fused else None,
-                                    dy_row_scale_grad=self.row_grad[:B] if fused else None)
-            for s in range(self.E_s):
-                seg = slice(B + s * T, B + (s + 1) * T)
-                one = slice(E + s, E + s + 1)
-                api.xmoe_expert_ffn_bwd(x, self.g[seg], self.u[seg], dout, self.one_segment, w["wg"][one],
-                                        w["wu"][one], w["wd"][one], self.dxd[seg], grads["dwg"][one],
-                                        grads["dwu"][one], grads["dwd"][one], self.ws)
-        if fused:
+        B = self.B
+        if self.fuse_combine_bwd:
+            api.xmoe_expert_ffn_bwd(x, self.g, self.u, dout, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
+                                    row_index=self.token_ids_all, dy_row_index=self.token_ids_all,
+                                    dy_row_scale=self.combine_weights_all, dy_row_scale_grad=self.row_grad)
             api.xmoe_combine_bwd_weights(self.row_grad, self.row_of_slot, self.dw)
+        else:
+            if self.E_s > 0:   # dY of a shared expert's rows is dout itself
+                if self.max_token_count is None:
+                    api.xmoe_dispatch(dout, self.token_ids_all[B:], self.dy[B:])
+                else:          # their first row is known on the device only: every row, the routed ones overwritten next
+                    api.xmoe_dispatch(dout, self.token_ids_all, self.dy)
+            api.xmoe_combine_bwd(dout, self.y[:B], self.row_of_slot, self.topk_w, self.dy[:B], self.dw)
+            api.xmoe_expert_ffn_bwd(x, self.g, self.u, self.dy, self.offsets_all, w["wg"], w["wu"], w["wd"],
+                                    self.dxd, grads["dwg"], grads["dwu"], grads["dwd"], self.ws,
+                                    row_index=self.token_ids_all)
         api.xmoe_route_bwd(self.logits, self.topk_idx, self.dw, self.dlogits)
         api.xmoe_gate_logits_bwd(x, w["w_router"], self.dlogits, grads["dw_router"], self.dx_gate, self.ws)
-        api.xmoe_dispatch_bwd(self.dxd[:B], self.row_of_slot, self._shared(self.dxd), self.dx_gate, self.k, self.dx)
+        dxd, dxd_shared, kw = self._row_args(self.dxd)
+        api.xmoe_dispatch_bwd(dxd, self.row_of_slot, dxd_shared, self.dx_gate, self.k, self.dx, **kw)
         return self.dx
 
 

@@ -103,11 +103,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     # the entry point with the static scratch array: sizes beyond the array are refused before anything is enqueued
     assert lib.xmoe_build_eri_static(p, p, 600000, 512, 1, p, p, p, p, p, p, null) == WORKSPACE
     assert lib.xmoe_build_eri_static(p, p, 16, 8, 9, p, p, p, p, p, p, null) == INVALID
-    assert lib.xmoe_combine(p, p, p, null, 0, null, 16, 0, 64, 1, p, null) == INVALID
-    assert lib.xmoe_combine(null, p, p, null, 0, null, 16, 2, 64, 1, p, null) == INVALID
-    assert lib.xmoe_combine(p, p, p, null, 2, null, 16, 2, 64, 1, p, null) == INVALID     # shared rows missing
-    assert lib.xmoe_combine(p, p, p, p, -1, null, 16, 2, 64, 1, p, null) == INVALID
-    assert lib.xmoe_dispatch_bwd(p, p, null, 1, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(p, p, p, null, 0, null, null, 16, 0, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(null, p, p, null, 0, null, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_combine(p, p, p, null, 2, null, null, 16, 2, 64, 1, p, null) == INVALID     # shared rows missing
+    assert lib.xmoe_combine(p, p, p, p, -1, null, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_dispatch_bwd(p, p, null, 1, null, null, 16, 2, 64, 1, p, null) == INVALID
+    assert lib.xmoe_append_shared_segments(null, p, p, 16, 8, 2, null) == INVALID
+    assert lib.xmoe_append_shared_segments(p, p, p, 16, 8, 0, null) == 0     # nothing to append
     assert lib.xmoe_combine_bwd(p, p, p, null, 16, 2, 64, 1, p, p, null) == INVALID   # dy wanted, no weights
     assert lib.xmoe_combine_bwd(p, p, p, null, 16, 2, 64, 1, null, null, null) == INVALID   # no dw
     assert lib.xmoe_route_bwd(p, p, p, 16, 8, 9, p, null) == INVALID
@@ -119,7 +121,7 @@ def test_empty_inputs_are_ok_without_a_launch(lib):
     assert lib.xmoe_route(p, 0, 8, 2, p, p, None) == 0
     assert lib.xmoe_gate_logits(p, p, None, p, 0, 32, 8, 1, None) == 0
     assert lib.xmoe_dispatch(p, p, 16, 0, 64, 1, p, None) == 0
-    assert lib.xmoe_combine(p, p, p, None, 0, None, 0, 2, 64, 1, p, None) == 0
+    assert lib.xmoe_combine(p, p, p, None, 0, None, None, 0, 2, 64, 1, p, None) == 0
 
 
 def test_product_package_does_not_import_the_oracle():

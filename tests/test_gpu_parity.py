@@ -576,8 +576,13 @@ def test_layer_with_token_dropping(name, cap):
     assert np.array_equal(layer.topk_idx.cpu().numpy(), fwd["topk_idx"])
     for key in ("tokens_per_expert", "expert_offsets", "row_of_slot"):
         assert np.array_equal(getattr(layer, key).cpu().numpy(), eri[key]), key
-    assert np.array_equal(layer.token_ids.cpu().numpy()[:nk], eri["token_ids"])
-    assert (layer.token_ids.cpu().numpy()[nk:] == -1).all()
+    tok_all = layer.token_ids_all.cpu().numpy()
+    assert np.array_equal(tok_all[:nk], eri["token_ids"])
+    # behind the retained rows: the shared experts' segments (token ids 0 .. T-1 each), then the sentinels
+    ns = cfg.E_s * cfg.T
+    assert np.array_equal(tok_all[nk:nk + ns], np.tile(np.arange(cfg.T), cfg.E_s))
+    assert (tok_all[nk + ns:cfg.B] == -1).all()
+    assert np.array_equal(layer.offsets_all.cpu().numpy()[cfg.E:], nk + cfg.T * np.arange(cfg.E_s + 1))
     assert_close_chain(to_host(out), fwd["out"], dt, "out")
     assert_close_chain(to_host(layer.y[:nk]), fwd["Y"], dt, "Y")
     assert_close_chain(to_host(dx), bwd["dx"], dt, "dx")
