@@ -45,8 +45,12 @@ constexpr int kIdxChunkBytes = kIdxChunk * 4 * 4;             // 256 bytes: one 
 constexpr int kIdxWaveBytes = 2 * kIdxChunkBytes;
 constexpr int kIdxBytes = 2 * 8 * kIdxWaveBytes;              // two operands x eight waves: 8 KiB
 constexpr int kIdxScalarTiles = kStages;                      // k-tiles 0 .. kStages-1 of a tile take their rows by scalar loads
-constexpr int kLdsBytes = kStages * kStageBytes + kIdxBytes;  // 136 KiB
-static_assert(kLdsBytes <= 160 * 1024, "LDS of one CU");
+// The GEMMs whose two operands are both K-contiguous run a ring of five 32 KiB units instead (mainloop_rr): all of a
+// CU's 160 KiB.
+constexpr int kUnitBytes = 256 * 64 * 2;                      // one operand, 256 rows x 64 k
+constexpr int kUnits = 5;
+constexpr int kLdsBytes = kUnits * kUnitBytes;                // 160 KiB
+static_assert(kStages * kStageBytes + kIdxBytes <= kLdsBytes && kLdsBytes <= 160 * 1024, "LDS of one CU");
 constexpr int kLoadsPerTile = 4;                // per thread: 2 for A, 2 for B
 constexpr int kNumXcd = 8;
 
@@ -445,6 +449,183 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
     if ((A_GATHER && A_COL) || (B_GATHER && B_COL)) __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);
 }
 
+// =========================================================================================================
+// Both operands K-contiguous (dAct: dOut rows x Wd rows; dX: dG | dU rows x Wg | Wu rows).
+// A 32-wide k-tile of such an operand is 64 bytes of each row, half a cache line, and the vector-memory front end of
+// a CU takes whole-line requests at twice the rate of half-line ones (measured with this load instruction on
+// L2-resident data: 58 against 29 B/clk per CU) - and the time a k-step's requests spend in that front end shows up
+// in the loop one to one: k-tiles of the row x row kernels took 0.95 to 1.08 us where the row x column kernels take
+// 0.8.  So these GEMMs load 64 k at a time: a unit is one operand's [256 rows][64 k], 128-byte rows, 32 KiB, one
+// instruction of a wave fetching eight whole lines.  The CU's 160 KiB hold a ring of five units that alternate
+// A(0) B(0) A(1) B(1) ...; the four 16-wide k-steps on A(p), B(p) are one pass of the loop, which refills the two
+// units the pass before it released (B(p+1) at its first k-step, A(p+2) at its third), so two to three units are in
+// flight at any time and a barrier waits for all but the newest.
+// Rows outside the operand are clamped to its last row instead of fetching zeros: the output rows and columns they
+// feed are never stored (K itself is a multiple of 64, there is no tail along K), which keeps a lane's address a
+// fixed 32-bit offset from a wave-uniform base for the whole tile.
+// =========================================================================================================
+template <bool GATHER>
+struct RowLoader {
+    uint32_t off[4];   // byte offset of this lane's 16 bytes in instruction i: source row * ld * 2 + chunk * 16
+    __device__ __forceinline__ void init(const Operand& o) {
+        const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        int grow[4] = {0, 0, 0, 0};
+        if (GATHER) {
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int r = wave * 32 + j;
+                const int v = o.gather[r < o.n_lo ? r : o.n_lo - 1];   // wave-uniform address: a scalar load
+                if ((lane >> 3) == (j & 7)) grow[j >> 3] = v;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = wave * 32 + i * 8 + (lane >> 3);
+            const int src = GATHER ? grow[i] : (row < o.n_lo ? row : o.n_lo - 1);
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            off[i] = (uint32_t)src * (uint32_t)(o.ld * 2) + (uint32_t)(c * 16);
+        }
+    }
+    // kbase: wave-uniform address of (row 0, first k of the unit); zero: the unit lies past the end of K and every
+    // lane fetches the block of zeros (the loads are issued all the same, which keeps the wait counts uniform)
+    __device__ __forceinline__ void issue(char* __restrict__ unit, const char* kbase, bool zero) const {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t o = zero ? 0u : off[i];
+            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + o), LDS_PTR(unit + (wave * 32 + i * 8) * 128), 16, 0, 0);
+        }
+    }
+};
+
+// 8 bf16 (k = 16*ks4 + 8*(lane/32) + 0..7 of the unit, ks4 = 0..3) of row base + lane%32; the 16-byte chunks of a row
+// are XOR-swizzled with (row / 2) % 8, so the 16 rows that one pass of a 16-byte LDS read covers hit 16 distinct
+// groups of four banks
+__device__ __forceinline__ bf16x8_t read_frag_unit(const char* unit, int base, int ks4) {
+    const int lane = threadIdx.x & 63;
+    const int r = base + (lane & 31);
+    const int chunk = 2 * ks4 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8_t*>(unit + r * 128 + ((chunk ^ ((r >> 1) & 7)) << 4));
+}
+__device__ __forceinline__ void read_frags_unit(Frags& f, const char* ua, const char* ub, int ks4) {
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) f.b[ni] = read_frag_unit(ub, b_col<false>(wn, ni), ks4);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) f.a[mi] = read_frag_unit(ua, wm * 128 + mi * 32, ks4);
+}
+
+// where unit u = 2*pair + (0: A, 1: B) comes from
+struct UnitSource {
+    const char *a1, *b1, *a2, *b2;   // operand sets 1 and 2 (set 2 = set 1 when there is one set)
+    int np1, np;                     // pairs (64-wide k ranges) of set 1, total
+    __device__ __forceinline__ const char* base(int u, bool& zero) const {
+        const int p = u >> 1;
+        zero = p >= np;
+        if (zero) return reinterpret_cast<const char*>(kZero16);
+        const bool second = p >= np1;
+        const char* b = (u & 1) ? (second ? b2 : b1) : (second ? a2 : a1);
+        return b + (long)(second ? p - np1 : p) * 128;
+    }
+};
+
+// One pass: the four 16-wide k-steps on A(p) = ua, B(p) = ub.  On entry both have landed for every thread, every wave
+// is done with the units of pass p-1 (fill1, fill2: their slots), and f1 holds the last k-step of pass p-1, whose
+// matrix instructions run first.  The five slots are distinct, and saying so with __restrict__ matters: see kstep.
+template <bool A_GATHER>
+__device__ __forceinline__ void rr_pass(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1, const RowLoader<A_GATHER>& la,
+                                        const RowLoader<false>& lb, const UnitSource& src, int p,
+                                        char* __restrict__ fill1, char* __restrict__ fill2,
+                                        const char* __restrict__ ua, const char* __restrict__ ub) {
+    // The requests are pinned where they stand (a scheduling barrier behind each group): left to itself the compiler
+    // sinks all eight to the end of the pass, where the wait that ends the pass would then sit out B(p+1)'s whole
+    // latency.
+    bool z;
+    const char* kb = src.base(2 * p + 3, z);
+    lb.issue(fill1, kb, z);                       // B(p+1)
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags_unit(f0, ua, ub, 0);
+    mma_step(acc, f1);
+    read_frags_unit(f1, ua, ub, 1);
+    mma_step(acc, f0);
+    kb = src.base(2 * p + 4, z);
+    __builtin_amdgcn_sched_barrier(0);
+    la.issue(fill2, kb, z);                       // A(p+2)
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags_unit(f0, ua, ub, 2);
+    mma_step(acc, f1);
+    read_frags_unit(f1, ua, ub, 3);
+    mma_step(acc, f0);
+}
+template <bool A_GATHER>
+__device__ __forceinline__ void rr_feed(const RowLoader<A_GATHER>& la, const RowLoader<false>& lb,
+                                        const UnitSource& src, int p, char* __restrict__ fill1,
+                                        char* __restrict__ fill2) {
+    bool z;
+    const char* kb = src.base(2 * p + 3, z);
+    lb.issue(fill1, kb, z);
+    kb = src.base(2 * p + 4, z);
+    la.issue(fill2, kb, z);
+}
+
+// acc += A x B over K (+ A2 x B2 over K2 when TWO); K and K2 are multiples of 64.  mi_count as in mainloop2.
+template <bool TWO, bool A_GATHER>
+__device__ __forceinline__ void mainloop_rr(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
+                                            const Operand& oa2, const Operand& ob2, int K2, int mi_count,
+                                            char* smem) {
+    UnitSource src;
+    src.np1 = K / 64;
+    src.np = src.np1 + (TWO ? K2 / 64 : 0);
+    if (src.np <= 0) return;
+    src.a1 = reinterpret_cast<const char*>(oa.p_lo);
+    src.b1 = reinterpret_cast<const char*>(ob.p_lo);
+    src.a2 = reinterpret_cast<const char*>(TWO ? oa2.p_lo : oa.p_lo);
+    src.b2 = reinterpret_cast<const char*>(TWO ? ob2.p_lo : ob.p_lo);
+    mi_count = __builtin_amdgcn_readfirstlane(mi_count);
+    RowLoader<A_GATHER> la;
+    RowLoader<false> lb;
+    la.init(oa);
+    lb.init(ob);
+    {   // prologue: A(0), B(0), A(1) into slots 0, 1, 2
+        bool z;
+        const char* kb = src.base(0, z);
+        la.issue(smem, kb, z);
+        kb = src.base(1, z);
+        lb.issue(smem + kUnitBytes, kb, z);
+        kb = src.base(2, z);
+        la.issue(smem + 2 * kUnitBytes, kb, z);
+    }
+    // Invariant at the top of pass p: units <= 2p+1 have landed for every thread, unit 2p+2 (four loads per thread) may
+    // still be in flight, and the slots of units 2p-2 and 2p-1 are free for units 2p+3 and 2p+4.
+    wait_loads_and_barrier<4>();
+    int sa = 0;   // slot of A(p) = (2p) % 5
+    if (mi_count > 0) {
+        Frags f0, f1;
+        zero_frags(f1);
+        for (int p = 0; p < src.np; ++p) {
+            const int sb = sa + 1 < kUnits ? sa + 1 : sa + 1 - kUnits;
+            const int s3 = sa + 3 < kUnits ? sa + 3 : sa + 3 - kUnits;
+            const int s4 = sa + 4 < kUnits ? sa + 4 : sa + 4 - kUnits;
+            rr_pass<A_GATHER>(acc, f0, f1, la, lb, src, p, smem + s3 * kUnitBytes, smem + s4 * kUnitBytes,
+                              smem + sa * kUnitBytes, smem + sb * kUnitBytes);
+            wait_loads_and_barrier<4>();
+            sa = sa + 2 < kUnits ? sa + 2 : sa + 2 - kUnits;
+        }
+        mma_step(acc, f1);
+    } else {
+        for (int p = 0; p < src.np; ++p) {
+            const int s3 = sa + 3 < kUnits ? sa + 3 : sa + 3 - kUnits;
+            const int s4 = sa + 4 < kUnits ? sa + 4 : sa + 4 - kUnits;
+            rr_feed<A_GATHER>(la, lb, src, p, smem + s3 * kUnitBytes, smem + s4 * kUnitBytes);
+            wait_loads_and_barrier<4>();
+            sa = sa + 2 < kUnits ? sa + 2 : sa + 2 - kUnits;
+        }
+    }
+    // all loads of this tile (and the dummy ones past its end) have landed before the ring is reused as staging
+    wait_loads_and_barrier<0>();
+}
+
 // acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
 // 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
@@ -453,6 +634,12 @@ template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER = false, bo
 __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
                                           const Operand& oa2, const Operand& ob2, int K2, int mi_count,
                                           char* smem) {
+#ifndef XMOE_NO_UNIT_RING
+    if constexpr (!A_COL && !B_COL && !B_GATHER) {
+        mainloop_rr<TWO, A_GATHER>(acc, oa, ob, K, oa2, ob2, K2, mi_count, smem);
+        return;
+    }
+#endif
     const int nk1 = (K + TK - 1) / TK;
     const int nk = nk1 + (TWO ? (K2 + TK - 1) / TK : 0);
     if (nk <= 0) return;
