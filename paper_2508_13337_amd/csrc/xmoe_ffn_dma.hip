@@ -540,7 +540,8 @@ __device__ __forceinline__ void rr_pass(f32x16_t (&acc)[4][2], Frags& f0, Frags&
                                         const char* __restrict__ ua, const char* __restrict__ ub) {
     // The requests are pinned where they stand (a scheduling barrier behind each group): left to itself the compiler
     // sinks all eight to the end of the pass, where the wait that ends the pass would then sit out B(p+1)'s whole
-    // latency.
+    // latency.  (Tried: both groups at the head of the pass, +6 %: bursts of requests cost more than they gain in lead;
+    // two requests per 16-wide k-step, +1.5 %; raised wave priority while requesting, no change.)
     bool z;
     const char* kb = src.base(2 * p + 3, z);
     lb.issue(fill1, kb, z);                       // B(p+1)
@@ -717,7 +718,7 @@ __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[4][2]) {
 // ---------------------------------------------------------------------------------------------------------
 // epilogue helpers: a wave stages 32 rows x NC columns of bf16 in its private LDS strip, then writes rows out
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kStripStride = 200;                 // bytes per staged row (96 columns + 8 bytes: conflict-free)
+constexpr int kStripStride = 392;                 // bytes per staged row (192 columns + 8 bytes: conflict-free)
 constexpr int kStripBytes = 32 * kStripStride;    // per wave
 constexpr int kInBytes = 2 * 32 * 64;             // per wave: 32 x 32 bf16 of G and of U (dAct epilogue)
 
@@ -819,9 +820,10 @@ struct TileQueue {
 // A workgroup's walk over the tiles of a launch.  Workgroups are persistent (at most one per CU); thread 0 draws the
 // next tile at the start of the current one (the atomic's latency passes during the main loop), resolves it after
 // the main loop and hands the number over through LDS; everybody reads it behind the barrier that ends the tile.
-// The two-slot hand-over buffer sits in the ring's last stage: a tile's prologue fills stages 0 .. kStages-2 only,
-// and the last stage is first refilled behind the main loop's first barrier, which no wave passes before it has read
-// the slot; it is written after the main loop's final wait, when no load is in flight.
+// The two-slot hand-over buffer sits in the last 16 bytes of the CU's LDS: behind the four-stage ring and the index
+// buffers, and inside the last unit of the five-unit ring, which a tile first refills behind its main loop's first
+// barrier - no wave passes that barrier before it has read the slot; it is written after the main loop's final wait,
+// when no load is in flight, and the epilogues' staging buffers end below it.
 struct TileWalker {
     TileQueue q;
     int* slot;
@@ -832,7 +834,7 @@ struct TileWalker {
         q.total = total;
         q.victim = blockIdx.x % kNumXcd;
         q.hops = 0;
-        slot = reinterpret_cast<int*>(smem + (kStages - 1) * kStageBytes);
+        slot = reinterpret_cast<int*>(smem + kLdsBytes - 16);
         it = 0;
         drawn = -1;
         if (threadIdx.x == 0) slot[0] = q.pop(-1);
@@ -1077,7 +1079,11 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
         // accumulator layout through a wave-private LDS buffer (rows of 64 bytes, 16-byte chunks XOR-swizzled).
         const int m = lane & 31;
         char* inbuf = smem + 8 * kStripBytes + wave * kInBytes;   // G rows, then U rows
-        uint4 gq[2][2], uq[2][2];
+#ifndef XMOE_DACT_PF
+#define XMOE_DACT_PF 1
+#endif
+        constexpr int PF = XMOE_DACT_PF;   // rounds of G / U fetched ahead
+        uint4 gq[PF + 1][2], uq[PF + 1][2];
         const int frow = lane >> 2, fchunk = lane & 3;
         auto fetch = [&](int r, uint4 (&g2)[2], uint4 (&u2)[2]) {
             const int mi = r >> 1, ni = r & 1;
@@ -1095,7 +1101,8 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                 }
             }
         };
-        fetch(0, gq[0], uq[0]);
+#pragma unroll
+        for (int r = 0; r < PF; ++r) fetch(r, gq[r], uq[r]);
         float rowpart = 0.f;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -1104,10 +1111,10 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
             for (int i = 0; i < 2; ++i) {
                 const int row = 16 * i + frow;
                 const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
-                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = gq[r & 1][i];
-                *reinterpret_cast<uint4*>(inbuf + 2048 + row * 64 + pos) = uq[r & 1][i];
+                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = gq[r % (PF + 1)][i];
+                *reinterpret_cast<uint4*>(inbuf + 2048 + row * 64 + pos) = uq[r % (PF + 1)][i];
             }
-            if (r + 1 < 8) fetch(r + 1, gq[(r + 1) & 1], uq[(r + 1) & 1]);
+            if (r + PF < 8) fetch(r + PF, gq[(r + PF) % (PF + 1)], uq[(r + PF) % (PF + 1)]);
             strip_sync();
             const int r0 = wm * 128 + mi * 32;
             const int rows_valid = rt.rows - r0;
@@ -1141,9 +1148,9 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                     av[j] = DY_GATHER ? a1 * sc : a1;
                     part = fmaf(pa, a1, part);
                 }
-                strip_put4(strip, 0, q, dg[0], dg[1], dg[2], dg[3]);
-                strip_put4(strip, 32, q, du[0], du[1], du[2], du[3]);
-                strip_put4(strip, 64, q, av[0], av[1], av[2], av[3]);
+                strip_put4(strip, ni * 32, q, dg[0], dg[1], dg[2], dg[3]);
+                strip_put4(strip, 64 + ni * 32, q, du[0], du[1], du[2], du[3]);
+                strip_put4(strip, 128 + ni * 32, q, av[0], av[1], av[2], av[3]);
             }
             if (row_part) {   // (wave-uniform) the two column halves of the row block, then the lane pair of a row
                 rowpart = ni == 0 ? part : rowpart + part;
@@ -1153,12 +1160,15 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
                         row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
                 }
             }
-            strip_sync();
-            const long o = base + ni * 32;
-            strip_flush<32>(strip, 0, dG + o, N, rows_valid, cols_valid - ni * 32);
-            strip_flush<32>(strip, 32, dU + o, N, rows_valid, cols_valid - ni * 32);
-            strip_flush<32>(strip, 64, A + o, N, rows_valid, cols_valid - ni * 32);
-            strip_sync();
+            if (ni == 1) {   // the row block's 64 columns of each output go out as whole 128-byte lines
+                strip_sync();
+                strip_flush<64>(strip, 0, dG + base, N, rows_valid, cols_valid);
+                __builtin_amdgcn_sched_barrier(0);   // (keeps the staged rows of one output in registers at a time)
+                strip_flush<64>(strip, 64, dU + base, N, rows_valid, cols_valid);
+                __builtin_amdgcn_sched_barrier(0);
+                strip_flush<64>(strip, 128, A + base, N, rows_valid, cols_valid);
+                strip_sync();
+            }
         }
     }
     }
@@ -1424,8 +1434,8 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                     av[j] = DY_GATHER ? a_ * sc : a_;
                     part = fmaf(pa, a_, part);
                 }
-                strip_put4(strip, 0, q, dh[0], dh[1], dh[2], dh[3]);
-                strip_put4(strip, 32, q, av[0], av[1], av[2], av[3]);
+                strip_put4(strip, ni * 32, q, dh[0], dh[1], dh[2], dh[3]);
+                strip_put4(strip, 64 + ni * 32, q, av[0], av[1], av[2], av[3]);
             }
             if (row_part) {
                 rowpart = ni == 0 ? part : rowpart + part;
@@ -1435,11 +1445,12 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
                         row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
                 }
             }
-            strip_sync();
-            const long o = base + ni * 32;
-            strip_flush<32>(strip, 0, dH + o, f, rows_valid, cols_valid - ni * 32);
-            strip_flush<32>(strip, 32, A + o, f, rows_valid, cols_valid - ni * 32);
-            strip_sync();
+            if (ni == 1) {
+                strip_sync();
+                strip_flush<64>(strip, 0, dH + base, f, rows_valid, cols_valid);
+                strip_flush<64>(strip, 64, A + base, f, rows_valid, cols_valid);
+                strip_sync();
+            }
         }
     }
     clock_note(clk, 1);
