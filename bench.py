@@ -287,8 +287,6 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
-    # the shader clock the matrix-core kernels ran at in the last timed step (the chip lowers it under this load)
-    clocks = xm.xmoe_prof_shader_clocks()
 
     # forward-only timing (reported, not the metric)
     torch.cuda.synchronize()
@@ -306,6 +304,9 @@ def main():
         eager_step()
     torch.cuda.synchronize()
     prof = xm.xmoe_prof_read()
+    # the shader clock the matrix-core kernels ran at in the last of these steps (the chip lowers it under this load;
+    # the kernels sample it only while the launch profiler is on)
+    clocks = xm.xmoe_prof_shader_clocks()
     xm.xmoe_prof_enable(False)
     xm.xmoe_prof_reset()
 
