@@ -36,6 +36,9 @@ constexpr int TM = 256, TN = 256, TK = 32;
 #define XMOE_DMA_STAGES 4
 #endif
 constexpr int kStages = XMOE_DMA_STAGES;
+#ifndef XMOE_DEEP_PROLOGUE
+#define XMOE_DEEP_PROLOGUE 1
+#endif
 constexpr int kOpBytes = 256 * TK * 2;          // one operand tile of one stage: 16 KiB
 constexpr int kStageBytes = 2 * kOpBytes;       // A + B
 // Behind the ring: the index buffers of the gathered K-strided operands (see Loader), per operand and wave two chunks
@@ -379,11 +382,13 @@ __device__ __forceinline__ void lds_done_and_barrier() { asm volatile("s_waitcnt
 // the other buffer of the pair.)
 
 // a k-tile of a wave that has nothing to multiply: it only feeds the ring
-template <class LA, class LB>
+template <bool ISSUE = true, class LA, class LB>
 __device__ __forceinline__ void feed_step(const LA& la, const LB& lb, char* __restrict__ st_next, int nt,
                                           const char* __restrict__ ia_rd, const char* __restrict__ ib_rd) {
-    la.template issue<false>(st_next, nt);
-    lb.template issue<false>(st_next + kOpBytes, nt);
+    if (ISSUE) {
+        la.template issue<false>(st_next, nt);
+        lb.template issue<false>(st_next + kOpBytes, nt);
+    }
     la.read_rows(nt + 1, ia_rd);
     lb.read_rows(nt + 1, ib_rd);
     la.prepare_next(nt + 1);
@@ -399,7 +404,8 @@ __device__ __forceinline__ void feed_step(const LA& la, const LB& lb, char* __re
 // The two stages are distinct, and saying so with __restrict__ matters: without it the compiler assumes an LDS
 // read may observe a direct-to-LDS load still in flight and drains every outstanding load (s_waitcnt vmcnt(0))
 // before each transposing read, which serialises the ring.
-template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER, bool B_GATHER>
+// ISSUE = false: the step of k-tile 0 where the prologue has already requested k-tile nt (see mainloop2).
+template <bool A_COL, bool B_COL, bool DUAL, bool TWO, bool A_GATHER, bool B_GATHER, bool ISSUE = true>
 __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1,
                                       const Loader<A_COL, TWO, A_GATHER>& la,
                                       const Loader<B_COL, TWO, B_GATHER>& lb, char* __restrict__ st_next,
@@ -409,10 +415,12 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
     // at raised priority, ahead of the other wave's matrix instructions on the same SIMD: measured -2 to -4 % there,
     // +4 to +10 % in the kernels with a K-contiguous operand, where it is therefore left alone.  (Raising the
     // priority during the matrix instructions instead costs 5 to 10 % everywhere.)
-    if (A_COL && B_COL) __builtin_amdgcn_s_setprio(1);
-    la.template issue<false>(st_next, nt);
-    lb.template issue<false>(st_next + kOpBytes, nt);
-    if (A_COL && B_COL) __builtin_amdgcn_s_setprio(0);
+    if (ISSUE) {
+        if (A_COL && B_COL) __builtin_amdgcn_s_setprio(1);
+        la.template issue<false>(st_next, nt);
+        lb.template issue<false>(st_next + kOpBytes, nt);
+        if (A_COL && B_COL) __builtin_amdgcn_s_setprio(0);
+    }
     read_frags<A_COL, B_COL, DUAL>(f0, st, st + kOpBytes, 0);
     mma_step(acc, f1);
     la.read_rows(nt + 1, ia_rd);
@@ -665,11 +673,33 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
     // every thread, and every wave is done reading k-tile kt-1, so that stage can be refilled with k-tile kt+3:
     // k-tiles kt+1 .. kt+3 are in flight while k-tile kt is multiplied.
     constexpr int kInFlight = (kStages - 2) * kLoadsPerTile;   // loads that may still be outstanding at the barrier
-    wait_loads_and_barrier<kInFlight>();
+    // Both operands K-strided (the weight gradients, whose K is an expert's row count: often a handful of k-tiles):
+    // nobody reads a stage before the first barrier, so the prologue requests k-tile kStages-1 as well - into the
+    // stage that iteration 0 would fill - and iteration 0 requests nothing.  A tile of up to kStages k-tiles then
+    // waits for memory once instead of twice.
+    constexpr bool kDeep = XMOE_DEEP_PROLOGUE && A_COL && B_COL;
+    if (kDeep) {
+        la.request_ahead(kStages - 1);
+        lb.request_ahead(kStages - 1);
+        la.template issue<false>(smem + (kStages - 1) * kStageBytes, kStages - 1);
+        lb.template issue<false>(smem + (kStages - 1) * kStageBytes + kOpBytes, kStages - 1);
+        wait_loads_and_barrier<kInFlight + kLoadsPerTile>();
+    } else {
+        wait_loads_and_barrier<kInFlight>();
+    }
     if (mi_count > 0) {
         Frags f0, f1;
         zero_frags(f1);   // the first call multiplies the carried fragments: zeros
-        for (int kt = 0; kt < nk; ++kt) {
+        int kt = 0;
+        if (kDeep) {
+            constexpr int nt = kStages - 1;
+            kstep<A_COL, B_COL, DUAL, TWO, A_GATHER, B_GATHER, false>(acc, f0, f1, la, lb, smem + nt * kStageBytes, smem,
+                                                                      nt, la.idx_buf((nt + 1) >> 4),
+                                                                      lb.idx_buf((nt + 1) >> 4));
+            wait_loads_and_barrier<kInFlight>();
+            kt = 1;
+        }
+        for (; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
             la.request_ahead(nt);
             lb.request_ahead(nt);
@@ -681,7 +711,14 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
         mma_step(acc, f1);   // second k-step of the last k-tile
     } else {
         // a wave whose rows (or columns) all lie past the ragged tail: it only feeds the ring and keeps the barriers
-        for (int kt = 0; kt < nk; ++kt) {
+        int kt = 0;
+        if (kDeep) {
+            constexpr int nt = kStages - 1;
+            feed_step<false>(la, lb, smem + nt * kStageBytes, nt, la.idx_buf((nt + 1) >> 4), lb.idx_buf((nt + 1) >> 4));
+            wait_loads_and_barrier<kInFlight>();
+            kt = 1;
+        }
+        for (; kt < nk; ++kt) {
             const int nt = kt + kStages - 1;
             la.request_ahead(nt);
             lb.request_ahead(nt);
@@ -863,6 +900,34 @@ struct TileWalker {
         return __builtin_amdgcn_readfirstlane(slot[it & 1]);
     }
 };
+
+// The weight gradients' tiles: experts in the order of `order` (longest first), tpe tiles each.  Dealt group by group
+// round the XCDs, an expert's tiles would be spread over all of them and every L2 would fetch the expert's two operand
+// panels (K rows of P and of Q) for itself.  Instead the queue numbers are mapped so that ONE list holds all tiles of an
+// expert: list x has the experts at positions x, x+8, x+16, ... of `order`, one after the other (the lists stay
+// balanced to within the stealing at the end, since neighbours in `order` have similar lengths).  The lists are
+// padded to whole groups of equal number; the padding and the positions past E are holes without work.
+// The host asks for this (one_xcd) where an expert's two panels fit an L2 with room to spare, which is where it pays:
+// measured -2.4 % and -4.8 % on the backward launch of the 256-expert shapes (128 to 192 rows per expert, memory
+// bound), +1.6 % at 64 experts of 770 rows, whose 6 MB of panels do not fit one L2 and are better off spread.
+__device__ __forceinline__ int wgrad_queue_total(int E, int tpe, bool one_xcd) {
+    if (!one_xcd) return E * tpe;
+    const int per_list = ((E + kNumXcd - 1) / kNumXcd) * tpe;
+    return ((per_list + kQueueGroup - 1) / kQueueGroup) * kQueueGroup * kNumXcd;
+}
+// queue number t -> position in `order` and tile of that expert; false: a hole
+__device__ __forceinline__ bool wgrad_queue_tile(int t, int E, int tpe, bool one_xcd, int& pos, int& u) {
+    if (!one_xcd) {
+        pos = t / tpe;
+        u = t - pos * tpe;
+        return true;
+    }
+    const int g = t / kQueueGroup, x = g % kNumXcd;
+    const int l = (g / kNumXcd) * kQueueGroup + t % kQueueGroup;   // number within list x
+    pos = (l / tpe) * kNumXcd + x;
+    u = l % tpe;
+    return pos < E;
+}
 
 #ifndef XMOE_ROW_BAND
 #define XMOE_ROW_BAND 4
@@ -1470,16 +1535,20 @@ __device__ __forceinline__ void wgrad_tile(int t, TileWalker& tw, char* smem, co
                                            const bf16_t* __restrict__ Q2, const int32_t* __restrict__ q_index,
                                            const int32_t* __restrict__ row_index_dma,
                                            const int32_t* __restrict__ q_index_dma, const int32_t* __restrict__ off,
-                                           const int32_t* __restrict__ order, int M, int N,
-                                           bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
+                                           const int32_t* __restrict__ order, int E, bool one_xcd, int M,
+                                           int N, bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2) {
     constexpr int NB = DUAL ? 128 : TN;   // output columns per block and matrix
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
-    const int e = order[t / (mt * nt)];
+    int pos, u;
+    if (!wgrad_queue_tile(t, E, mt * nt, one_xcd, pos, u)) {
+        tw.hand_over();
+        return;
+    }
+    const int e = order[pos];
     // Inside an expert the tiles are numbered band by band (kWgradBand tile rows), down the columns of a band, so
     // that the kQueueGroup consecutive tiles a group of workgroups takes form a 2 x 8 block of tiles rather than a
     // 1 x 16 strip: the operand that the strip would fetch once per tile is then fetched once per two tiles
     // (measured: bands of 2 beat bands of 1 and of 4 by 3 to 4 % on both the long and the short segments).
-    const int u = t % (mt * nt);
     const int band = u / (kWgradBand * nt);
     const int in_band = u - band * kWgradBand * nt;
     const int band_rows = mt - band * kWgradBand < kWgradBand ? mt - band * kWgradBand : kWgradBand;
@@ -1547,17 +1616,19 @@ __global__ __launch_bounds__(512) void ffn_wgrad_dma_kernel(const bf16_t* __rest
                                                             const int32_t* __restrict__ q_index_dma,
                                                             const int32_t* __restrict__ off,
                                                             const int32_t* __restrict__ order,
-                                                            int32_t* __restrict__ counters, int E, int M, int N,
-                                                            bf16_t* __restrict__ dW1, bf16_t* __restrict__ dW2, unsigned long long* __restrict__ clk) {
+                                                            int32_t* __restrict__ counters, int E, int one_xcd,
+                                                            int M, int N, bf16_t* __restrict__ dW1,
+                                                            bf16_t* __restrict__ dW2,
+                                                            unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
     clock_note(clk, 0);
     constexpr int NB = DUAL ? 128 : TN;
     const int mt = (M + TM - 1) / TM, nt = (N + NB - 1) / NB;
     TileWalker tw;
-    for (int t = tw.start(counters, E * mt * nt, smem); t >= 0; t = tw.next()) {
+    for (int t = tw.start(counters, wgrad_queue_total(E, mt * nt, one_xcd), smem); t >= 0; t = tw.next()) {
         tw.draw();
         wgrad_tile<DUAL, GATHER, QGATHER>(t, tw, smem, P, row_index, Q1, Q2, q_index, row_index_dma, q_index_dma, off,
-                                          order, M, N, dW1, dW2);
+                                          order, E, one_xcd, M, N, dW1, dW2);
     }
     clock_note(clk, 1);
 }
@@ -1577,7 +1648,8 @@ __global__ __launch_bounds__(512) void ffn_bwd_rest_dma_kernel(
     const bf16_t* __restrict__ dY, const int32_t* __restrict__ dy_index, const int32_t* __restrict__ dy_index_dma,
     const bf16_t* __restrict__ xd, const int32_t* __restrict__ row_index, const int32_t* __restrict__ row_index_dma,
     const int32_t* __restrict__ off, const int32_t* __restrict__ map, const int32_t* __restrict__ order,
-    int32_t* __restrict__ cnt_dx, int32_t* __restrict__ cnt_wd, int32_t* __restrict__ cnt_wgu, int E, int d, int f,
+    int32_t* __restrict__ cnt_dx, int32_t* __restrict__ cnt_wd, int32_t* __restrict__ cnt_wgu, int E, int one_xcd,
+    int d, int f,
     const bf16_t* __restrict__ wg, const bf16_t* __restrict__ wu, bf16_t* __restrict__ dXd, bf16_t* __restrict__ dWd,
     bf16_t* __restrict__ dWg, bf16_t* __restrict__ dWu, unsigned long long* __restrict__ clk) {
     extern __shared__ __align__(16) char smem[];
@@ -1589,17 +1661,19 @@ __global__ __launch_bounds__(512) void ffn_bwd_rest_dma_kernel(
     }
     // a walk's start writes the hand-over slot that the last next() of the walk before it has just read
     __syncthreads();
-    for (int t = tw.start(cnt_wd, E * ((f + TM - 1) / TM) * ((d + TN - 1) / TN), smem); t >= 0; t = tw.next()) {
+    for (int t = tw.start(cnt_wd, wgrad_queue_total(E, ((f + TM - 1) / TM) * ((d + TN - 1) / TN), one_xcd), smem); t >= 0;
+         t = tw.next()) {
         tw.draw();
         wgrad_tile<false, false, DY_GATHER>(t, tw, smem, act, nullptr, dY, nullptr, dy_index, nullptr, dy_index_dma,
-                                            off, order, f, d, dWd, nullptr);
+                                            off, order, E, one_xcd, f, d, dWd, nullptr);
     }
     __syncthreads();
     constexpr int NB = SWIGLU ? 128 : TN;
-    for (int t = tw.start(cnt_wgu, E * ((d + TM - 1) / TM) * ((f + NB - 1) / NB), smem); t >= 0; t = tw.next()) {
+    for (int t = tw.start(cnt_wgu, wgrad_queue_total(E, ((d + TM - 1) / TM) * ((f + NB - 1) / NB), one_xcd), smem); t >= 0;
+         t = tw.next()) {
         tw.draw();
         wgrad_tile<SWIGLU, GATHER, false>(t, tw, smem, xd, row_index, dG, dU, nullptr, row_index_dma, nullptr, off,
-                                          order, d, f, dWg, dWu);
+                                          order, E, one_xcd, d, f, dWg, dWu);
     }
     clock_note(clk, 1);
 }
@@ -1661,12 +1735,16 @@ static inline unsigned long long* clock_slot(int slot) {
 }
 
 template <class Kern>
-static int allow_big_lds(Kern k) {
-    // kernels of this family use 136 KiB of dynamic LDS, above the 64 KiB default limit
+static int allow_lds(Kern k, int bytes) {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               kLdsBytes) == hipSuccess
+                               bytes) == hipSuccess
                ? XMOE_OK
                : XMOE_ERR_HIP;
+}
+template <class Kern>
+static int allow_big_lds(Kern k) {
+    // the large-tile kernels use all 160 KiB of a CU's LDS, above the 64 KiB default limit
+    return allow_lds(k, kLdsBytes);
 }
 
 static int init_device() {
@@ -1715,6 +1793,16 @@ static int init_device() {
     if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, false>);
     if (st == XMOE_OK) st = allow_big_lds(ffn_wgrad_dma_kernel<true, true>);
     return ds.status = st;
+}
+
+// whether the weight gradients' tiles of an expert all go to one XCD: where its two panels (the mean number of rows
+// of the d-wide and the f-wide operand) take at most 3 MiB of that XCD's 4 MiB of L2
+#ifndef XMOE_WGRAD_ONE_XCD_BYTES
+#define XMOE_WGRAD_ONE_XCD_BYTES (3l << 20)
+#endif
+template <class Args>
+static inline int wgrad_one_xcd(const Args& a) {
+    return (long)(a.B / (a.E > 0 ? a.E : 1) + 1) * (a.d + a.f) * 2 <= XMOE_WGRAD_ONE_XCD_BYTES;
 }
 
 int ffn_fwd_dma(const FfnArgs& a, hipStream_t s) {
@@ -1781,7 +1869,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                 hipLaunchKernelGGL((ffn_bwd_rest_dma_kernel<true, G, DYG>), grid, dim3(512), kLdsBytes, s, dg, du,    \
                                    act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off, a.map,       \
                                    a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E, a.sched + a.E + kNumXcd,    \
-                                   a.E, a.d, a.f, wg, wu, (bf16_t*)a.dxd, (bf16_t*)a.dwd, (bf16_t*)a.dwg,             \
+                                   a.E, wgrad_one_xcd(a), a.d, a.f, wg, wu, (bf16_t*)a.dxd, (bf16_t*)a.dwd, (bf16_t*)a.dwg,             \
                                    (bf16_t*)a.dwu, clock_slot(CS_BWD_REST)))
         if (a.row_index && a.dy_index) XMOE_REST(true, true);
         else if (a.row_index) XMOE_REST(true, false);
@@ -1798,7 +1886,7 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
-                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
+                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, wgrad_one_xcd(a), a.f,
                                        a.d,
                                        (bf16_t*)a.dwd, nullptr, clock_slot(CS_WGRAD)));
     else
@@ -1806,19 +1894,19 @@ int ffn_bwd_dma(const FfnArgs& a, hipStream_t s) {
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
                                        dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dwd, nullptr, clock_slot(CS_WGRAD)));
+                                       a.sched + a.E, a.E, wgrad_one_xcd(a), a.f, a.d, (bf16_t*)a.dwd, nullptr, clock_slot(CS_WGRAD)));
     // dWg, dWu [d, f] = Xd^T dG, Xd^T dU in one launch
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, true>), dim3(round_up8((long)a.E * mtd * ntf2)),
                                        dim3(512), kLdsBytes, s, xd, a.row_index, dg, du, nullptr, a.row_index, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
+                                       a.sched + a.E + kNumXcd, a.E, wgrad_one_xcd(a), a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DUAL_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<true, false>), dim3(round_up8((long)a.E * mtd * ntf2)),
                                        dim3(512), kLdsBytes, s, xd, nullptr, dg, du, nullptr, nullptr, nullptr, a.off, a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
+                                       a.sched + a.E + kNumXcd, a.E, wgrad_one_xcd(a), a.d, a.f, (bf16_t*)a.dwg, (bf16_t*)a.dwu, clock_slot(CS_WGRAD_DUAL)));
     return XMOE_OK;
 }
 
@@ -1907,7 +1995,8 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
                 hipLaunchKernelGGL((ffn_bwd_rest_dma_kernel<false, G, DYG>), grid_rest, dim3(512), kLdsBytes, s, dh,  \
                                    nullptr, act, dy, a.dy_index, a.dy_index, xd, a.row_index, a.row_index, a.off,     \
                                    a.map, a.sched, row_counters(a.sched, a.E, 1), a.sched + a.E,                      \
-                                   a.sched + a.E + kNumXcd, a.E, a.d, a.f, w1, nullptr, (bf16_t*)a.dxd,               \
+                                   a.sched + a.E + kNumXcd, a.E, wgrad_one_xcd(a), a.d, a.f, w1, nullptr,             \
+                                   (bf16_t*)a.dxd,                                                                    \
                                    (bf16_t*)a.dw2, (bf16_t*)a.dw1, nullptr, clock_slot(CS_BWD_REST)))
         if (a.row_index && a.dy_index) XMOE_REST(true, true);
         else if (a.row_index) XMOE_REST(true, false);
@@ -1925,7 +2014,7 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false, true>),
                                        dim3(round_up8((long)a.E * mtf * ntd)), dim3(512), kLdsBytes, s, act, nullptr, dy,
-                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, a.f,
+                                       nullptr, a.dy_index, nullptr, a.dy_index, a.off, a.sched, a.sched + a.E, a.E, wgrad_one_xcd(a), a.f,
                                        a.d,
                                        (bf16_t*)a.dw2, nullptr, clock_slot(CS_WGRAD)));
     else
@@ -1933,20 +2022,20 @@ int mlp2_bwd_dma(const Mlp2Args& a, hipStream_t s) {
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtf * ntd)),
                                        dim3(512), kLdsBytes, s, act, nullptr, dy, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E, a.E, a.f, a.d, (bf16_t*)a.dw2, nullptr, clock_slot(CS_WGRAD)));
+                                       a.sched + a.E, a.E, wgrad_one_xcd(a), a.f, a.d, (bf16_t*)a.dw2, nullptr, clock_slot(CS_WGRAD)));
     // dW1 [d, f] = Xd^T dH
     if (a.row_index)
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, true>), dim3(round_up8((long)a.E * mtd * ntf)),
                                        dim3(512), kLdsBytes, s, xd, a.row_index, dh, nullptr, nullptr, a.row_index, nullptr,
                                        a.off, a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
+                                       a.sched + a.E + kNumXcd, a.E, wgrad_one_xcd(a), a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
     else
         XMOE_LAUNCH(K_FFN_WGRAD_DMA, s,
                     hipLaunchKernelGGL((ffn_wgrad_dma_kernel<false, false>), dim3(round_up8((long)a.E * mtd * ntf)),
                                        dim3(512), kLdsBytes, s, xd, nullptr, dh, nullptr, nullptr, nullptr, nullptr, a.off,
                                        a.sched,
-                                       a.sched + a.E + kNumXcd, a.E, a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
+                                       a.sched + a.E + kNumXcd, a.E, wgrad_one_xcd(a), a.d, a.f, (bf16_t*)a.dw1, nullptr, clock_slot(CS_WGRAD)));
     return XMOE_OK;
 }
 
