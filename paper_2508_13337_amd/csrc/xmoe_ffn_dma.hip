@@ -36,6 +36,9 @@ constexpr int TM = 256, TN = 256, TK = 32;
 #define XMOE_DMA_STAGES 4
 #endif
 constexpr int kStages = XMOE_DMA_STAGES;
+#ifndef XMOE_RC_RING
+#define XMOE_RC_RING 1
+#endif
 #ifndef XMOE_DEEP_PROLOGUE
 #define XMOE_DEEP_PROLOGUE 1
 #endif
@@ -635,6 +638,115 @@ __device__ __forceinline__ void mainloop_rr(f32x16_t (&acc)[4][2], const Operand
     wait_loads_and_barrier<0>();
 }
 
+// =========================================================================================================
+// A K-contiguous, B K-strided (gate/up and down: activation rows x weights "in x out").  The same observation as for
+// the row x row kernels, applied to the one operand it concerns: A is loaded 64 k at a time as units of
+// [256 rows][64 k] (whole 128-byte lines), B stays in 32-wide k-tiles of [32 k][256 n] (512-byte rows, whole lines
+// already).  LDS: three A units (96 KiB) and behind them four B tiles (64 KiB).  One pass = the two k-tiles of A(p):
+// the first requests A(p+2) and B(2p+3), the second B(2p+4); at every barrier the wave may have eight requests
+// outstanding (the two newest B tiles and the newest A unit), so A runs two units and B three tiles ahead, as in the
+// rings above.  The hand-over slot of the tile walk lies in the last bytes of the fourth B tile, which a tile first
+// refills behind its main loop's first barrier.  The compiler's own order of requests, fragment reads and matrix
+// instructions is kept (prescribing kstep's interleaving here measured the same).  Measured against the four-stage
+// ring of 32-wide k-tiles for both operands (XMOE_RC_RING=0): down -2 to -3 %, the two-matrix expert's up
+// projection -3 %, gate/up -1 to -2 %.
+// =========================================================================================================
+constexpr int kRcAUnits = 3;
+constexpr int kRcBStages = 4;
+constexpr int kRcBBase = kRcAUnits * kUnitBytes;
+static_assert(kRcBBase + kRcBStages * kOpBytes <= kLdsBytes, "three A units and four B tiles");
+
+// one k-tile: HALF2 = false: the first k-tile of A's unit (requests the unit two passes ahead), true: the second
+template <bool DUAL, bool A_GATHER, bool HALF2>
+__device__ __forceinline__ void rc_step(f32x16_t (&acc)[4][2], Frags& f0, Frags& f1, const RowLoader<A_GATHER>& la,
+                                        const Loader<true, false, false>& lb, char* __restrict__ fill_a,
+                                        const char* a_kb, bool a_zero, char* __restrict__ fill_b,
+                                        const char* __restrict__ ua, const char* __restrict__ tb, int nt) {
+    if (!HALF2) la.issue(fill_a, a_kb, a_zero);
+    lb.template issue<false>(fill_b, nt);
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) f0.b[ni] = read_frag<true>(tb, b_col<DUAL>(wn, ni), 0);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) f0.a[mi] = read_frag_unit(ua, wm * 128 + mi * 32, HALF2 ? 2 : 0);
+    mma_step(acc, f1);
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) f1.b[ni] = read_frag<true>(tb, b_col<DUAL>(wn, ni), 1);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) f1.a[mi] = read_frag_unit(ua, wm * 128 + mi * 32, HALF2 ? 3 : 1);
+    mma_step(acc, f0);
+    lb.prepare_next(nt + 1);
+}
+template <bool A_GATHER, bool HALF2>
+__device__ __forceinline__ void rc_feed(const RowLoader<A_GATHER>& la, const Loader<true, false, false>& lb,
+                                        char* __restrict__ fill_a, const char* a_kb, bool a_zero,
+                                        char* __restrict__ fill_b, int nt) {
+    if (!HALF2) la.issue(fill_a, a_kb, a_zero);
+    lb.template issue<false>(fill_b, nt);
+    lb.prepare_next(nt + 1);
+}
+
+// acc += A x B over K, a multiple of 64.  mi_count as in mainloop2.
+template <bool DUAL, bool A_GATHER>
+__device__ __forceinline__ void mainloop_rc(f32x16_t (&acc)[4][2], const Operand& oa, const Operand& ob, int K,
+                                            int mi_count, char* smem) {
+    const int np = K / 64, nk = 2 * np;
+    if (np <= 0) return;
+    mi_count = __builtin_amdgcn_readfirstlane(mi_count);
+    RowLoader<A_GATHER> la;
+    Loader<true, false, false> lb;
+    la.init(oa);
+    lb.init(ob, ob, nk, nk, smem);   // (no index buffers: B is not gathered)
+    const char* a0 = reinterpret_cast<const char*>(oa.p_lo);
+    const char* zero16 = reinterpret_cast<const char*>(kZero16);
+    char* bt = smem + kRcBBase;
+    // prologue: A(0), B(0), then A(1), B(1), B(2): the first wait leaves exactly those last three outstanding
+    la.issue(smem, a0, false);
+    lb.template issue<true>(bt, 0);
+    lb.prepare_next(1);
+    la.issue(smem + kUnitBytes, np > 1 ? a0 + 128 : zero16, np <= 1);
+    lb.template issue<true>(bt + kOpBytes, 1);
+    lb.prepare_next(2);
+    lb.template issue<true>(bt + 2 * kOpBytes, 2);
+    lb.prepare_next(3);
+    wait_loads_and_barrier<8>();
+    int sa = 0;   // slot of A(p) = p % 3
+    int sb = 0;   // stage of B(2p) = 2p % 4: 0 or 2
+#define XMOE_RC_LOOP(STEP_A, STEP_B)                                                                                  \
+    for (int p = 0; p < np; ++p) {                                                                                    \
+        const int s2 = sa + 2 < kRcAUnits ? sa + 2 : sa + 2 - kRcAUnits;                                              \
+        const bool z = p + 2 >= np;                                                                                   \
+        const char* kb = z ? zero16 : a0 + (long)(p + 2) * 128;                                                       \
+        STEP_A(smem + s2 * kUnitBytes, kb, z, bt + ((sb + 3) & 3) * kOpBytes, smem + sa * kUnitBytes,                 \
+               bt + sb * kOpBytes, 2 * p + 3);                                                                        \
+        wait_loads_and_barrier<8>();                                                                                  \
+        STEP_B(smem + s2 * kUnitBytes, kb, z, bt + sb * kOpBytes, smem + sa * kUnitBytes, bt + (sb + 1) * kOpBytes,   \
+               2 * p + 4);                                                                                            \
+        wait_loads_and_barrier<8>();                                                                                  \
+        sa = sa + 1 < kRcAUnits ? sa + 1 : 0;                                                                         \
+        sb ^= 2;                                                                                                      \
+    }
+    if (mi_count > 0) {
+        Frags f0, f1;
+        zero_frags(f1);
+#define XMOE_RC_A(fa, kb, z, fb, ua, tb, nt) rc_step<DUAL, A_GATHER, false>(acc, f0, f1, la, lb, fa, kb, z, fb, ua, tb, nt)
+#define XMOE_RC_B(fa, kb, z, fb, ua, tb, nt) rc_step<DUAL, A_GATHER, true>(acc, f0, f1, la, lb, fa, kb, z, fb, ua, tb, nt)
+        XMOE_RC_LOOP(XMOE_RC_A, XMOE_RC_B)
+#undef XMOE_RC_A
+#undef XMOE_RC_B
+        mma_step(acc, f1);
+    } else {
+#define XMOE_RC_A(fa, kb, z, fb, ua, tb, nt) rc_feed<A_GATHER, false>(la, lb, fa, kb, z, fb, nt)
+#define XMOE_RC_B(fa, kb, z, fb, ua, tb, nt) rc_feed<A_GATHER, true>(la, lb, fa, kb, z, fb, nt)
+        XMOE_RC_LOOP(XMOE_RC_A, XMOE_RC_B)
+#undef XMOE_RC_A
+#undef XMOE_RC_B
+    }
+#undef XMOE_RC_LOOP
+    wait_loads_and_barrier<0>();
+}
+
 // acc += A x B over K (+ A2 x B2 over K2 when TWO).  mi_count = number of 32-row blocks of this wave that hold
 // valid rows; 0 skips the MFMAs but the wave still takes part in the loads and barriers.  (Skipping single
 // 32-row blocks inside the loop is not worth it: guarded accumulator updates make the compiler copy all 128
@@ -646,6 +758,12 @@ __device__ __forceinline__ void mainloop2(f32x16_t (&acc)[4][2], const Operand& 
 #ifndef XMOE_NO_UNIT_RING
     if constexpr (!A_COL && !B_COL && !B_GATHER) {
         mainloop_rr<TWO, A_GATHER>(acc, oa, ob, K, oa2, ob2, K2, mi_count, smem);
+        return;
+    }
+#endif
+#if XMOE_RC_RING
+    if constexpr (!A_COL && B_COL && !B_GATHER && !TWO) {
+        mainloop_rc<DUAL, A_GATHER>(acc, oa, ob, K, mi_count, smem);
         return;
     }
 #endif
