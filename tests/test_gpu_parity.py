@@ -449,6 +449,58 @@ def test_expert_ffn_fwd_bwd(name):
                               ws, row_index=tok, dy_row_index=None, dy_row_scale=cw)
 
 
+@pytest.mark.parametrize("d,f", [(64, 64), (64, 192), (192, 64), (128, 128)])
+def test_expert_ffn_smallest_widths(d, f):
+    """The narrowest shapes the matrix-core kernels take (d, f multiples of 64): K of one or two 64-wide passes, so the
+    main loops' prologues request units past the end of K, and output tiles a quarter wide.  Forward and backward, rows
+    gathered, against the oracle; an empty expert, a one-row-tile tail of one row."""
+    m = xm()
+    rows = (300, 0, 17, 257)
+    rng = np.random.default_rng(1000 * d + f)
+    T, E = 400, len(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    B = int(off[-1])
+    dt = "bf16"
+    tdt = torch_dtype(dt)
+    x = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), dt)
+    dout = xi.round_to_storage(rng.standard_normal((T, d)).astype(np.float32), dt)
+    tok = rng.integers(0, T, size=B).astype(np.int32)
+    cw = rng.random(B).astype(np.float32)
+    wg, wu = (xi.round_to_storage((rng.standard_normal((E, d, f)) / np.sqrt(d)).astype(np.float32), dt) for _ in range(2))
+    wd = xi.round_to_storage((rng.standard_normal((E, f, d)) / np.sqrt(f)).astype(np.float32), dt)
+    code = m.dtype_code(tdt)
+    ws = m.alloc_workspace(max(m.xmoe_workspace_bytes(m.WS_FFN_FWD, B, d, E, 1, f, code),
+                               m.xmoe_workspace_bytes(m.WS_FFN_BWD, B, d, E, 1, f, code)))
+    g = torch.empty((B, f), dtype=tdt, device="cuda")
+    u, y = torch.empty_like(g), torch.empty((B, d), dtype=tdt, device="cuda")
+    m.xmoe_prof_reset()
+    m.xmoe_prof_enable(True)
+    m.xmoe_expert_ffn_fwd(to_dev(x, dt), i32(off), to_dev(wg, dt), to_dev(wu, dt), to_dev(wd, dt), g, u, y, ws,
+                          row_index=i32(tok))
+    torch.cuda.synchronize()
+    launched = set(m.xmoe_prof_read())
+    m.xmoe_prof_enable(False)
+    m.xmoe_prof_reset()
+    assert "ffn_gateup_dma_kernel" in launched, launched
+    Xd = x.astype(np.float64)[tok]
+    Y, G, U = oracle.expert_ffn_fwd(Xd, off, wg.astype(np.float64), wu.astype(np.float64), wd.astype(np.float64))
+    assert_close(to_host(g), G, dt, "G", floor="row")
+    assert_close(to_host(u), U, dt, "U", floor="row")
+    assert_close(to_host(y), Y, dt, "Y", floor="row")
+    Gs, Us = to_host(g), to_host(u)          # the stored activations the backward starts from
+    dY = cw.astype(np.float64)[:, None] * dout.astype(np.float64)[tok]
+    ref = oracle.expert_ffn_bwd(Xd, Gs, Us, dY, off, wg.astype(np.float64), wu.astype(np.float64), wd.astype(np.float64))
+    dxd = torch.empty((B, d), dtype=tdt, device="cuda")
+    dwg = torch.full((E, d, f), 3.0, dtype=tdt, device="cuda")
+    dwu, dwd = torch.full_like(dwg, 3.0), torch.full((E, f, d), 3.0, dtype=tdt, device="cuda")
+    m.xmoe_expert_ffn_bwd(to_dev(x, dt), g, u, to_dev(dout, dt), i32(off), to_dev(wg, dt), to_dev(wu, dt),
+                          to_dev(wd, dt), dxd, dwg, dwu, dwd, ws, row_index=i32(tok), dy_row_index=i32(tok),
+                          dy_row_scale=f32(cw))
+    for got, want, what in zip((dxd, dwg, dwu, dwd), ref, ("dXd", "dWg", "dWu", "dWd")):
+        assert_close(to_host(got), want, dt, what, floor="row" if what == "dXd" else "expert")
+    assert not dwg[1].any() and not dwu[1].any() and not dwd[1].any()
+
+
 @pytest.mark.parametrize("rows", [(1537, 0, 163), (2049, 31, 1), (513, 512, 511)])
 def test_expert_ffn_bwd_long_ragged_segments(rows):
     """Segments of several index chunks (a K-strided gathered operand fetches its row indices 16 k-tiles = 512 rows at
