@@ -215,7 +215,9 @@ int xmoe_dispatch(const void* x, const int32_t* token_ids, int T, int B, int d, 
  * as one of the two activation tensors worth removing): xd is then the token matrix x [T,d] itself, row_index [B]
  * int32 holds token ids (token_ids of the ERI-arrays), and row i of the expert input is x[row_index[i]]; no [B,d]
  * copy of the tokens exists.  Entries of rows outside every segment are never read.  Results are bit-identical to
- * the call on the dispatched copy.
+ * the call on the dispatched copy.  The token matrix reached through row_index (and the one reached through
+ * dy_row_index in the backward call) may span at most 64 GiB: the matrix-core kernels address a gathered row with a
+ * 32-bit offset in units of 16 bytes.  The calls do not know T and cannot check this.
  * Shared experts are served by the same call as E_s further experts whose segments are all T tokens: expert_offsets
  * continues with B+T, B+2T, ..., the weights of the shared experts follow the routed ones, and the rows are x again
  * (row_index continues with 0..T-1 per shared expert; or xmoe_dispatch makes the copies).  (A single call on x

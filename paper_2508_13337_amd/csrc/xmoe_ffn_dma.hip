@@ -477,7 +477,10 @@ __device__ __forceinline__ void kstep(f32x16_t (&acc)[4][2], Frags& f0, Frags& f
 // =========================================================================================================
 template <bool GATHER>
 struct RowLoader {
-    uint32_t off[4];   // byte offset of this lane's 16 bytes in instruction i: source row * ld * 2 + chunk * 16
+    // offset of this lane's 16 bytes in instruction i from (row 0, first k of the unit): source row * ld * 2 +
+    // chunk * 16 bytes.  Rows of the tile itself: in bytes.  GATHER: the source row is any row of the gathered
+    // matrix, so the offset is kept in units of 16 bytes (ld is a multiple of 64 elements) and reaches 64 GiB.
+    uint32_t off[4];
     __device__ __forceinline__ void init(const Operand& o) {
         const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         int grow[4] = {0, 0, 0, 0};
@@ -494,7 +497,8 @@ struct RowLoader {
             const int row = wave * 32 + i * 8 + (lane >> 3);
             const int src = GATHER ? grow[i] : (row < o.n_lo ? row : o.n_lo - 1);
             const int c = (lane & 7) ^ ((row >> 1) & 7);
-            off[i] = (uint32_t)src * (uint32_t)(o.ld * 2) + (uint32_t)(c * 16);
+            off[i] = GATHER ? (uint32_t)src * (uint32_t)(o.ld / 8) + (uint32_t)c
+                            : (uint32_t)src * (uint32_t)(o.ld * 2) + (uint32_t)(c * 16);
         }
     }
     // kbase: wave-uniform address of (row 0, first k of the unit); zero: the unit lies past the end of K and every
@@ -504,7 +508,8 @@ struct RowLoader {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t o = zero ? 0u : off[i];
-            __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + o), LDS_PTR(unit + (wave * 32 + i * 8) * 128), 16, 0, 0);
+            const char* p = GATHER ? kbase + ((unsigned long long)o << 4) : kbase + o;
+            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(unit + (wave * 32 + i * 8) * 128), 16, 0, 0);
         }
     }
 };
