@@ -1030,9 +1030,9 @@ struct TileWalker {
 // expert: list x has the experts at positions x, x+8, x+16, ... of `order`, one after the other (the lists stay
 // balanced to within the stealing at the end, since neighbours in `order` have similar lengths).  The lists are
 // padded to whole groups of equal number; the padding and the positions past E are holes without work.
-// The host asks for this (one_xcd) where an expert's two panels fit an L2 with room to spare, which is where it pays:
-// measured -2.4 % and -4.8 % on the backward launch of the 256-expert shapes (128 to 192 rows per expert, memory
-// bound), +1.6 % at 64 experts of 770 rows, whose 6 MB of panels do not fit one L2 and are better off spread.
+// The host asks for this (one_xcd) where an expert's two panels are not much larger than an L2, which is where it pays:
+// measured -2.4 % and -4.8 % on the backward launch of the 256-expert shapes (128 rows per expert, memory bound),
+// -3.2 % at 128 experts of 384 rows, +1.6 % at 64 experts of 770 rows, whose 6.6 MB of panels are better off spread.
 __device__ __forceinline__ int wgrad_queue_total(int E, int tpe, bool one_xcd) {
     if (!one_xcd) return E * tpe;
     const int per_list = ((E + kNumXcd - 1) / kNumXcd) * tpe;
@@ -1919,9 +1919,10 @@ static int init_device() {
 }
 
 // whether the weight gradients' tiles of an expert all go to one XCD: where its two panels (the mean number of rows
-// of the d-wide and the f-wide operand) take at most 3 MiB of that XCD's 4 MiB of L2
+// of the d-wide and the f-wide operand) take at most 5.5 MiB - somewhat more than that XCD's 4 MiB of L2 still pays
+// (measured: 2.5 MiB -2.4 %, 4.9 MiB -3.2 %, 5.1 MiB +-0, 6.6 MiB +1.6 % on the backward launch)
 #ifndef XMOE_WGRAD_ONE_XCD_BYTES
-#define XMOE_WGRAD_ONE_XCD_BYTES (3l << 20)
+#define XMOE_WGRAD_ONE_XCD_BYTES (11l << 19)
 #endif
 template <class Args>
 static inline int wgrad_one_xcd(const Args& a) {
