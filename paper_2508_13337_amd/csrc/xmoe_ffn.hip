@@ -80,7 +80,7 @@ int xmoe_expert_ffn_bwd(const void* xd, const int32_t* row_index, const void* g_
     a.act = p;
     p += ffn_act_bytes(B, f, dt);
     a.row_grad = dy_row_scale_grad;
-    a.row_part = dy_row_scale_grad ? (float*)p : nullptr;
+    a.row_part = (float*)p;   // the partial sums are always written (the matrix-core kernel has no branch for them)
     hipStream_t s = (hipStream_t)stream;
     if (ffn_dma_supported(a)) return ffn_bwd_dma(a, s);
     return ffn_bwd_simt(a, s);

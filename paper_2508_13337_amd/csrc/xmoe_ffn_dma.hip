@@ -61,6 +61,7 @@ constexpr int kLoadsPerTile = 4;                // per thread: 2 for A, 2 for B
 constexpr int kNumXcd = 8;
 
 __device__ __align__(16) const unsigned int kZero16[4] = {0u, 0u, 0u, 0u};
+__device__ const float kOneF = 1.0f;
 
 // Shader clock under load: workgroup 0 of every launch of this family notes the shader-clock counter and the
 // constant 100 MHz counter when it starts and when it leaves (it is persistent, so that spans the launch); the
@@ -914,24 +915,31 @@ __device__ __forceinline__ void strip_put4(char* strip, int col0, int q, float a
 // again and that are written as whole 128-byte lines: they then do not displace the operand panels the workgroups of
 // an XCD share through L2 (measured -1 to -2 % in the down, dX and weight-gradient kernels; the gate/up kernel, whose
 // rows go out as 64-byte pieces, is 2.5 % slower with them and keeps ordinary stores).
-template <int NC, bool NT = false>
+// MASK = false: the caller knows that all 32 rows and NC columns are valid; the stores then stand outside any
+// branch, and the compiler can tell how many of them are outstanding at a later wait (see the dAct epilogue).
+// OFF32: a lane's address is a wave-uniform row group of C plus a fixed 32-bit offset (fewer address registers; it
+// pays in the dAct epilogue, which is short of registers, and costs 1 to 5 % in the other kernels).
+template <int NC, bool NT = false, bool MASK = true, bool OFF32 = false>
 __device__ __forceinline__ void strip_flush(const char* strip, int col0, bf16_t* C, long ldc, int rows_valid,
                                             int cols_valid) {
     const int lane = threadIdx.x & 63;
     constexpr int LPR = NC / 4;          // lanes per row, 4 columns (8 bytes) each
     constexpr int RPI = 64 / LPR;        // rows per instruction
     const int c4 = (lane % LPR) * 4;
+    const uint32_t o = (uint32_t)((lane / LPR) * (int)ldc + c4) * 2u;
 #pragma unroll
     for (int it = 0; it < 32 / RPI; ++it) {
         const int r = it * RPI + lane / LPR;
-        if (r < rows_valid && c4 < cols_valid) {
+        if (!MASK || (r < rows_valid && c4 < cols_valid)) {
             const uint2 v = *reinterpret_cast<const uint2*>(strip + r * kStripStride + (col0 + c4) * 2);
+            bf16_t* dst = OFF32 ? reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(C + (long)(it * RPI) * ldc) + o)
+                                : C + (long)r * ldc + c4;
             if (NT) {
                 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
                 const u32x2_t w = {v.x, v.y};
-                __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t*>(C + (long)r * ldc + c4));
+                __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t*>(dst));
             } else {
-                *reinterpret_cast<uint2*>(C + (long)r * ldc + c4) = v;
+                *reinterpret_cast<uint2*>(dst) = v;
             }
         }
     }
@@ -1271,93 +1279,131 @@ __global__ __launch_bounds__(512) void ffn_rowgemm_dma_kernel(const bf16_t* __re
 #define XMOE_DACT_PF 1
 #endif
         constexpr int PF = XMOE_DACT_PF;   // rounds of G / U fetched ahead
-        uint4 gq[PF + 1][2], uq[PF + 1][2];
-        const int frow = lane >> 2, fchunk = lane & 3;
-        auto fetch = [&](int r, uint4 (&g2)[2], uint4 (&u2)[2]) {
-            const int mi = r >> 1, ni = r & 1;
-            const int r0 = wm * 128 + mi * 32;
-            const int rows_valid = rt.rows - r0;
-            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64 + ni * 32;
+        // Two copies of the rounds.  FULL: every row and column of the wave's 128 x 64 block is valid, and no load or
+        // store stands inside a branch.  That matters for more than the branches: the compiler can only leave memory
+        // operations outstanding at a wait if it knows how many were issued, and with every load and store
+        // conditional it waited for all of them (s_waitcnt vmcnt(0)) before each round's G and U were used - the
+        // round's own stores and the G and U requested ahead for the next round included.
+        const float* sc_base = x_scale ? x_scale + rt.row0 : &kOneF;
+        const int sc_stride = x_scale ? 1 : 0;
+        auto rounds = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            constexpr int NQ = PF + 1;   // buffers of a round's G / U
+            uint4 gq[NQ][2], uq[NQ][2];
+            const int frow = lane >> 2, fchunk = lane & 3;
+            auto fetch = [&](int r, uint4 (&g2)[2], uint4 (&u2)[2]) {
+                const int mi = r >> 1, ni = r & 1;
+                const int r0 = wm * 128 + mi * 32;
+                const int rows_valid = rt.rows - r0;
+                const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64 + ni * 32;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = 16 * i + frow;
-                g2[i] = make_uint4(0, 0, 0, 0);
-                u2[i] = make_uint4(0, 0, 0, 0);
-                if (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid) {
-                    g2[i] = *reinterpret_cast<const uint4*>(G + base + (long)row * N + fchunk * 8);
-                    u2[i] = *reinterpret_cast<const uint4*>(U + base + (long)row * N + fchunk * 8);
+                for (int i = 0; i < 2; ++i) {
+                    const int row = 16 * i + frow;
+                    g2[i] = make_uint4(0, 0, 0, 0);
+                    u2[i] = make_uint4(0, 0, 0, 0);
+                    if (FULL || (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid)) {
+                        // a wave-uniform group of 16 rows plus this lane's fixed 32-bit offset
+                        const uint32_t o = (uint32_t)(frow * N + fchunk * 8) * 2u;
+                        g2[i] = *reinterpret_cast<const uint4*>(
+                            reinterpret_cast<const char*>(G + base + (long)(16 * i) * N) + o);
+                        u2[i] = *reinterpret_cast<const uint4*>(
+                            reinterpret_cast<const char*>(U + base + (long)(16 * i) * N) + o);
+                    }
+                }
+            };
+            // FULL: the four row blocks' scales first, ahead of every other request of the epilogue (requested where
+            // they are used they would be the newest request each time, and waiting for the newest is waiting for
+            // all).  No branch: without scales every lane reads a 1.  Read as global memory: through the selected
+            // pointer it would be a flat load, which the compiler can only wait for by waiting for everything.
+            float scv[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+            if (DY_GATHER && FULL) {
+                typedef const __attribute__((address_space(1))) char* gchar_p;
+                typedef const __attribute__((address_space(1))) float* gfloat_p;
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+                    scv[mi] = *(gfloat_p)((gchar_p)GLB_PTR(sc_base) +
+                                          (uint32_t)((wm * 128 + mi * 32 + m) * sc_stride) * 4u);
+            }
+#pragma unroll
+            for (int r = 0; r < PF; ++r) fetch(r, gq[r], uq[r]);
+            float rowpart = 0.f;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int mi = r >> 1, ni = r & 1;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int row = 16 * i + frow;
+                    const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
+                    *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = gq[r % NQ][i];
+                    *reinterpret_cast<uint4*>(inbuf + 2048 + row * 64 + pos) = uq[r % NQ][i];
+                }
+                if (r + PF < 8) fetch(r + PF, gq[(r + PF) % NQ], uq[(r + PF) % NQ]);
+                strip_sync();
+                const int r0 = wm * 128 + mi * 32;
+                const int rows_valid = rt.rows - r0;
+                const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
+                uint2 gv[4], uv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
+                    const int off = m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5);
+                    gv[q] = *reinterpret_cast<const uint2*>(inbuf + off);
+                    uv[q] = *reinterpret_cast<const uint2*>(inbuf + 2048 + off);
+                }
+                float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
+                if (DY_GATHER && FULL)
+                    sc = scv[mi];
+                else if (DY_GATHER && x_scale && m < rows_valid)
+                    sc = x_scale[rt.row0 + r0 + m];
+                float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row>
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t gw[2] = {gv[q].x, gv[q].y}, uw[2] = {uv[q].x, uv[q].y};
+                    float dg[4], du[4], av[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
+                        const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
+                        const float g = __uint_as_float(gb), u = __uint_as_float(ub);
+                        const float pa = acc[mi][ni][4 * q + j];
+                        const float da = DY_GATHER ? pa * sc : pa;
+                        const float sg = fast_sigmoid(g);
+                        const float sl = g * sg;
+                        const float a1 = sl * u;
+                        dg[j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
+                        du[j] = da * sl;
+                        av[j] = DY_GATHER ? a1 * sc : a1;
+                        part = fmaf(pa, a1, part);
+                    }
+                    strip_put4(strip, ni * 32, q, dg[0], dg[1], dg[2], dg[3]);
+                    strip_put4(strip, 64 + ni * 32, q, du[0], du[1], du[2], du[3]);
+                    strip_put4(strip, 128 + ni * 32, q, av[0], av[1], av[2], av[3]);
+                }
+                {   // the two column halves of the row block, then the lane pair of a row
+                    rowpart = ni == 0 ? part : rowpart + part;
+                    if (ni == 1) {
+                        const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
+                        // (FULL: both lanes of a row hold the same total and both store it)
+                        if (FULL || (lane < 32 && m < rows_valid))
+                            *reinterpret_cast<float*>(
+                                reinterpret_cast<char*>(row_part + (long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0) +
+                                (uint32_t)m * 4u) = tot;
+                    }
+                }
+                if (ni == 1) {   // the row block's 64 columns of each output go out as whole 128-byte lines
+                    strip_sync();
+                    strip_flush<64, false, !FULL, true>(strip, 0, dG + base, N, rows_valid, cols_valid);
+                    __builtin_amdgcn_sched_barrier(0);   // (keeps the staged rows of one output in registers at a time)
+                    strip_flush<64, false, !FULL, true>(strip, 64, dU + base, N, rows_valid, cols_valid);
+                    __builtin_amdgcn_sched_barrier(0);
+                    strip_flush<64, false, !FULL, true>(strip, 128, A + base, N, rows_valid, cols_valid);
+                    strip_sync();
                 }
             }
         };
-#pragma unroll
-        for (int r = 0; r < PF; ++r) fetch(r, gq[r], uq[r]);
-        float rowpart = 0.f;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int mi = r >> 1, ni = r & 1;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = 16 * i + frow;
-                const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
-                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = gq[r % (PF + 1)][i];
-                *reinterpret_cast<uint4*>(inbuf + 2048 + row * 64 + pos) = uq[r % (PF + 1)][i];
-            }
-            if (r + PF < 8) fetch(r + PF, gq[(r + PF) % (PF + 1)], uq[(r + PF) % (PF + 1)]);
-            strip_sync();
-            const int r0 = wm * 128 + mi * 32;
-            const int rows_valid = rt.rows - r0;
-            const long base = (long)(rt.row0 + r0) * N + n0 + wn * 64;
-            uint2 gv[4], uv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
-                const int off = m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5);
-                gv[q] = *reinterpret_cast<const uint2*>(inbuf + off);
-                uv[q] = *reinterpret_cast<const uint2*>(inbuf + 2048 + off);
-            }
-            float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
-            if (DY_GATHER && x_scale && m < rows_valid) sc = x_scale[rt.row0 + r0 + m];
-            float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row>
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t gw[2] = {gv[q].x, gv[q].y}, uw[2] = {uv[q].x, uv[q].y};
-                float dg[4], du[4], av[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t gb = (j & 1) ? (gw[j >> 1] & 0xffff0000u) : (gw[j >> 1] << 16);
-                    const uint32_t ub = (j & 1) ? (uw[j >> 1] & 0xffff0000u) : (uw[j >> 1] << 16);
-                    const float g = __uint_as_float(gb), u = __uint_as_float(ub);
-                    const float pa = acc[mi][ni][4 * q + j];
-                    const float da = DY_GATHER ? pa * sc : pa;
-                    const float sg = fast_sigmoid(g);
-                    const float sl = g * sg;
-                    const float a1 = sl * u;
-                    dg[j] = da * u * (sg * (1.0f + g * (1.0f - sg)));
-                    du[j] = da * sl;
-                    av[j] = DY_GATHER ? a1 * sc : a1;
-                    part = fmaf(pa, a1, part);
-                }
-                strip_put4(strip, ni * 32, q, dg[0], dg[1], dg[2], dg[3]);
-                strip_put4(strip, 64 + ni * 32, q, du[0], du[1], du[2], du[3]);
-                strip_put4(strip, 128 + ni * 32, q, av[0], av[1], av[2], av[3]);
-            }
-            if (row_part) {   // (wave-uniform) the two column halves of the row block, then the lane pair of a row
-                rowpart = ni == 0 ? part : rowpart + part;
-                if (ni == 1) {
-                    const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
-                    if (lane < 32 && m < rows_valid)
-                        row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
-                }
-            }
-            if (ni == 1) {   // the row block's 64 columns of each output go out as whole 128-byte lines
-                strip_sync();
-                strip_flush<64>(strip, 0, dG + base, N, rows_valid, cols_valid);
-                __builtin_amdgcn_sched_barrier(0);   // (keeps the staged rows of one output in registers at a time)
-                strip_flush<64>(strip, 64, dU + base, N, rows_valid, cols_valid);
-                __builtin_amdgcn_sched_barrier(0);
-                strip_flush<64>(strip, 128, A + base, N, rows_valid, cols_valid);
-                strip_sync();
-            }
-        }
+        if (rt.rows - wm * 128 >= 128 && cols_valid >= 64)
+            rounds(std::true_type{});
+        else
+            rounds(std::false_type{});
     }
     }
     clock_note(clk, 1);
