@@ -143,7 +143,7 @@ int xmoe_expert_mlp2_bwd(const void* xd, const int32_t* row_index, const void* h
     a.a_buf = p;
     p += ffn_act_bytes(B, f, dt);
     a.row_grad = dy_row_scale_grad;
-    a.row_part = dy_row_scale_grad ? (float*)p : nullptr;
+    a.row_part = (float*)p;   // always written, as for the SwiGLU expert
     hipStream_t s = (hipStream_t)stream;
     if (mlp2_dma_supported(a)) return mlp2_bwd_dma(a, s);
     return mlp2_bwd_simt(a, s);

@@ -1616,76 +1616,102 @@ __global__ __launch_bounds__(512) void mlp2_dact_dma_kernel(const bf16_t* __rest
         // accumulator layout through a wave-private LDS buffer (rows of 64 bytes, 16-byte chunks XOR-swizzled).
         const int m = lane & 31;
         char* inbuf = smem + 8 * kStripBytes + wave * kInBytes;
-        uint4 hq[2][2];
-        const int frow = lane >> 2, fchunk = lane & 3;
-        auto fetch = [&](int r, uint4 (&h2)[2]) {
-            const int mi = r >> 1, ni = r & 1;
-            const int r0 = wm * 128 + mi * 32;
-            const int rows_valid = rt.rows - r0;
-            const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64 + ni * 32;
+        // two copies of the rounds, as in ffn_rowgemm_dma_kernel: FULL has no branch around any load or store
+        const float* sc_base = dy_scale ? dy_scale + rt.row0 : &kOneF;
+        const int sc_stride = dy_scale ? 1 : 0;
+        auto rounds = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            uint4 hq[2][2];
+            const int frow = lane >> 2, fchunk = lane & 3;
+            auto fetch = [&](int r, uint4 (&h2)[2]) {
+                const int mi = r >> 1, ni = r & 1;
+                const int r0 = wm * 128 + mi * 32;
+                const int rows_valid = rt.rows - r0;
+                const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64 + ni * 32;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = 16 * i + frow;
-                h2[i] = make_uint4(0, 0, 0, 0);
-                if (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid)
-                    h2[i] = *reinterpret_cast<const uint4*>(H + base + (long)row * f + fchunk * 8);
+                for (int i = 0; i < 2; ++i) {
+                    const int row = 16 * i + frow;
+                    h2[i] = make_uint4(0, 0, 0, 0);
+                    if (FULL || (row < rows_valid && ni * 32 + fchunk * 8 < cols_valid)) {
+                        // a wave-uniform group of 16 rows plus this lane's fixed 32-bit offset
+                        const uint32_t o = (uint32_t)(frow * f + fchunk * 8) * 2u;
+                        h2[i] = *reinterpret_cast<const uint4*>(
+                            reinterpret_cast<const char*>(H + base + (long)(16 * i) * f) + o);
+                    }
+                }
+            };
+            float scv[4] = {1.0f, 1.0f, 1.0f, 1.0f};   // FULL: the four row blocks' scales, requested first
+            if (DY_GATHER && FULL) {
+                typedef const __attribute__((address_space(1))) char* gchar_p;
+                typedef const __attribute__((address_space(1))) float* gfloat_p;
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+                    scv[mi] = *(gfloat_p)((gchar_p)GLB_PTR(sc_base) +
+                                          (uint32_t)((wm * 128 + mi * 32 + m) * sc_stride) * 4u);
+            }
+            fetch(0, hq[0]);
+            float rowpart = 0.f;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int mi = r >> 1, ni = r & 1;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int row = 16 * i + frow;
+                    const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
+                    *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = hq[r & 1][i];
+                }
+                if (r + 1 < 8) fetch(r + 1, hq[(r + 1) & 1]);
+                strip_sync();
+                const int r0 = wm * 128 + mi * 32;
+                const int rows_valid = rt.rows - r0;
+                const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64;
+                uint2 hv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
+                    hv[q] = *reinterpret_cast<const uint2*>(inbuf + m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5));
+                float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
+                if (DY_GATHER && FULL)
+                    sc = scv[mi];
+                else if (DY_GATHER && dy_scale && m < rows_valid)
+                    sc = dy_scale[rt.row0 + r0 + m];
+                float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row> (see ffn_rowgemm_dma_kernel)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t hw[2] = {hv[q].x, hv[q].y};
+                    float dh[4], av[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t hb = (j & 1) ? (hw[j >> 1] & 0xffff0000u) : (hw[j >> 1] << 16);
+                        float a_, g_;
+                        act_fast_grad<ACT>(__uint_as_float(hb), a_, g_);
+                        const float pa = acc[mi][ni][4 * q + j];
+                        dh[j] = DY_GATHER ? pa * sc * g_ : pa * g_;
+                        av[j] = DY_GATHER ? a_ * sc : a_;
+                        part = fmaf(pa, a_, part);
+                    }
+                    strip_put4(strip, ni * 32, q, dh[0], dh[1], dh[2], dh[3]);
+                    strip_put4(strip, 64 + ni * 32, q, av[0], av[1], av[2], av[3]);
+                }
+                {
+                    rowpart = ni == 0 ? part : rowpart + part;
+                    if (ni == 1) {
+                        const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
+                        if (FULL || (lane < 32 && m < rows_valid))
+                            row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
+                    }
+                }
+                if (ni == 1) {
+                    strip_sync();
+                    strip_flush<64, false, !FULL, true>(strip, 0, dH + base, f, rows_valid, cols_valid);
+                    strip_flush<64, false, !FULL, true>(strip, 64, A + base, f, rows_valid, cols_valid);
+                    strip_sync();
+                }
             }
         };
-        fetch(0, hq[0]);
-        float rowpart = 0.f;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int mi = r >> 1, ni = r & 1;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int row = 16 * i + frow;
-                const int pos = (fchunk ^ ((row >> 2) & 3)) << 4;
-                *reinterpret_cast<uint4*>(inbuf + row * 64 + pos) = hq[r & 1][i];
-            }
-            if (r + 1 < 8) fetch(r + 1, hq[(r + 1) & 1]);
-            strip_sync();
-            const int r0 = wm * 128 + mi * 32;
-            const int rows_valid = rt.rows - r0;
-            const long base = (long)(rt.row0 + r0) * f + n0 + wn * 64;
-            uint2 hv[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)   // columns 8q + 4*(lane/32) .. +3 of row m: half (lane/32) of chunk q
-                hv[q] = *reinterpret_cast<const uint2*>(inbuf + m * 64 + ((q ^ ((m >> 2) & 3)) << 4) + 8 * (lane >> 5));
-            float sc = 1.0f;   // DY_GATHER: the scale of this lane's row
-            if (DY_GATHER && dy_scale && m < rows_valid) sc = dy_scale[rt.row0 + r0 + m];
-            float part = 0.f;   // this lane's 16 columns of <unscaled dY row, Y row> (see ffn_rowgemm_dma_kernel)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t hw[2] = {hv[q].x, hv[q].y};
-                float dh[4], av[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t hb = (j & 1) ? (hw[j >> 1] & 0xffff0000u) : (hw[j >> 1] << 16);
-                    float a_, g_;
-                    act_fast_grad<ACT>(__uint_as_float(hb), a_, g_);
-                    const float pa = acc[mi][ni][4 * q + j];
-                    dh[j] = DY_GATHER ? pa * sc * g_ : pa * g_;
-                    av[j] = DY_GATHER ? a_ * sc : a_;
-                    part = fmaf(pa, a_, part);
-                }
-                strip_put4(strip, ni * 32, q, dh[0], dh[1], dh[2], dh[3]);
-                strip_put4(strip, 64 + ni * 32, q, av[0], av[1], av[2], av[3]);
-            }
-            if (row_part) {
-                rowpart = ni == 0 ? part : rowpart + part;
-                if (ni == 1) {
-                    const float tot = rowpart + __shfl_xor(rowpart, 32, 64);
-                    if (lane < 32 && m < rows_valid)
-                        row_part[(long)(rt.col * 4 + wn) * row_part_ld + rt.row0 + r0 + m] = tot;
-                }
-            }
-            if (ni == 1) {
-                strip_sync();
-                strip_flush<64>(strip, 0, dH + base, f, rows_valid, cols_valid);
-                strip_flush<64>(strip, 64, A + base, f, rows_valid, cols_valid);
-                strip_sync();
-            }
-        }
+        if (rt.rows - wm * 128 >= 128 && cols_valid >= 64)
+            rounds(std::true_type{});
+        else
+            rounds(std::false_type{});
     }
     clock_note(clk, 1);
 }
